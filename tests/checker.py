@@ -1,0 +1,312 @@
+"""Independent schedule checker (test infrastructure, pure Python/numpy).
+
+It replays a schedule and asserts what the paper and the mathematics fix for ANY valid
+result of the synthesis, whatever the random choices were:
+
+  * every transfer uses a link of the topology between neighbouring NPUs (the paper's
+    deadlock-freedom remark) and its (src, dst) are that link's;
+  * a transfer is sourced from an NPU that already HOLDS the chunk at its start time;
+  * every (destination, chunk) is delivered exactly once and never to the owner;
+  * per link the busy intervals [t, t+cost) are disjoint (one chunk per TEN link);
+  * at the end every NPU holds all chunks (All-Gather postcondition); collective time
+    is the latest arrival;
+  * matching is maximal: after the matching of an event no idle link has a chunk its
+    source holds and its destination neither holds nor is receiving;
+  * transfers start only at event times (0 or an arrival time).
+
+It shares nothing with the oracle or with the HIP path.
+"""
+from __future__ import annotations
+
+from collections import defaultdict
+
+import numpy as np
+
+
+def link_costs_ps(alpha_ps, beta_fs_per_B, chunk_bytes):
+    """alpha + beta*n in integer ps, beta given in fs/B, rounded to nearest (python ints)."""
+    return [int(a) + (int(b) * int(chunk_bytes) + 500) // 1000
+            for a, b in zip(alpha_ps, beta_fs_per_B)]
+
+
+def check_all_gather(n_npus, link_src, link_dst, cost, cpn, xfers, collective_time,
+                     check_maximal=True, t0=0):
+    """xfers: structured array (t_ps, src, dst, chunk, link) of ONE All-Gather pass whose
+    time origin is t0.  Raises AssertionError on the first violated invariant."""
+    N = int(n_npus)
+    C = N * int(cpn)
+    L = len(link_src)
+    t = xfers["t_ps"].astype(object) - t0 if len(xfers) else np.zeros(0, dtype=object)
+    t = [int(x) for x in t]
+    src = xfers["src"].astype(np.int64)
+    dst = xfers["dst"].astype(np.int64)
+    chunk = xfers["chunk"].astype(np.int64)
+    link = xfers["link"].astype(np.int64)
+    n = len(xfers)
+
+    assert n == C * (N - 1), f"expected {C * (N - 1)} transfers, got {n}"
+    # canonical order: (t, link) strictly ascending
+    for i in range(1, n):
+        assert (t[i - 1], link[i - 1]) < (t[i], link[i]), f"records not in (t, link) order at {i}"
+    # links of the topology
+    assert np.all(link < L) and np.all(link >= 0)
+    assert np.array_equal(np.asarray(link_src, dtype=np.int64)[link], src), "src is not the link's source"
+    assert np.array_equal(np.asarray(link_dst, dtype=np.int64)[link], dst), "dst is not the link's destination"
+    assert np.all(chunk < C) and np.all(chunk >= 0)
+
+    arrive = {}  # (npu, chunk) -> arrival time
+    for i in range(N):
+        for j in range(cpn):
+            arrive[(i, i * cpn + j)] = 0
+    order = sorted(range(n), key=lambda i: (t[i], link[i]))
+    last_free = [0] * L
+    # delivery uniqueness + interval disjointness
+    for i in order:
+        key = (int(dst[i]), int(chunk[i]))
+        assert key not in arrive, f"chunk {key[1]} delivered twice to NPU {key[0]} (or to its owner)"
+        arrive[key] = t[i] + cost[link[i]]
+        assert t[i] >= last_free[link[i]], f"link {link[i]} carries two chunks at once at t={t[i]}"
+        last_free[link[i]] = t[i] + cost[link[i]]
+    # source holds the chunk when the transfer starts
+    for i in range(n):
+        key = (int(src[i]), int(chunk[i]))
+        assert key in arrive and arrive[key] <= t[i], \
+            f"transfer {i}: NPU {key[0]} sends chunk {key[1]} at {t[i]} before holding it"
+    assert len(arrive) == N * C, "All-Gather postcondition not met"
+    T = max(arrive.values()) if arrive else 0
+    assert int(collective_time) - t0 == T, f"collective time {collective_time} != last arrival {T}"
+
+    # transfers start only at event times
+    event_times = {0} | set(arrive.values())
+    for i in range(n):
+        assert t[i] in event_times, f"transfer {i} starts at {t[i]}, which is no event time"
+
+    if check_maximal:
+        in_links = defaultdict(list)
+        for l in range(L):
+            in_links[int(link_dst[l])].append(l)
+        by_link = defaultdict(list)
+        for i in range(n):
+            by_link[int(link[i])].append((t[i], t[i] + cost[link[i]]))
+        recv = defaultdict(list)  # npu -> [(match time, arrival time, chunk)]
+        for i in range(n):
+            recv[int(dst[i])].append((t[i], t[i] + cost[link[i]], int(chunk[i])))
+        have = defaultdict(list)
+        for (npu, c), ta in arrive.items():
+            have[npu].append((ta, c))
+        for te in sorted(event_times):
+            if te >= T:
+                continue
+            held = {npu: {c for (ta, c) in have[npu] if ta <= te} for npu in range(N)}
+            for d in range(N):
+                blocked = held[d] | {c for (tm, ta, c) in recv[d] if tm <= te < ta}
+                for l in in_links[d]:
+                    busy = any(a <= te < b for (a, b) in by_link[l])
+                    if busy:
+                        continue
+                    cand = held[int(link_src[l])] - blocked
+                    assert not cand, (f"matching not maximal: at t={te} link {l} "
+                                      f"({link_src[l]}->{d}) is idle but could carry {sorted(cand)[:4]}")
+    return T
+
+
+def check_reduce_scatter(n_npus, link_src, link_dst, cost, cpn, xfers, collective_time):
+    """Invariants of a Reduce-Scatter schedule obtained by reversal: for every chunk the
+    transfers form an in-tree over all NPUs rooted at the owner; an NPU forwards its
+    partial sum of chunk c once, and only after everything sent TO it for c has arrived;
+    links carry one chunk at a time; the collective ends at the last arrival."""
+    N = int(n_npus)
+    C = N * int(cpn)
+    n = len(xfers)
+    assert n == C * (N - 1)
+    t = [int(x) for x in xfers["t_ps"]]
+    src = xfers["src"].astype(np.int64)
+    dst = xfers["dst"].astype(np.int64)
+    chunk = xfers["chunk"].astype(np.int64)
+    link = xfers["link"].astype(np.int64)
+    for i in range(1, n):
+        assert (t[i - 1], link[i - 1]) < (t[i], link[i])
+    assert np.array_equal(np.asarray(link_src, dtype=np.int64)[link], src)
+    assert np.array_equal(np.asarray(link_dst, dtype=np.int64)[link], dst)
+    send_time = {}
+    for i in range(n):
+        key = (int(src[i]), int(chunk[i]))
+        assert key not in send_time, f"NPU {key[0]} sends chunk {key[1]} twice"
+        assert key[0] != key[1] // cpn, "the owner never sends its own chunk in Reduce-Scatter"
+        send_time[key] = t[i]
+    assert len(send_time) == C * (N - 1)
+    for i in range(n):
+        d, c = int(dst[i]), int(chunk[i])
+        ta = t[i] + cost[link[i]]
+        if d != c // cpn:
+            assert ta <= send_time[(d, c)], \
+                f"NPU {d} forwards chunk {c} at {send_time[(d, c)]} before a contribution arrives at {ta}"
+    # every chain ends at the owner: follow parents
+    parent = {(int(src[i]), int(chunk[i])): int(dst[i]) for i in range(n)}
+    for (s, c), d in parent.items():
+        hops = 0
+        cur = s
+        while cur != c // cpn:
+            cur = parent[(cur, c)]
+            hops += 1
+            assert hops <= N
+    last_free = defaultdict(int)
+    for i in sorted(range(n), key=lambda i: (t[i], link[i])):
+        assert t[i] >= last_free[int(link[i])]
+        last_free[int(link[i])] = t[i] + cost[link[i]]
+    T = max(t[i] + cost[link[i]] for i in range(n)) if n else 0
+    assert T == int(collective_time)
+    return T
+
+
+def digest(xfers) -> int:
+    """Sum over records of a 64-bit mix of (t, link, chunk), modulo 2^64 (numpy retyping
+    of the boundary's digest definition, used to cross-check both implementations)."""
+    if len(xfers) == 0:
+        return 0
+    with np.errstate(over="ignore"):
+        t = xfers["t_ps"].astype(np.uint64)
+        lc = (xfers["link"].astype(np.uint64) << np.uint64(32)) | xfers["chunk"].astype(np.uint64)
+        h = t ^ (lc * np.uint64(0x9E3779B97F4A7C15))
+        h ^= h >> np.uint64(33)
+        h *= np.uint64(0xFF51AFD7ED558CCD)
+        h ^= h >> np.uint64(33)
+        h *= np.uint64(0xC4CEB9FE1A85EC53)
+        h ^= h >> np.uint64(33)
+        return int(np.sum(h, dtype=np.uint64))
+
+
+# ------------------------------------------------------------------ lower bounds
+
+def ingress_lower_bound(n_npus, link_dst, cost, cpn):
+    """Bandwidth term of the paper's 'Ideal': NPU d must receive C-cpn chunks over its
+    incoming links; link l can deliver floor(T/cost_l) chunks by time T."""
+    N = int(n_npus)
+    need = N * cpn - cpn
+    best = 0
+    by_d = defaultdict(list)
+    for l, d in enumerate(link_dst):
+        by_d[int(d)].append(int(cost[l]))
+    for d in range(N):
+        cs = by_d[d]
+        if need == 0:
+            continue
+        assert cs, "NPU without incoming link"
+        lo, hi = 0, min(cs) * need
+        while lo < hi:
+            mid = (lo + hi) // 2
+            if sum(mid // c for c in cs) >= need:
+                hi = mid
+            else:
+                lo = mid + 1
+        best = max(best, lo)
+    return best
+
+
+def diameter_lower_bound(n_npus, link_src, link_dst, cost):
+    """Latency term of the paper's 'Ideal': the largest shortest-path cost between two
+    NPUs (Dijkstra from every source)."""
+    import heapq
+    N = int(n_npus)
+    adj = defaultdict(list)
+    for l in range(len(link_src)):
+        adj[int(link_src[l])].append((int(link_dst[l]), int(cost[l])))
+    worst = 0
+    for s in range(N):
+        dist = {s: 0}
+        pq = [(0, s)]
+        while pq:
+            du, u = heapq.heappop(pq)
+            if du > dist.get(u, 1 << 200):
+                continue
+            for v, c in adj[u]:
+                nd = du + c
+                if nd < dist.get(v, 1 << 200):
+                    dist[v] = nd
+                    heapq.heappush(pq, (nd, v))
+        assert len(dist) == N
+        worst = max(worst, max(dist.values()))
+    return worst
+
+
+# ------------------------------------------------------------------ brute force
+
+def optimal_steps_unit(n_npus, edges):
+    """Exact minimum number of spans of an All-Gather (1 chunk per NPU, unit-cost links,
+    one chunk per link per span) by breadth-first search over held-state vectors.
+    Uses only that holding more chunks is never worse, so per destination only the
+    inclusion-maximal receivable sets are expanded."""
+    N = n_npus
+    full = (1 << N) - 1
+    start = tuple(1 << i for i in range(N))
+    goal = tuple(full for _ in range(N))
+    if start == goal:
+        return 0
+    in_nb = defaultdict(list)
+    for (s, d) in edges:
+        in_nb[d].append(s)
+    frontier = {start}
+    seen = {start}
+    steps = 0
+    while frontier:
+        steps += 1
+        nxt = set()
+        for st in frontier:
+            per_dest = []
+            for d in range(N):
+                options = {st[d]}
+                for s in in_nb[d]:
+                    useful = st[s] & ~st[d]
+                    new_opts = set()
+                    for o in options:
+                        new_opts.add(o)
+                        b = useful
+                        while b:
+                            low = b & -b
+                            new_opts.add(o | low)
+                            b ^= low
+                    options = new_opts
+                maximal = [o for o in options if not any((o | p) == p and p != o for p in options)]
+                per_dest.append(maximal)
+            stack = [()]
+            for d in range(N):
+                stack = [pre + (o,) for pre in stack for o in per_dest[d]]
+            for ns in stack:
+                if ns == goal:
+                    return steps
+                if ns not in seen:
+                    seen.add(ns)
+                    nxt.add(ns)
+        frontier = nxt
+        assert steps <= N * N, "unreachable"
+    raise AssertionError("goal not reachable")
+
+
+def strongly_connected_digraphs(n):
+    """All labelled simple digraphs on n nodes that are strongly connected."""
+    pairs = [(i, j) for i in range(n) for j in range(n) if i != j]
+    out = []
+    for mask in range(1 << len(pairs)):
+        edges = [pairs[k] for k in range(len(pairs)) if mask >> k & 1]
+        if _strong(n, edges):
+            out.append(edges)
+    return out
+
+
+def _strong(n, edges):
+    def reach(adj):
+        seen = {0}
+        st = [0]
+        while st:
+            u = st.pop()
+            for v in adj[u]:
+                if v not in seen:
+                    seen.add(v)
+                    st.append(v)
+        return len(seen) == n
+    fw = defaultdict(list)
+    bw = defaultdict(list)
+    for s, d in edges:
+        fw[s].append(d)
+        bw[d].append(s)
+    return reach(fw) and reach(bw)
