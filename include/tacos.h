@@ -1,0 +1,187 @@
+/*
+ * tacos.h -- C ABI of the MI355X-native TACOS collective-algorithm synthesizer.
+ *
+ * The library synthesizes a topology-aware collective algorithm by greedy
+ * link-chunk matching over the Time-Expanded Network (TEN) of the target topology
+ * (TACOS, arXiv 2304.05301: Algorithm 1 "Utilization Maximizing Matching" run once
+ * per time span by Algorithm 2 "End-to-End Synthesis").  All of the synthesis runs
+ * in HIP kernels on the current device (gfx950); the host code of the library only
+ * validates and uploads the inputs, launches, and copies results out.  There is no
+ * CPU fallback: without a usable HIP device every call returns TACOS_E_DEVICE.
+ *
+ * Conventions
+ *   - All pointers in this header are HOST pointers unless a comment says "device".
+ *   - Times are unsigned 64-bit integer picoseconds.  No floating point is used for
+ *     times anywhere, so equal times compare equal.
+ *   - A topology is a directed multigraph in CSR form by source NPU.  The LINK ID of
+ *     a link is its index into col_idx.  Parallel links are allowed (distinct ids);
+ *     self-loops are rejected.
+ *   - Chunk c (0 <= c < n_npus*chunks_per_npu) is owned by NPU c / chunks_per_npu:
+ *     the precondition of All-Gather is that every NPU holds its own chunks, the
+ *     postcondition that every NPU holds all chunks (paper, section "Collective
+ *     Communication Patterns").
+ *
+ * What is computed (the deterministic, link-centric form of the paper's matching):
+ *   cost[l] = alpha[l] + beta[l]*chunk_bytes, rounded to the nearest picosecond
+ *             (alpha-beta model, section "TACOS for Heterogeneous Networks");
+ *   state:    held[n]     chunks that have arrived at NPU n (only these make n a source),
+ *             inflight[n] chunks matched to n and not yet arrived (never re-delivered),
+ *             per link the chunk it carries and the time it becomes free;
+ *   loop (Algorithm 2), starting at t = 0, event = 0:
+ *     1. arrivals: every link whose transfer ends at t delivers its chunk;
+ *     2. if every NPU holds every chunk: collective_time = t, stop;
+ *     3. matching for this span (Algorithm 1): for every destination NPU d, for every
+ *        IDLE incoming link l = (s -> d) in ascending link id:
+ *          cand = held[s] & ~held[d] & ~inflight[d];  p = |cand|;  if p == 0 skip;
+ *          r = word 0 of Philox4x32-10(counter = (l, event, phase, 0),
+ *                                      key = (seed mod 2^32, seed div 2^32));
+ *          the link carries the (r mod p)-th smallest chunk id of cand, from t to
+ *          t + cost[l]  (one chunk per TEN link: section "Representing Collective
+ *          Algorithms using TEN");
+ *     4. t = earliest end of a transfer in flight, event += 1.  Nothing in flight
+ *        while chunks are missing = the topology is not strongly connected.
+ *   phase is 0 for a forward (All-Gather) pass and 1 for the reversed pass of a
+ *   Reduce-Scatter.  Reduce-Scatter = the All-Gather pass on the topology with every
+ *   link reversed (same ids, same costs), then every transfer (t', l, c) of it mapped
+ *   to (T - t' - cost[l], src[l], dst[l], c); All-Reduce = Reduce-Scatter followed by
+ *   All-Gather starting at the Reduce-Scatter's end (paragraph "Collectives with
+ *   Reduction Operations").
+ *
+ * Canonical order of a schedule: ascending (t_ps, link); for All-Reduce all
+ * Reduce-Scatter transfers precede all All-Gather transfers.  (t_ps, link) is unique
+ * inside one pass because a link starts at most one transfer per event.
+ */
+#ifndef TACOS_H
+#define TACOS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TACOS_ALL_GATHER = 0,
+  TACOS_REDUCE_SCATTER = 1,
+  TACOS_ALL_REDUCE = 2
+} tacos_collective_t;
+
+/* Error codes (every entry point that returns int: 0 = success, negative = error). */
+#define TACOS_OK             0
+#define TACOS_E_INVAL       (-1) /* null pointer, N = 0, chunks_per_npu = 0, chunk_bytes = 0,
+                                    malformed row_ptr, col_idx out of range, self-loop, unknown
+                                    collective, N*chunks_per_npu beyond the supported maximum,
+                                    bad window in tacos_result_read                          */
+#define TACOS_E_UNREACHABLE (-2) /* chunks missing and nothing in flight: not strongly connected */
+#define TACOS_E_OVERFLOW    (-3) /* a link cost or a time does not fit 64 bits                 */
+#define TACOS_E_NOMEM       (-4) /* host or device allocation failed                           */
+#define TACOS_E_DEVICE      (-5) /* no HIP device / a HIP call failed (see tacos_last_error)   */
+
+/* Largest supported number of chunks N*chunks_per_npu (one wavefront keeps a
+ * destination's whole "still needed" bitset in registers). */
+#define TACOS_MAX_CHUNKS 65536u
+
+#define TACOS_NO_CHUNK 0xFFFFFFFFu
+
+/* Topology: borrowed, read during the call only. */
+typedef struct {
+  uint32_t        n_npus;        /* N >= 1                                                    */
+  uint32_t        n_links;       /* L, must equal row_ptr[N]                                  */
+  const uint32_t *row_ptr;       /* [N+1] non-decreasing, row_ptr[0] == 0 (CSR by source)     */
+  const uint32_t *col_idx;       /* [L]   destination NPU of link id l                        */
+  const uint64_t *alpha_ps;      /* [L]   link latency, picoseconds                           */
+  const uint64_t *beta_fs_per_B; /* [L]   reciprocal bandwidth, femtoseconds per byte
+                                          (50 GB/s == 20000)                                  */
+} tacos_topology_t;
+
+/* One link-chunk match of the schedule: `chunk` occupies link `link` = (src -> dst)
+ * from t_ps to t_ps + cost[link]. 24 bytes, no padding. */
+typedef struct {
+  uint64_t t_ps;
+  uint32_t src, dst, chunk, link;
+} tacos_xfer_t;
+
+/* Optional knobs; zero-initialise for the defaults. */
+typedef struct {
+  void    *stream;        /* hipStream_t to launch on (NULL = the null stream).  The call
+                             returns after the work on it has completed.                    */
+  uint64_t max_events;    /* 0 = run to completion; > 0 = stop each pass after that many
+                             matching sweeps (the result then covers that prefix only and
+                             collective_time is the time reached)                           */
+  uint32_t time_kernels;  /* != 0: bracket every launch of the matching kernel with HIP
+                             events on `stream` so tacos_result_kernel_ms is available      */
+  uint32_t reserved;
+} tacos_options_t;
+
+typedef struct tacos_result tacos_result_t; /* opaque; owns device and host buffers */
+
+/*
+ * Synthesize `coll` for the topology (steps 1-4 above, on the current HIP device).
+ * On success *out receives a result handle to be released with tacos_result_free.
+ * On error *out is left untouched.  opts may be NULL.
+ */
+int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu,
+                     uint64_t chunk_bytes, tacos_collective_t coll, uint64_t seed,
+                     const tacos_options_t *opts, tacos_result_t **out);
+
+/* Time of the last arrival (All-Reduce: Reduce-Scatter time + All-Gather time). */
+uint64_t tacos_result_collective_time_ps(const tacos_result_t *r);
+/* Number of link-chunk matches in the schedule (all passes). */
+uint64_t tacos_result_num_xfers(const tacos_result_t *r);
+/* Number of matching sweeps (TEN spans expanded), summed over passes. */
+uint64_t tacos_result_num_events(const tacos_result_t *r);
+/* Number of passes (1, or 2 for All-Reduce) and per-pass time / sweeps. */
+uint32_t tacos_result_num_passes(const tacos_result_t *r);
+uint64_t tacos_result_pass_time_ps(const tacos_result_t *r, uint32_t pass);
+uint64_t tacos_result_pass_events(const tacos_result_t *r, uint32_t pass);
+/*
+ * Copies transfers [first, first+count) of the canonical order into host_out
+ * (count * sizeof(tacos_xfer_t) bytes, caller-owned).  Windowed because a large
+ * schedule (1.7e9 transfers for 40,960 NPUs) does not fit host memory at once.
+ * Returns TACOS_E_INVAL if the window exceeds tacos_result_num_xfers.
+ */
+int tacos_result_read(const tacos_result_t *r, uint64_t first, uint64_t count,
+                      tacos_xfer_t *host_out);
+/*
+ * Per-sweep trace of pass `pass`: time of every matching sweep and the number of
+ * matches made in it, n = tacos_result_pass_events entries each (either pointer may
+ * be NULL).  Link utilisation of a sweep = matches / n_links.
+ */
+int tacos_result_event_trace(const tacos_result_t *r, uint32_t pass,
+                             uint64_t *event_time_ps, uint32_t *event_matches);
+/*
+ * Order-independent digest of the schedule: sum modulo 2^64 over all transfers of
+ *   h = t_ps ^ (((link << 32) | chunk) * 0x9E3779B97F4A7C15);
+ *   h ^= h >> 33; h *= 0xFF51AFD7ED558CCD; h ^= h >> 33; h *= 0xC4CEB9FE1A85EC53; h ^= h >> 33.
+ */
+uint64_t tacos_result_digest(const tacos_result_t *r);
+/* Milliseconds spent inside the matching kernel (sum over its launches) and the
+ * number of launches; 0 unless opts->time_kernels was set. */
+double   tacos_result_kernel_ms(const tacos_result_t *r);
+uint64_t tacos_result_kernel_launches(const tacos_result_t *r);
+/* Host wall-clock milliseconds of the whole tacos_synthesize call. */
+double   tacos_result_wall_ms(const tacos_result_t *r);
+/* Bytes of device memory the result holds (schedule tables). */
+uint64_t tacos_result_device_bytes(const tacos_result_t *r);
+void     tacos_result_free(tacos_result_t *r);
+
+/* Text for an error code; tacos_last_error gives the HIP detail of the calling
+ * thread's last TACOS_E_DEVICE / TACOS_E_NOMEM (empty string if none). */
+const char *tacos_strerror(int code);
+const char *tacos_last_error(void);
+
+/*
+ * Step a1 alone: the link costs of the alpha-beta model as the synthesis uses them,
+ * cost_ps[l] = alpha_ps[l] + round(beta_fs_per_B[l] * chunk_bytes / 1000), computed by
+ * the library's device kernel and copied to cost_ps (host, [n_links], caller-owned).
+ * Returns TACOS_E_OVERFLOW if a cost does not fit 64 bits.
+ */
+int tacos_link_costs(const tacos_topology_t *topo, uint64_t chunk_bytes, uint64_t *cost_ps);
+
+/* Library version string. */
+const char *tacos_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TACOS_H */

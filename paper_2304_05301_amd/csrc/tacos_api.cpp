@@ -1,0 +1,586 @@
+// Host side of the C ABI declared in include/tacos.h: input validation, upload, the
+// launch loop over TEN spans, and windowed read-back of the schedule.  Everything the
+// method computes (link costs, arrivals, matching, next-event reduction, schedule
+// statistics) runs in the kernels of tacos_kernels.hip; this file holds no CPU
+// implementation of any of it.
+
+#include "../../include/tacos.h"
+#include "tacos_internal.h"
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+using tacos::Ctl;
+using tacos::PassDev;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+struct HipFail {
+  int code;
+};
+
+void hip_check(hipError_t e, const char *what, const char *file, int line)
+{
+  if (e == hipSuccess) return;
+  char buf[512];
+  std::snprintf(buf, sizeof buf, "%s failed: %s (%s:%d)", what, hipGetErrorString(e), file, line);
+  g_last_error = buf;
+  (void)hipGetLastError();
+  throw HipFail{e == hipErrorOutOfMemory ? TACOS_E_NOMEM : TACOS_E_DEVICE};
+}
+#define HIP_TRY(expr) hip_check((expr), #expr, __FILE__, __LINE__)
+
+// Owning device allocation.
+struct DevBuf {
+  void *p = nullptr;
+  size_t bytes = 0;
+  DevBuf() = default;
+  explicit DevBuf(size_t n) { alloc(n); }
+  DevBuf(const DevBuf &) = delete;
+  DevBuf &operator=(const DevBuf &) = delete;
+  DevBuf(DevBuf &&o) noexcept : p(o.p), bytes(o.bytes) { o.p = nullptr; o.bytes = 0; }
+  DevBuf &operator=(DevBuf &&o) noexcept
+  {
+    if (this != &o) { reset(); p = o.p; bytes = o.bytes; o.p = nullptr; o.bytes = 0; }
+    return *this;
+  }
+  ~DevBuf() { reset(); }
+  void alloc(size_t n)
+  {
+    reset();
+    HIP_TRY(hipMalloc(&p, n ? n : 1));
+    bytes = n;
+  }
+  void reset()
+  {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    bytes = 0;
+  }
+  template <class T> T *as() const { return static_cast<T *>(p); }
+};
+
+struct PinnedCtl {
+  Ctl *p = nullptr;
+  PinnedCtl() { HIP_TRY(hipHostMalloc(reinterpret_cast<void **>(&p), sizeof(Ctl), hipHostMallocDefault)); }
+  ~PinnedCtl() { if (p) (void)hipHostFree(p); }
+};
+
+template <class T> void upload(DevBuf &b, const T *src, size_t n, hipStream_t s)
+{
+  b.alloc(n * sizeof(T));
+  if (n) HIP_TRY(hipMemcpyAsync(b.p, src, n * sizeof(T), hipMemcpyHostToDevice, s));
+}
+
+// Schedule rows are stored in segments so that the number of spans need not be known
+// up front: segment k holds rows [k*rows_per_seg, (k+1)*rows_per_seg) and their times.
+constexpr size_t kSegmentBytes = 256ull << 20;
+
+struct Segment {
+  DevBuf rows;      // uint32 [rows_per_seg][L], chunk carried or TACOS_NO_CHUNK
+  DevBuf row_time;  // uint64 [rows_per_seg], event time of the row
+};
+
+struct Pass {
+  bool reversed = false;
+  uint32_t L = 0;
+  uint32_t rows_per_seg = 1;
+  std::vector<Segment> segs;
+  uint64_t T = 0;         // pass time
+  uint64_t n_events = 0;  // matching sweeps
+  uint64_t n_rows = 0;    // schedule rows that may hold records
+  uint64_t t_off = 0;     // start of the pass inside the collective
+  uint64_t n_xfers = 0;
+  std::vector<uint64_t> row_time;   // [n_rows] by event index
+  std::vector<uint32_t> row_count;  // [n_rows] by event index
+  std::vector<uint64_t> canon_base; // [n_rows+1] prefix of counts in canonical row order
+  // canonical row k is event k of a forward pass, event n_rows-1-k of a reversed one
+  uint64_t event_of(uint64_t k) const { return reversed ? n_rows - 1 - k : k; }
+  uint64_t time_of_event(uint64_t e) const { return reversed ? T - row_time[e] : row_time[e] + t_off; }
+};
+
+}  // namespace
+
+struct tacos_result {
+  int device = 0;
+  uint32_t N = 0, L = 0;
+  std::vector<uint32_t> link_src, link_dst;  // original orientation
+  std::vector<Pass> passes;
+  uint64_t collective_time = 0, n_xfers = 0, n_events = 0, digest = 0;
+  double kernel_ms = 0.0, wall_ms = 0.0;
+  uint64_t kernel_launches = 0;
+  uint64_t device_bytes = 0;
+};
+
+namespace {
+
+struct EventPool {
+  std::vector<hipEvent_t> ev;
+  ~EventPool() { for (auto e : ev) (void)hipEventDestroy(e); }
+  void ensure(size_t n)
+  {
+    while (ev.size() < n) {
+      hipEvent_t e;
+      HIP_TRY(hipEventCreate(&e));
+      ev.push_back(e);
+    }
+  }
+};
+
+// Runs one All-Gather pass over links psrc[l] -> pdst[l] and stores its schedule rows.
+int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
+             const DevBuf &d_cost, uint32_t cpn, uint64_t seed, uint32_t phase, bool reversed,
+             uint64_t max_events, bool time_kernels, hipStream_t stream, tacos_result &res, Pass &pass)
+{
+  const uint32_t C = N * cpn;
+  const uint32_t NP = (C + 8191u) / 8192u;
+  pass.reversed = reversed;
+  pass.L = L;
+  pass.rows_per_seg = (uint32_t)std::max<size_t>(1, std::min<size_t>(kSegmentBytes / ((size_t)L * 4), 1u << 20));
+
+  // incoming links of every NPU in ascending link id (stable counting sort by destination)
+  std::vector<uint32_t> in_ptr(N + 1, 0), in_link(L), in_src(L);
+  for (uint32_t l = 0; l < L; ++l) in_ptr[pdst[l] + 1]++;
+  for (uint32_t d = 0; d < N; ++d) in_ptr[d + 1] += in_ptr[d];
+  {
+    std::vector<uint32_t> fill(in_ptr.begin(), in_ptr.end() - 1);
+    for (uint32_t l = 0; l < L; ++l) {
+      const uint32_t j = fill[pdst[l]]++;
+      in_link[j] = l;
+      in_src[j] = psrc[l];
+    }
+  }
+
+  DevBuf d_in_ptr, d_in_link, d_in_src, d_link_dst, d_held, d_carry, d_free_at, d_ctl;
+  upload(d_in_ptr, in_ptr.data(), in_ptr.size(), stream);
+  upload(d_in_link, in_link.data(), in_link.size(), stream);
+  upload(d_in_src, in_src.data(), in_src.size(), stream);
+  upload(d_link_dst, pdst.data(), pdst.size(), stream);
+  const uint32_t row_words = NP * 128u;
+  d_held.alloc((size_t)N * row_words * 8);
+  d_carry.alloc((size_t)L * 4);
+  d_free_at.alloc((size_t)L * 8);
+  d_ctl.alloc(sizeof(Ctl));
+
+  PassDev p{};
+  p.N = N; p.L = L; p.cpn = cpn; p.NP = NP; p.C = C; p.phase = phase;
+  p.seed_lo = (uint32_t)(seed & 0xFFFFFFFFull); p.seed_hi = (uint32_t)(seed >> 32);
+  p.row_words = row_words; p.reversed = reversed ? 1u : 0u;
+  p.held = d_held.as<unsigned long long>();
+  p.in_ptr = d_in_ptr.as<uint32_t>(); p.in_link = d_in_link.as<uint32_t>();
+  p.in_src = d_in_src.as<uint32_t>(); p.link_dst = d_link_dst.as<uint32_t>();
+  p.cost = d_cost.as<unsigned long long>();
+  p.carry = d_carry.as<uint32_t>(); p.free_at = d_free_at.as<unsigned long long>();
+  p.ctl = d_ctl.as<Ctl>();
+  tacos::launch_init_pass(p, stream);
+  HIP_TRY(hipGetLastError());
+
+  PinnedCtl host_ctl;
+  EventPool pool;
+  auto row_slot = [&](uint64_t e, uint32_t **row, unsigned long long **tslot) {
+    const uint64_t k = e / pass.rows_per_seg;
+    while (pass.segs.size() <= k) {
+      Segment s;
+      s.rows.alloc((size_t)pass.rows_per_seg * L * 4);
+      s.row_time.alloc((size_t)pass.rows_per_seg * 8);
+      res.device_bytes += s.rows.bytes + s.row_time.bytes;
+      pass.segs.push_back(std::move(s));
+    }
+    const uint64_t i = e - k * pass.rows_per_seg;
+    *row = pass.segs[k].rows.as<uint32_t>() + i * L;
+    *tslot = pass.segs[k].row_time.as<unsigned long long>() + i;
+  };
+
+  uint64_t e = 0;
+  uint32_t batch = 8;
+  bool stopped = false;  // prefix run reached max_events
+  for (;;) {
+    size_t n_timed = 0;
+    if (time_kernels) pool.ensure(2 * (size_t)batch);
+    for (uint32_t i = 0; i < batch; ++i) {
+      if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
+      uint32_t *row = nullptr;
+      unsigned long long *tslot = nullptr;
+      row_slot(e, &row, &tslot);
+      tacos::launch_arrive(p, (uint32_t)e, tslot, reversed ? row : nullptr, stream);
+      if (max_events && e >= max_events) { stopped = true; break; }
+      if (time_kernels) HIP_TRY(hipEventRecord(pool.ev[2 * n_timed], stream));
+      tacos::launch_match(p, (uint32_t)e, reversed ? nullptr : row, stream);
+      if (time_kernels) { HIP_TRY(hipEventRecord(pool.ev[2 * n_timed + 1], stream)); n_timed++; }
+      e++;
+    }
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(host_ctl.p, p.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    const bool done = host_ctl.p->done != 0;
+    if (time_kernels) {
+      // launches after the pass ended return at once; count the ones that did work
+      const uint64_t e_first = e - n_timed, e_end = host_ctl.p->n_events;
+      const uint64_t useful = !done ? n_timed : (e_end > e_first ? std::min<uint64_t>(n_timed, e_end - e_first) : 0);
+      for (size_t i = 0; i < n_timed; ++i) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, pool.ev[2 * i], pool.ev[2 * i + 1]));
+        if (i < useful) { res.kernel_ms += ms; res.kernel_launches++; }
+      }
+    }
+    if (done || stopped) break;
+    batch = std::min<uint32_t>(batch * 2, 512);
+  }
+
+  const Ctl &c = *host_ctl.p;
+  if (c.status == tacos::kStUnreachable) return TACOS_E_UNREACHABLE;
+  if (c.status == tacos::kStOverflow) return TACOS_E_OVERFLOW;
+  if (c.done) {
+    pass.T = c.T;
+    pass.n_events = c.n_events;
+  } else {  // prefix run: time reached, sweeps run
+    pass.T = c.next_t[max_events & 1u];
+    pass.n_events = max_events;
+  }
+  pass.n_rows = reversed ? pass.n_events + 1 : pass.n_events;
+  // drop segments past the end (batches run ahead of the terminating span)
+  const uint64_t used_segs = (pass.n_rows + pass.rows_per_seg - 1) / pass.rows_per_seg;
+  while (pass.segs.size() > used_segs) {
+    res.device_bytes -= pass.segs.back().rows.bytes + pass.segs.back().row_time.bytes;
+    pass.segs.pop_back();
+  }
+  return TACOS_OK;
+}
+
+// Epilogue of a pass: event times to the host, per-row match counts and the digest.
+void finish_pass(Pass &pass, uint64_t t_off, uint64_t *digest, hipStream_t stream)
+{
+  pass.t_off = t_off;
+  pass.row_time.assign(pass.n_rows, 0);
+  pass.row_count.assign(pass.n_rows, 0);
+  DevBuf d_digest(8);
+  HIP_TRY(hipMemsetAsync(d_digest.p, 0, 8, stream));
+  const uint64_t t_base = pass.reversed ? pass.T : t_off;
+  for (size_t k = 0; k < pass.segs.size(); ++k) {
+    const uint64_t first = (uint64_t)k * pass.rows_per_seg;
+    const uint32_t n = (uint32_t)std::min<uint64_t>(pass.rows_per_seg, pass.n_rows - first);
+    DevBuf d_count((size_t)n * 4);
+    HIP_TRY(hipMemsetAsync(d_count.p, 0, (size_t)n * 4, stream));
+    tacos::launch_row_stats(pass.segs[k].rows.as<uint32_t>(), n, pass.L,
+                            pass.segs[k].row_time.as<unsigned long long>(), t_base,
+                            pass.reversed ? 1u : 0u, d_count.as<uint32_t>(),
+                            d_digest.as<unsigned long long>(), stream);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(pass.row_time.data() + first, pass.segs[k].row_time.p, (size_t)n * 8,
+                           hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipMemcpyAsync(pass.row_count.data() + first, d_count.p, (size_t)n * 4,
+                           hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+  }
+  uint64_t dg = 0;
+  HIP_TRY(hipMemcpyAsync(&dg, d_digest.p, 8, hipMemcpyDeviceToHost, stream));
+  HIP_TRY(hipStreamSynchronize(stream));
+  *digest += dg;
+  pass.canon_base.assign(pass.n_rows + 1, 0);
+  for (uint64_t k = 0; k < pass.n_rows; ++k)
+    pass.canon_base[k + 1] = pass.canon_base[k] + pass.row_count[pass.event_of(k)];
+  pass.n_xfers = pass.canon_base[pass.n_rows];
+}
+
+int validate(const tacos_topology_t *topo, uint32_t cpn, uint64_t chunk_bytes, int coll)
+{
+  if (!topo || !topo->row_ptr || topo->n_npus == 0 || cpn == 0 || chunk_bytes == 0) return TACOS_E_INVAL;
+  if (coll != TACOS_ALL_GATHER && coll != TACOS_REDUCE_SCATTER && coll != TACOS_ALL_REDUCE) return TACOS_E_INVAL;
+  const uint32_t N = topo->n_npus;
+  if (topo->row_ptr[0] != 0) return TACOS_E_INVAL;
+  for (uint32_t i = 0; i < N; ++i)
+    if (topo->row_ptr[i + 1] < topo->row_ptr[i]) return TACOS_E_INVAL;
+  const uint32_t L = topo->row_ptr[N];
+  if (L != topo->n_links) return TACOS_E_INVAL;
+  if (L && (!topo->col_idx || !topo->alpha_ps || !topo->beta_fs_per_B)) return TACOS_E_INVAL;
+  if ((uint64_t)N * cpn > TACOS_MAX_CHUNKS) return TACOS_E_INVAL;
+  for (uint32_t i = 0; i < N; ++i)
+    for (uint32_t l = topo->row_ptr[i]; l < topo->row_ptr[i + 1]; ++l)
+      if (topo->col_idx[l] >= N || topo->col_idx[l] == i) return TACOS_E_INVAL;
+  return TACOS_OK;
+}
+
+int require_device(int *device)
+{
+  int n = 0;
+  hipError_t e = hipGetDeviceCount(&n);
+  if (e != hipSuccess || n <= 0) {
+    g_last_error = std::string("no HIP device: ") + hipGetErrorString(e);
+    (void)hipGetLastError();
+    return TACOS_E_DEVICE;
+  }
+  e = hipGetDevice(device);
+  if (e != hipSuccess) {
+    g_last_error = std::string("hipGetDevice failed: ") + hipGetErrorString(e);
+    return TACOS_E_DEVICE;
+  }
+  return TACOS_OK;
+}
+
+// a1 on the device; returns the device buffer and, if asked, a host copy.
+int device_costs(const tacos_topology_t *topo, uint64_t chunk_bytes, hipStream_t stream, DevBuf &d_cost,
+                 std::vector<uint64_t> *host_cost)
+{
+  const uint32_t L = topo->n_links;
+  DevBuf d_alpha, d_beta, d_ovf(4);
+  upload(d_alpha, reinterpret_cast<const unsigned long long *>(topo->alpha_ps), L, stream);
+  upload(d_beta, reinterpret_cast<const unsigned long long *>(topo->beta_fs_per_B), L, stream);
+  d_cost.alloc((size_t)L * 8);
+  HIP_TRY(hipMemsetAsync(d_ovf.p, 0, 4, stream));
+  tacos::launch_link_cost(d_alpha.as<unsigned long long>(), d_beta.as<unsigned long long>(), chunk_bytes, L,
+                          d_cost.as<unsigned long long>(), d_ovf.as<uint32_t>(), stream);
+  HIP_TRY(hipGetLastError());
+  uint32_t ovf = 0;
+  HIP_TRY(hipMemcpyAsync(&ovf, d_ovf.p, 4, hipMemcpyDeviceToHost, stream));
+  if (host_cost) {
+    host_cost->resize(L);
+    if (L) HIP_TRY(hipMemcpyAsync(host_cost->data(), d_cost.p, (size_t)L * 8, hipMemcpyDeviceToHost, stream));
+  }
+  HIP_TRY(hipStreamSynchronize(stream));
+  return ovf ? TACOS_E_OVERFLOW : TACOS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint64_t chunk_bytes,
+                     tacos_collective_t coll, uint64_t seed, const tacos_options_t *opts,
+                     tacos_result_t **out)
+{
+  g_last_error.clear();
+  if (!out) return TACOS_E_INVAL;
+  int rc = validate(topo, chunks_per_npu, chunk_bytes, (int)coll);
+  if (rc != TACOS_OK) return rc;
+  const uint64_t max_events = opts ? opts->max_events : 0;
+  if (max_events && coll != TACOS_ALL_GATHER) return TACOS_E_INVAL;
+  const bool time_kernels = opts && opts->time_kernels;
+  hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
+
+  const auto wall0 = std::chrono::steady_clock::now();
+  std::unique_ptr<tacos_result> res(new (std::nothrow) tacos_result);
+  if (!res) return TACOS_E_NOMEM;
+  rc = require_device(&res->device);
+  if (rc != TACOS_OK) return rc;
+
+  const uint32_t N = topo->n_npus, L = topo->n_links;
+  try {
+    res->N = N;
+    res->L = L;
+    res->link_src.resize(L);
+    res->link_dst.assign(topo->col_idx, topo->col_idx + L);
+    for (uint32_t i = 0; i < N; ++i)
+      for (uint32_t l = topo->row_ptr[i]; l < topo->row_ptr[i + 1]; ++l) res->link_src[l] = i;
+
+    const int n_pass = coll == TACOS_ALL_REDUCE ? 2 : 1;
+    if (N == 1) {
+      // a single NPU holds everything at t = 0: no span is expanded
+      for (int i = 0; i < n_pass; ++i) {
+        Pass ps;
+        ps.reversed = (coll != TACOS_ALL_GATHER) && i == 0;
+        ps.canon_base.assign(1, 0);
+        res->passes.push_back(std::move(ps));
+      }
+    } else {
+      if (L == 0) return TACOS_E_UNREACHABLE;
+      DevBuf d_cost;
+      rc = device_costs(topo, chunk_bytes, stream, d_cost, nullptr);
+      if (rc != TACOS_OK) return rc;
+      uint64_t t_off = 0;
+      if (coll == TACOS_REDUCE_SCATTER || coll == TACOS_ALL_REDUCE) {
+        // reversed pass: every link (s -> d) is used as (d -> s), ids and costs unchanged
+        res->passes.emplace_back();
+        rc = run_pass(N, L, res->link_dst, res->link_src, d_cost, chunks_per_npu, seed, 1u, true, 0,
+                      time_kernels, stream, *res, res->passes.back());
+        if (rc != TACOS_OK) return rc;
+        finish_pass(res->passes.back(), 0, &res->digest, stream);
+        t_off = res->passes.back().T;
+      }
+      if (coll == TACOS_ALL_GATHER || coll == TACOS_ALL_REDUCE) {
+        res->passes.emplace_back();
+        rc = run_pass(N, L, res->link_src, res->link_dst, d_cost, chunks_per_npu, seed, 0u, false,
+                      max_events, time_kernels, stream, *res, res->passes.back());
+        if (rc != TACOS_OK) return rc;
+        finish_pass(res->passes.back(), t_off, &res->digest, stream);
+      }
+    }
+    for (const Pass &ps : res->passes) {
+      res->collective_time += ps.T;
+      res->n_events += ps.n_events;
+      res->n_xfers += ps.n_xfers;
+    }
+  } catch (const HipFail &f) {
+    return f.code;
+  } catch (const std::bad_alloc &) {
+    g_last_error = "host allocation failed";
+    return TACOS_E_NOMEM;
+  }
+  res->wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - wall0).count();
+  *out = res.release();
+  return TACOS_OK;
+}
+
+uint64_t tacos_result_collective_time_ps(const tacos_result_t *r) { return r ? r->collective_time : 0; }
+uint64_t tacos_result_num_xfers(const tacos_result_t *r) { return r ? r->n_xfers : 0; }
+uint64_t tacos_result_num_events(const tacos_result_t *r) { return r ? r->n_events : 0; }
+uint32_t tacos_result_num_passes(const tacos_result_t *r) { return r ? (uint32_t)r->passes.size() : 0; }
+uint64_t tacos_result_pass_time_ps(const tacos_result_t *r, uint32_t pass)
+{
+  return (r && pass < r->passes.size()) ? r->passes[pass].T : 0;
+}
+uint64_t tacos_result_pass_events(const tacos_result_t *r, uint32_t pass)
+{
+  return (r && pass < r->passes.size()) ? r->passes[pass].n_events : 0;
+}
+uint64_t tacos_result_digest(const tacos_result_t *r) { return r ? r->digest : 0; }
+double tacos_result_kernel_ms(const tacos_result_t *r) { return r ? r->kernel_ms : 0.0; }
+uint64_t tacos_result_kernel_launches(const tacos_result_t *r) { return r ? r->kernel_launches : 0; }
+double tacos_result_wall_ms(const tacos_result_t *r) { return r ? r->wall_ms : 0.0; }
+uint64_t tacos_result_device_bytes(const tacos_result_t *r) { return r ? r->device_bytes : 0; }
+
+int tacos_result_event_trace(const tacos_result_t *r, uint32_t pass, uint64_t *event_time_ps,
+                             uint32_t *event_matches)
+{
+  if (!r || pass >= r->passes.size()) return TACOS_E_INVAL;
+  const Pass &ps = r->passes[pass];
+  // forward pass: sweeps 0..E-1; reversed pass: its rows are keyed by arrival, sweeps 1..E
+  const uint64_t first = ps.reversed ? 1 : 0;
+  for (uint64_t i = 0; i < ps.n_events; ++i) {
+    if (event_time_ps) event_time_ps[i] = ps.row_time[first + i];
+    if (event_matches) event_matches[i] = ps.row_count[first + i];
+  }
+  return TACOS_OK;
+}
+
+int tacos_result_read(const tacos_result_t *r, uint64_t first, uint64_t count, tacos_xfer_t *host_out)
+{
+  g_last_error.clear();
+  if (!r || (count && !host_out)) return TACOS_E_INVAL;
+  if (first > r->n_xfers || count > r->n_xfers - first) return TACOS_E_INVAL;
+  if (count == 0) return TACOS_OK;
+  try {
+    int prev = 0;
+    HIP_TRY(hipGetDevice(&prev));
+    if (prev != r->device) HIP_TRY(hipSetDevice(r->device));
+    std::vector<uint32_t> stage;
+    uint64_t written = 0;
+    uint64_t pass_base = 0;
+    for (const Pass &ps : r->passes) {
+      const uint64_t lo = std::max(first, pass_base), hi = std::min(first + count, pass_base + ps.n_xfers);
+      if (lo < hi) {
+        const uint64_t lfirst = lo - pass_base, lend = hi - pass_base;
+        // first canonical row holding record lfirst
+        uint64_t k = (uint64_t)(std::upper_bound(ps.canon_base.begin(), ps.canon_base.end(), lfirst) -
+                                ps.canon_base.begin()) - 1;
+        // last canonical row (exclusive) that holds a record below lend
+        const uint64_t k_end = (uint64_t)(std::lower_bound(ps.canon_base.begin(), ps.canon_base.end(), lend) -
+                                          ps.canon_base.begin());
+        const uint64_t block_rows = std::max<uint64_t>(1, (64ull << 20) / ((uint64_t)ps.L * 4));
+        while (k < k_end) {
+          // a block of canonical rows that is contiguous in one segment
+          const uint64_t e = ps.event_of(k);
+          const uint64_t seg = e / ps.rows_per_seg;
+          uint64_t n = std::min(block_rows, k_end - k);
+          uint64_t e_lo;
+          if (!ps.reversed) {
+            n = std::min(n, (seg + 1) * ps.rows_per_seg - e);
+            e_lo = e;
+          } else {
+            n = std::min(n, e - seg * ps.rows_per_seg + 1);
+            e_lo = e - n + 1;
+          }
+          stage.resize((size_t)n * ps.L);
+          HIP_TRY(hipMemcpy(stage.data(),
+                            ps.segs[seg].rows.as<uint32_t>() + (e_lo - seg * ps.rows_per_seg) * ps.L,
+                            (size_t)n * ps.L * 4, hipMemcpyDeviceToHost));
+          for (uint64_t q = 0; q < n; ++q) {
+            const uint64_t kk = k + q, ee = ps.event_of(kk);
+            if (ps.row_count[ee] == 0) continue;
+            const uint32_t *row = stage.data() + (ee - e_lo) * ps.L;
+            const uint64_t t = ps.time_of_event(ee);
+            uint64_t idx = ps.canon_base[kk];
+            for (uint32_t l = 0; l < ps.L && idx < lend; ++l) {
+              const uint32_t c = row[l];
+              if (c == TACOS_NO_CHUNK) continue;
+              if (idx >= lfirst) {
+                tacos_xfer_t &x = host_out[written++];
+                x.t_ps = t; x.src = r->link_src[l]; x.dst = r->link_dst[l]; x.chunk = c; x.link = l;
+              }
+              idx++;
+            }
+          }
+          k += n;
+        }
+      }
+      pass_base += ps.n_xfers;
+    }
+    if (prev != r->device) HIP_TRY(hipSetDevice(prev));
+    if (written != count) { g_last_error = "internal: window size mismatch"; return TACOS_E_DEVICE; }
+  } catch (const HipFail &f) {
+    return f.code;
+  } catch (const std::bad_alloc &) {
+    return TACOS_E_NOMEM;
+  }
+  return TACOS_OK;
+}
+
+void tacos_result_free(tacos_result_t *r)
+{
+  if (!r) return;
+  int prev = 0;
+  const int dev = r->device;
+  const bool have = hipGetDevice(&prev) == hipSuccess;
+  if (have && prev != dev) (void)hipSetDevice(dev);
+  delete r;
+  if (have && prev != dev) (void)hipSetDevice(prev);
+}
+
+int tacos_link_costs(const tacos_topology_t *topo, uint64_t chunk_bytes, uint64_t *cost_ps)
+{
+  g_last_error.clear();
+  if (!topo || chunk_bytes == 0 || (topo->n_links && (!cost_ps || !topo->alpha_ps || !topo->beta_fs_per_B)))
+    return TACOS_E_INVAL;
+  int dev = 0;
+  int rc = require_device(&dev);
+  if (rc != TACOS_OK) return rc;
+  if (topo->n_links == 0) return TACOS_OK;
+  try {
+    DevBuf d_cost;
+    std::vector<uint64_t> host;
+    rc = device_costs(topo, chunk_bytes, nullptr, d_cost, &host);
+    if (rc != TACOS_OK) return rc;
+    std::memcpy(cost_ps, host.data(), host.size() * 8);
+  } catch (const HipFail &f) {
+    return f.code;
+  } catch (const std::bad_alloc &) {
+    return TACOS_E_NOMEM;
+  }
+  return TACOS_OK;
+}
+
+const char *tacos_strerror(int code)
+{
+  switch (code) {
+    case TACOS_OK: return "success";
+    case TACOS_E_INVAL: return "invalid argument";
+    case TACOS_E_UNREACHABLE: return "topology not strongly connected: chunks missing and nothing in flight";
+    case TACOS_E_OVERFLOW: return "a link cost or a time does not fit 64 bits";
+    case TACOS_E_NOMEM: return "out of host or device memory";
+    case TACOS_E_DEVICE: return "no HIP device or a HIP call failed";
+    default: return "unknown error code";
+  }
+}
+
+const char *tacos_last_error(void) { return g_last_error.c_str(); }
+
+const char *tacos_version(void) { return "tacos-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

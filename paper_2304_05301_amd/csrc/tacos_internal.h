@@ -1,0 +1,77 @@
+// Internal interface between the host side of the library (tacos_api.cpp) and its
+// HIP kernels (tacos_kernels.hip).  Not installed; the public ABI is include/tacos.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tacos {
+
+constexpr uint32_t kNone = 0xFFFFFFFFu;
+constexpr uint64_t kInf = 0xFFFFFFFFFFFFFFFFull;
+
+// Status words written by the kernels into Ctl::status (0 = running / fine).
+constexpr uint32_t kStUnreachable = 1;
+constexpr uint32_t kStOverflow = 2;
+
+// Device-resident control block of one pass.  next_t is double-buffered by event
+// parity: the matching kernel of event e min-reduces the end times of all transfers
+// in flight into next_t[(e+1)&1]; the arrival kernel of event e+1 reads it as "now".
+struct Ctl {
+  unsigned long long next_t[2];
+  unsigned long long remaining;  // unsatisfied postconditions (NPU, chunk)
+  unsigned long long T;          // time of the last arrival, valid once done
+  uint32_t done;
+  uint32_t status;
+  uint32_t n_events;             // matching sweeps run, valid once done
+  uint32_t pad;
+};
+
+// HBM layout of the per-NPU held bitsets ("precondition" rows).
+//
+// A row has NP "pieces" of 1 KiB.  In piece i lane j of a wavefront owns the 16 bytes
+// at byte offset i*1024 + j*16, so one global_load_dwordx4 per piece per lane reads the
+// row fully coalesced.  Chunk ids are laid out LANE-MAJOR: lane j owns the 2*NP
+// consecutive 64-bit words [j*2NP, (j+1)*2NP) of the logical bitset, word 2i+s of them
+// sitting in half s of its 16 bytes of piece i.  So ascending chunk id = ascending
+// (lane, piece, half, bit), and one wave prefix sum over per-lane popcounts locates
+// the k-th candidate.  Bits of chunk ids >= C are stored as 1 ("held") in every row so
+// that they never become candidates.
+struct PassDev {
+  uint32_t N, L, cpn, NP;
+  uint32_t C;
+  uint32_t phase;
+  uint32_t seed_lo, seed_hi;
+  uint32_t row_words;              // 64-bit words per row = NP*128
+  uint32_t reversed;               // 1: schedule rows are keyed by ARRIVAL event
+  unsigned long long *held;        // [N][row_words]
+  const uint32_t *in_ptr;          // [N+1]
+  const uint32_t *in_link;         // [L] incoming links of each NPU, ascending link id
+  const uint32_t *in_src;          // [L] their source NPUs (pass orientation)
+  const uint32_t *link_dst;        // [L] destination NPU of link id (pass orientation)
+  const unsigned long long *cost;  // [L]
+  uint32_t *carry;                 // [L] chunk in flight or kNone
+  unsigned long long *free_at;     // [L]
+  Ctl *ctl;
+};
+
+// a1: cost = alpha + round(beta*bytes/1000); *overflow set non-zero if any cost >= 2^64-1
+void launch_link_cost(const unsigned long long *alpha, const unsigned long long *beta,
+                      unsigned long long chunk_bytes, uint32_t L, unsigned long long *cost,
+                      uint32_t *overflow, hipStream_t s);
+// a2: precondition rows, idle links, control block
+void launch_init_pass(const PassDev &p, hipStream_t s);
+// a3 + a8 (consume): arrivals at the event's time; writes event_time_slot and, for a
+// reversed pass, the schedule row of the event
+void launch_arrive(const PassDev &p, uint32_t event, unsigned long long *event_time_slot,
+                   uint32_t *sched_row, hipStream_t s);
+// a4-a8 (produce): termination test, matching for all destinations, min-reduction of
+// the next event time; a forward pass writes the schedule row of the event
+void launch_match(const PassDev &p, uint32_t event, uint32_t *sched_row, hipStream_t s);
+// epilogue: per-row match counts and the schedule digest of a block of rows
+void launch_row_stats(const uint32_t *rows, uint32_t n_rows, uint32_t L,
+                      const unsigned long long *row_time, unsigned long long t_base,
+                      uint32_t reversed, uint32_t *row_count, unsigned long long *digest,
+                      hipStream_t s);
+
+}  // namespace tacos

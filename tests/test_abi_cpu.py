@@ -1,0 +1,92 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol include/tacos.h declares, validates arguments, and refuses to compute without
+a HIP device (there is no CPU fallback in the product path)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2304_05301_amd import binding, topologies as T
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _has_gpu():
+    try:
+        import torch
+        return torch.cuda.is_available()
+    except Exception:
+        return False
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    header = open(os.path.join(ROOT, "include", "tacos.h")).read()
+    declared = set(re.findall(r"\b(tacos_[a-z_0-9]+)\s*\(", header))
+    declared -= {"tacos_xfer_t"}
+    assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert "gfx950" in binding.tacos_version()
+
+
+def test_strerror_texts():
+    lib = binding.load()
+    for code in (0, -1, -2, -3, -4, -5):
+        assert lib.tacos_strerror(code)
+    assert lib.tacos_strerror(-99) == b"unknown error code"
+
+
+def test_invalid_arguments_are_rejected_before_any_device_work():
+    good = T.ring(4)
+
+    def call(topo, cpn=1, cb=1 << 20, coll=0, **kw):
+        return binding.tacos_synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps,
+                                        topo.beta_fs_per_B, cpn, cb, coll, 0, **kw)
+
+    for kw in (dict(cpn=0), dict(cb=0), dict(coll=3)):
+        with pytest.raises(binding.TacosError) as e:
+            call(good, **kw)
+        assert e.value.code == binding.TACOS_E_INVAL
+    # self-loop, destination out of range, decreasing row_ptr, too many chunks
+    loop = T.Topology(2, np.array([0, 1, 2], np.uint32), np.array([0, 0], np.uint32),
+                      np.ones(2, np.uint64), np.ones(2, np.uint64))
+    oob = T.Topology(2, np.array([0, 1, 2], np.uint32), np.array([1, 5], np.uint32),
+                     np.ones(2, np.uint64), np.ones(2, np.uint64))
+    dec = T.Topology(2, np.array([0, 2, 1], np.uint32), np.array([1, 0], np.uint32),
+                     np.ones(2, np.uint64), np.ones(2, np.uint64))
+    for bad in (loop, oob, dec):
+        with pytest.raises(binding.TacosError) as e:
+            call(bad)
+        assert e.value.code == binding.TACOS_E_INVAL
+    with pytest.raises(binding.TacosError) as e:
+        call(good, cpn=binding.TACOS_MAX_CHUNKS // 4 + 1)
+    assert e.value.code == binding.TACOS_E_INVAL
+    # a prefix run is only defined for All-Gather
+    with pytest.raises(binding.TacosError) as e:
+        call(good, coll=T.ALL_REDUCE, max_events=2)
+    assert e.value.code == binding.TACOS_E_INVAL
+
+
+@pytest.mark.skipif(_has_gpu(), reason="checks the no-device behaviour")
+def test_no_device_means_error_not_fallback():
+    topo = T.ring(4)
+    with pytest.raises(binding.TacosError) as e:
+        binding.tacos_synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps,
+                                 topo.beta_fs_per_B, 1, 1 << 20, 0, 0)
+    assert e.value.code == binding.TACOS_E_DEVICE
+    with pytest.raises(binding.TacosError) as e:
+        binding.tacos_link_costs(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps,
+                                 topo.beta_fs_per_B, 1 << 20)
+    assert e.value.code == binding.TACOS_E_DEVICE
+
+
+def test_product_does_not_import_oracle():
+    pkg = os.path.join(ROOT, "paper_2304_05301_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle\b", src, re.M), f
+                assert "tacos_oracle" not in src and "orc_" not in src, f

@@ -1,0 +1,198 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle: bit-exact schedules,
+collective times, event traces and digests on the same seeded inputs."""
+import hashlib
+import json
+import os
+
+import numpy as np
+import pytest
+
+import checker
+import oracle
+from paper_2304_05301_amd import binding, topologies as T
+
+pytestmark = pytest.mark.gpu
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "workloads_oracle.json")
+MiB = 1 << 20
+
+
+@pytest.fixture(scope="module")
+def stream():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a HIP device"
+    torch.cuda.set_device(0)
+    return torch.cuda.current_stream().cuda_stream
+
+
+def gpu(topo, cpn, cb, coll, seed, stream, **kw):
+    return binding.tacos_synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps,
+                                    topo.beta_fs_per_B, cpn, cb, coll, seed, stream=stream, **kw)
+
+
+def cpu(topo, cpn, cb, coll, seed, **kw):
+    return oracle.synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps,
+                             topo.beta_fs_per_B, cpn, cb, coll, seed, **kw)
+
+
+def assert_same(r, ref, name=""):
+    assert r.collective_time_ps == ref.collective_time_ps, name
+    assert r.num_events == ref.n_events, name
+    assert r.num_xfers == ref.n_xfers, name
+    got = r.read()
+    assert got.shape == ref.xfers.shape, name
+    if not np.array_equal(got, ref.xfers):
+        bad = np.nonzero(got != ref.xfers)[0]
+        i = int(bad[0])
+        raise AssertionError(f"{name}: first difference at record {i}: gpu {got[i]} oracle {ref.xfers[i]} "
+                             f"({len(bad)} differ)")
+    assert r.digest == ref.digest, name
+
+
+def test_link_costs_match_alpha_beta_model(stream):
+    """a1: alpha + beta*n in integer ps, against python integers."""
+    rng = np.random.default_rng(0)
+    L = 1000
+    edges = [(0, 1, int(a), int(b)) for a, b in zip(rng.integers(0, 5_000_000, L), rng.integers(0, 80_000, L))]
+    topo = T.from_edge_list(2, edges)
+    for cb in (1, 999, MiB, 4 * MiB, (1 << 40) + 12345):
+        got = binding.tacos_link_costs(2, topo.row_ptr, topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B, cb)
+        want = checker.link_costs_ps(topo.alpha_ps, topo.beta_fs_per_B, cb)
+        assert got.tolist() == want
+    big = T.from_edge_list(2, [(0, 1, 0, (1 << 64) - 1), (1, 0, (1 << 64) - 1, 1000)])
+    with pytest.raises(binding.TacosError) as e:
+        binding.tacos_link_costs(2, big.row_ptr, big.col_idx, big.alpha_ps, big.beta_fs_per_B, 1 << 30)
+    assert e.value.code == binding.TACOS_E_OVERFLOW
+
+
+SMALL = [
+    ("uniring2", lambda: T.ring(2), 1, T.ALL_GATHER),
+    ("uniring13", lambda: T.ring(13), 1, T.ALL_GATHER),
+    ("biring9_cpn3", lambda: T.ring(9, bidirectional=True), 3, T.ALL_GATHER),
+    ("fc16", lambda: T.fully_connected(16), 1, T.ALL_GATHER),
+    ("fc70_indeg_over_64", lambda: T.fully_connected(70), 2, T.ALL_GATHER),
+    ("mesh5x4_cpn7", lambda: T.mesh2d(5, 4), 7, T.ALL_GATHER),
+    ("torus2x3_parallel_links", lambda: T.grid([2, 3], True), 2, T.ALL_GATHER),
+    ("hetero_torus_rs", lambda: T.grid([3, 2, 3], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000]), 2, T.REDUCE_SCATTER),
+    ("hetero_torus_ar", lambda: T.grid([3, 3, 2], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000]), 3, T.ALL_REDUCE),
+    ("random40_ag", lambda: T.random_regular_out(40, 3, seed=7)[0], 2, T.ALL_GATHER),
+    ("random40_ar", lambda: T.random_regular_out(40, 3, seed=7)[0], 1, T.ALL_REDUCE),
+    ("switch12d3_rs", lambda: T.switch_unwound(12, 3), 1, T.REDUCE_SCATTER),
+]
+
+
+@pytest.mark.parametrize("name,mk,cpn,coll", SMALL, ids=[c[0] for c in SMALL])
+@pytest.mark.parametrize("seed", [0, 0xDEADBEEFCAFE])
+def test_small_cases_bit_exact(name, mk, cpn, coll, seed, stream):
+    topo = mk()
+    cb = 192 << 10
+    ref = cpu(topo, cpn, cb, coll, seed)
+    with gpu(topo, cpn, cb, coll, seed, stream) as r:
+        assert_same(r, ref, name)
+        assert r.num_passes == (2 if coll == T.ALL_REDUCE else 1)
+        if coll == T.ALL_GATHER:
+            t, m = r.event_trace(0)
+            assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches)
+
+
+def test_single_npu(stream):
+    topo = T.from_edge_list(1, [])
+    for coll in (T.ALL_GATHER, T.REDUCE_SCATTER, T.ALL_REDUCE):
+        with gpu(topo, 3, MiB, coll, 0, stream) as r:
+            assert (r.collective_time_ps, r.num_events, r.num_xfers, r.digest) == (0, 0, 0, 0)
+            assert len(r.read()) == 0
+
+
+def test_unreachable_is_an_error(stream):
+    topo = T.from_edge_list(3, [(0, 1, 1, 0), (1, 2, 1, 0)])
+    with pytest.raises(binding.TacosError) as e:
+        gpu(topo, 1, 1, T.ALL_GATHER, 0, stream)
+    assert e.value.code == binding.TACOS_E_UNREACHABLE
+    nolinks = T.from_edge_list(2, [])
+    with pytest.raises(binding.TacosError) as e:
+        gpu(nolinks, 1, 1, T.ALL_GATHER, 0, stream)
+    assert e.value.code == binding.TACOS_E_UNREACHABLE
+
+
+def test_time_overflow_is_an_error(stream):
+    # two hops of cost 2^63 each: the second transfer would end beyond 2^64
+    big = (1 << 63)
+    topo = T.from_edge_list(3, [(0, 1, big, 0), (1, 2, big, 0), (2, 0, 1, 0), (1, 0, 1, 0), (2, 1, 1, 0)])
+    with pytest.raises(binding.TacosError) as e:
+        gpu(topo, 1, 1, T.ALL_GATHER, 0, stream)
+    assert e.value.code == binding.TACOS_E_OVERFLOW
+    with pytest.raises(oracle.OracleError) as e2:
+        cpu(topo, 1, 1, T.ALL_GATHER, 0)
+    assert e2.value.code == oracle.E_OVERFLOW
+
+
+@pytest.mark.parametrize("C_npus,cpn", [(128, 65), (96, 171), (64, 1024)])
+def test_several_pieces_and_ragged_tail(C_npus, cpn, stream):
+    """Chunk counts that span 2, 3 and 8 one-KiB pieces per row, the first two with a
+    ragged last word."""
+    topo = T.torus3d(4, 4, C_npus // 16)
+    ref = cpu(topo, cpn, MiB, T.ALL_GATHER, 21, max_events=40)
+    with gpu(topo, cpn, MiB, T.ALL_GATHER, 21, stream, max_events=40) as r:
+        assert_same(r, ref, f"C={C_npus * cpn}")
+
+
+def test_windowed_read_and_errors(stream):
+    topo = T.mesh2d(6, 5)
+    ref = cpu(topo, 2, MiB, T.ALL_REDUCE, 4)
+    with gpu(topo, 2, MiB, T.ALL_REDUCE, 4, stream) as r:
+        n = r.num_xfers
+        for first, count in ((0, 1), (n - 1, 1), (17, 1000), (n // 2 - 50, 100), (0, 0), (n, 0)):
+            assert np.array_equal(r.read(first, count), ref.xfers[first:first + count])
+        with pytest.raises(binding.TacosError) as e:
+            r.read(n - 1, 2)
+        assert e.value.code == binding.TACOS_E_INVAL
+
+
+def _golden():
+    with open(GOLDEN) as f:
+        return json.load(f)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_workloads_1_to_3_bit_exact(idx, stream):
+    w = T.workload(idx)
+    ref = oracle.synthesize_workload(w)
+    g = _golden()[str(idx)]
+    assert ref.collective_time_ps == g["collective_time_ps"] and ref.digest == g["digest"]
+    with binding.synthesize_workload(w, stream=stream) as r:
+        assert_same(r, ref, w.name)
+        for i in range(r.num_passes):
+            assert r.pass_time_ps(i) == g["pass_time_ps"][i] and r.pass_events(i) == g["pass_events"][i]
+
+
+def test_workload_4_against_stored_oracle_result(stream):
+    """Random 1024-NPU topology, 1.05 M spans.  The oracle needs about a minute for it, so
+    the comparison is with the values tests/golden/make_golden.py stored from the oracle:
+    time, spans, records, digest and the SHA-256 of the canonical record array."""
+    w = T.workload(4)
+    g = _golden()["4"]
+    with binding.synthesize_workload(w, stream=stream) as r:
+        assert r.collective_time_ps == g["collective_time_ps"]
+        assert r.num_events == g["n_events"] and r.num_xfers == g["n_xfers"]
+        assert r.digest == g["digest"]
+        got = r.read()
+        assert hashlib.sha256(got.tobytes()).hexdigest() == g["sha256_xfers"]
+
+
+def test_same_seed_same_digest_and_stream_independence(stream):
+    import torch
+    topo = T.torus3d(5, 4, 3)
+    with gpu(topo, 2, MiB, T.ALL_GATHER, 77, stream) as a:
+        side = torch.cuda.Stream()
+        with gpu(topo, 2, MiB, T.ALL_GATHER, 77, side.cuda_stream) as b:
+            assert a.digest == b.digest and a.collective_time_ps == b.collective_time_ps
+            assert np.array_equal(a.read(), b.read())
+        with gpu(topo, 2, MiB, T.ALL_GATHER, 78, stream) as c:
+            assert c.digest != a.digest
+
+
+def test_kernel_timing_is_reported(stream):
+    topo = T.torus3d(6, 6, 4)
+    with gpu(topo, 1, MiB, T.ALL_GATHER, 1, stream, time_kernels=True) as r:
+        assert r.kernel_launches == r.num_events
+        assert 0.0 < r.kernel_ms < r.wall_ms
