@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the TACOS synthesis hot path on one MI355X.
+
+One "step" = one complete synthesis (link costs, precondition init, every TEN span:
+arrivals + matching + next-event reduction, schedule statistics) of the workload through
+the C ABI.  Default workload: All-Gather on the 32x32x40 3D torus (40,960 NPUs, 245,760
+links, 1 chunk of 1 MiB per NPU, seed 4).  Prints ONE JSON line.
+
+  value      = link-chunk matches per second of the whole synthesis call (wall clock,
+               inputs are a few MB of topology arrays uploaded inside the call)
+  roofline   = matching kernel: algorithmic bytes per launch / mean launch duration
+               (HIP events on the launch stream) against the 8 TB/s HBM peak
+  cpu_baseline = the CPU oracle timed on this machine's host cores on a bounded prefix of
+               the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "match_kernel_traffic.json")
+
+
+def algorithmic_bytes(n_matches, n_npus, n_links, n_chunks):
+    """Bytes the word-wise candidate computation must move per match: one held[src] row
+    per matched link plus held[dst] and inflight[dst] once per destination and span,
+    i.e. Wb * (1 + 2 / mean in-degree) with Wb = 8 * ceil(C / 64)."""
+    wb = 8 * ((n_chunks + 63) // 64)
+    deg = n_links / n_npus
+    return n_matches * wb * (1.0 + 2.0 / deg)
+
+
+def cpu_baseline(w, target_s=15.0):
+    import oracle
+    threads = min(oracle.max_threads(), 16)
+    t = w.topo
+
+    def run(n_events):
+        t0 = time.perf_counter()
+        r = oracle.synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B,
+                              w.chunks_per_npu, w.chunk_bytes, w.collective, w.seed,
+                              max_events=n_events, keep_xfers=0, n_threads=threads)
+        return time.perf_counter() - t0, r
+
+    dt, r = run(2)
+    per_event = max(dt / 2, 1e-6)
+    n = int(max(2, min(2000, target_s / per_event)))
+    complete = False
+    if w.collective == 0 and n < 2000:
+        dt, r = run(n)
+        sample = f"first {n} TEN spans of the workload ({r.n_xfers} matches)"
+    else:
+        # small workloads: run the whole thing
+        t0 = time.perf_counter()
+        r = oracle.synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B,
+                              w.chunks_per_npu, w.chunk_bytes, w.collective, w.seed,
+                              keep_xfers=0, n_threads=threads)
+        dt = time.perf_counter() - t0
+        complete = True
+        sample = f"whole workload ({r.n_xfers} matches)"
+    return {"value": r.n_xfers / dt, "unit": "matches/s", "cores": threads, "kind": "oracle",
+            "sample": sample, "seconds": dt, "complete": complete}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", type=int, default=5, help="1..5 (default 5: 40,960-NPU torus)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2304_05301_amd import binding, topologies as T
+
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    w = T.workload(args.workload)
+    topo = w.topo
+    n_chunks = topo.n_npus * w.chunks_per_npu
+
+    def step(timed):
+        r = binding.synthesize_workload(w, stream=stream, time_kernels=timed)
+        out = (r.num_xfers, r.num_events, r.collective_time_ps, r.kernel_ms, r.kernel_launches,
+               r.digest, r.wall_ms)
+        r.free()
+        return out
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    results = [step(True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    n_xfers, n_events, T_ps, _, launches, digest, _ = results[0]
+    assert all(r[0] == n_xfers and r[5] == digest for r in results), "non-deterministic result"
+    ms_per_step = 1e3 * elapsed / args.steps
+    kernel_ms = sum(r[3] for r in results) / args.steps
+    launches = max(1, launches)
+    alg_bytes = algorithmic_bytes(n_xfers, topo.n_npus, topo.n_links, n_chunks)
+    mean_launch_s = kernel_ms * 1e-3 / launches
+    achieved = alg_bytes / launches / mean_launch_s / 1e9 if mean_launch_s > 0 else 0.0
+    traffic = None
+    if os.path.exists(TRAFFIC_FILE):
+        with open(TRAFFIC_FILE) as f:
+            tr = json.load(f)
+        if tr.get("workload") == w.name:
+            traffic = tr.get("hbm_bytes_per_launch")
+
+    line = {
+        "metric": "ten_link_chunk_matches_per_sec",
+        "value": n_xfers / (ms_per_step * 1e-3),
+        "unit": "matches/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64",
+        "data": "synthetic",
+        "config": {"workload": w.name, "topology": topo.name, "n_npus": topo.n_npus,
+                   "n_links": topo.n_links, "chunks": n_chunks, "chunk_bytes": w.chunk_bytes,
+                   "collective": ["all_gather", "reduce_scatter", "all_reduce"][w.collective],
+                   "seed": w.seed},
+        "synthesis_wall_s": ms_per_step * 1e-3,
+        "matches": n_xfers,
+        "ten_spans": n_events,
+        "collective_time_ps": T_ps,
+        "schedule_digest": digest,
+        "match_kernel_ms_per_step": kernel_ms,
+        "match_kernel_launches": launches,
+        "match_kernel_matches_per_s": n_xfers / (kernel_ms * 1e-3) if kernel_ms > 0 else None,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "match_kernel",
+                     "algorithmic_bytes_per_launch": alg_bytes / launches,
+                     "mean_launch_us": mean_launch_s * 1e6},
+        "paper_context": "paper reports wall-clock only: 128-NPU All-Reduce synthesized in 1.08 s, "
+                         "40K-NPU 2D mesh All-Reduce in 2.52 h (Xeon E5-2699v3, 64 threads)",
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

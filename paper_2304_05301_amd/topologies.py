@@ -83,22 +83,21 @@ def from_edge_list(n_npus: int,
     Links are sorted by (src, dst); parallel links keep their generation order
     (the sort is stable)."""
     edges = list(edges)
-    if edges:
-        arr = np.array(edges, dtype=np.int64).reshape(-1, 4)
-    else:
-        arr = np.zeros((0, 4), dtype=np.int64)
-    order = np.lexsort((arr[:, 1], arr[:, 0]))  # stable: primary src, secondary dst
-    arr = arr[order]
-    src = arr[:, 0]
+    src = np.array([e[0] for e in edges], dtype=np.int64)
+    dst = np.array([e[1] for e in edges], dtype=np.int64)
+    alpha = np.array([e[2] for e in edges], dtype=np.uint64)
+    beta = np.array([e[3] for e in edges], dtype=np.uint64)
+    order = np.lexsort((dst, src))  # stable: primary src, secondary dst
+    src, dst, alpha, beta = src[order], dst[order], alpha[order], beta[order]
     counts = np.bincount(src, minlength=n_npus) if len(src) else np.zeros(n_npus, dtype=np.int64)
     row_ptr = np.zeros(n_npus + 1, dtype=np.uint32)
     row_ptr[1:] = np.cumsum(counts)
     return Topology(
         n_npus=int(n_npus),
         row_ptr=row_ptr,
-        col_idx=arr[:, 1].astype(np.uint32),
-        alpha_ps=arr[:, 2].astype(np.uint64),
-        beta_fs_per_B=arr[:, 3].astype(np.uint64),
+        col_idx=dst.astype(np.uint32),
+        alpha_ps=alpha,
+        beta_fs_per_B=beta,
         name=name,
     )
 
