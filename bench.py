@@ -47,8 +47,9 @@ def cpu_baseline(w, target_s=15.0):
                               max_events=n_events, keep_xfers=0, n_threads=threads)
         return time.perf_counter() - t0, r
 
-    dt, r = run(2)
-    per_event = max(dt / 2, 1e-6)
+    dt2, _ = run(2)
+    dt6, r = run(6)
+    per_event = max((dt6 - dt2) / 4, 1e-6)   # set-up time cancels
     n = int(max(2, min(2000, target_s / per_event)))
     complete = False
     if w.collective == 0 and n < 2000:
@@ -74,6 +75,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", type=int, default=5, help="1..5 (default 5: 40,960-NPU torus)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference dispatch for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -99,6 +102,13 @@ def main():
         r.free()
         return out
 
+    if args.calibrate_copy:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        a.fill_(1)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()

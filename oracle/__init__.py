@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.orc_link_cost.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
                                     ctypes.POINTER(ctypes.c_uint64)]
         L.orc_max_threads.restype = ctypes.c_int
+        L.orc_set_progress.restype = None
+        L.orc_set_progress.argtypes = [ctypes.c_uint64]
         _lib = L
     return _lib
 
@@ -112,6 +114,11 @@ def link_cost(alpha_ps: int, beta_fs_per_B: int, chunk_bytes: int):
     out = ctypes.c_uint64(0)
     ok = lib().orc_link_cost(alpha_ps, beta_fs_per_B, chunk_bytes, ctypes.byref(out))
     return int(out.value) if ok else None
+
+
+def set_progress(every: int) -> None:
+    """Print a line on stderr every `every` matching sweeps (0 = silent)."""
+    lib().orc_set_progress(int(every))
 
 
 def max_threads() -> int:

@@ -37,6 +37,7 @@
  * except by those invariants and bounds.
  */
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
@@ -126,6 +127,11 @@ int orc_link_cost(uint64_t alpha_ps, uint64_t beta_fs_per_B, uint64_t chunk_byte
   *cost = (uint64_t)ps;
   return 1;
 }
+
+/* Optional progress lines on stderr every `every` matching sweeps (0 = silent), for
+ * runs that take minutes. */
+static uint64_t g_progress_every = 0;
+void orc_set_progress(uint64_t every) { g_progress_every = every; }
 
 /* ------------------------------------------------------------------- one pass   */
 typedef struct { uint64_t t; uint32_t link, chunk; } pass_rec_t;
@@ -299,6 +305,11 @@ static int ag_pass(uint32_t N, uint32_t L, const uint32_t *psrc, const uint32_t 
       matches++;
     }
     if (!push_event(out, t, matches)) { rc = ORC_E_NOMEM; goto done; }
+    if (g_progress_every && event % g_progress_every == 0) {
+      fprintf(stderr, "[oracle] sweep %llu t=%llu ps matches=%u remaining=%llu\n",
+              (unsigned long long)event, (unsigned long long)t, matches, (unsigned long long)remaining);
+      fflush(stderr);
+    }
 
     /* 4. next span = earliest arrival; nothing in flight and work left = stall */
     uint64_t tn = ORC_INF;

@@ -196,3 +196,41 @@ def test_kernel_timing_is_reported(stream):
     with gpu(topo, 1, MiB, T.ALL_GATHER, 1, stream, time_kernels=True) as r:
         assert r.kernel_launches == r.num_events
         assert 0.0 < r.kernel_ms < r.wall_ms
+
+
+def test_five_piece_rows_full_run(stream):
+    """512 NPUs x 72 chunks = 36,864 chunks: rows of 5 one-KiB pieces like the 40,960-NPU
+    workload, run to completion (18.8 M transfers, ~6.1 k spans) and compared record by
+    record."""
+    topo = T.torus3d(8, 8, 8)
+    cpn = 72
+    ref = cpu(topo, cpn, MiB, T.ALL_GATHER, 31, n_threads=min(16, oracle.max_threads()))
+    with gpu(topo, cpn, MiB, T.ALL_GATHER, 31, stream) as r:
+        assert r.collective_time_ps == ref.collective_time_ps
+        assert r.num_events == ref.n_events and r.num_xfers == ref.n_xfers == 36_864 * 511
+        assert r.digest == ref.digest
+        t, m = r.event_trace(0)
+        assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches)
+        n = r.num_xfers
+        step = 1 << 21
+        for first in range(0, n, step):
+            cnt = min(step, n - first)
+            assert np.array_equal(r.read(first, cnt), ref.xfers[first:first + cnt]), first
+
+
+def test_workload_5_prefix_bit_exact(stream):
+    """40,960-NPU torus in the launch configuration bench.py times: the first 48 TEN spans
+    (11.8 M transfers) record by record.  The complete run is compared by
+    tests/full_size_parity.py (minutes of oracle time)."""
+    w = T.workload(5)
+    n_ev = 48
+    ref = oracle.synthesize_workload(w, max_events=n_ev, n_threads=min(16, oracle.max_threads()))
+    with binding.synthesize_workload(w, stream=stream, max_events=n_ev) as r:
+        assert r.collective_time_ps == ref.collective_time_ps == n_ev * 10_985_760
+        assert r.num_events == n_ev and r.num_xfers == ref.n_xfers
+        assert r.digest == ref.digest
+        n = r.num_xfers
+        step = 1 << 21
+        for first in range(0, n, step):
+            cnt = min(step, n - first)
+            assert np.array_equal(r.read(first, cnt), ref.xfers[first:first + cnt]), first
