@@ -23,7 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "match_kernel_traffic.json")
+PROFILES = os.path.join(ROOT, "profiles")
 
 
 def algorithmic_bytes(n_matches, n_npus, n_links, n_chunks):
@@ -33,6 +33,23 @@ def algorithmic_bytes(n_matches, n_npus, n_links, n_chunks):
     wb = 8 * ((n_chunks + 63) // 64)
     deg = n_links / n_npus
     return n_matches * wb * (1.0 + 2.0 / deg)
+
+
+def measured_traffic(workload_name):
+    """HBM-side bytes per launch of the matching kernel from the committed rocprofv3 --pmc
+    summary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size), or None."""
+    path = os.path.join(PROFILES, f"match_kernel_{workload_name}_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    with open(path) as f:
+        for line in f:
+            if "=" in line and not line.startswith("#"):
+                k, v = line.split("=", 1)
+                vals[k.strip()] = v.strip()
+    if vals.get("workload") != workload_name:
+        return None
+    return float(vals["hbm_bytes_per_launch"])
 
 
 def cpu_baseline(w, target_s=15.0):
@@ -125,12 +142,7 @@ def main():
     alg_bytes = algorithmic_bytes(n_xfers, topo.n_npus, topo.n_links, n_chunks)
     mean_launch_s = kernel_ms * 1e-3 / launches
     achieved = alg_bytes / launches / mean_launch_s / 1e9 if mean_launch_s > 0 else 0.0
-    traffic = None
-    if os.path.exists(TRAFFIC_FILE):
-        with open(TRAFFIC_FILE) as f:
-            tr = json.load(f)
-        if tr.get("workload") == w.name:
-            traffic = tr.get("hbm_bytes_per_launch")
+    traffic = measured_traffic(w.name)
 
     line = {
         "metric": "ten_link_chunk_matches_per_sec",

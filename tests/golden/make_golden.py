@@ -5,6 +5,12 @@ It calls nothing but the input generators and oracle/; the HIP path is never inv
 Stored per workload 1..4: collective time, matching sweeps, records, the schedule
 digest and the SHA-256 of the canonical record array (little-endian structs of
 t_ps:u64, src:u32, dst:u32, chunk:u32, link:u32).  Workload 4 takes about a minute.
+
+    python tests/golden/make_golden.py --with-5 [--threads 8]
+
+additionally runs the 40,960-NPU workload 5 to completion (OpenMP over destinations;
+minutes) and stores its time, sweeps, records, digest and the SHA-256 of the per-sweep
+(time, match count) trace in workload5_oracle.json.  Its 1.68e9 records are not kept.
 """
 import hashlib
 import json
@@ -18,7 +24,32 @@ import oracle  # noqa: E402
 from paper_2304_05301_amd import topologies as T  # noqa: E402
 
 
+def workload5(threads):
+    w = T.workload(5)
+    oracle.set_progress(500)
+    r = oracle.synthesize_workload(w, keep_first=0, keep_xfers=4096, n_threads=threads)
+    trace = hashlib.sha256(r.event_times.tobytes() + r.event_matches.tobytes()).hexdigest()
+    out = {
+        "name": w.name,
+        "topology": w.topo.name,
+        "collective_time_ps": r.collective_time_ps,
+        "n_events": r.n_events,
+        "n_xfers": r.n_xfers,
+        "digest": r.digest,
+        "sha256_event_trace": trace,
+        "sha256_first_4096_xfers": hashlib.sha256(r.xfers.tobytes()).hexdigest(),
+    }
+    print(5, out, flush=True)
+    with open(os.path.join(HERE, "workload5_oracle.json"), "w") as f:
+        json.dump(out, f, indent=1, sort_keys=True)
+        f.write("\n")
+
+
 def main():
+    if "--with-5" in sys.argv:
+        threads = int(sys.argv[sys.argv.index("--threads") + 1]) if "--threads" in sys.argv else 8
+        workload5(threads)
+        return
     out = {}
     for idx in (1, 2, 3, 4):
         w = T.workload(idx)
