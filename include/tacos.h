@@ -108,9 +108,14 @@ typedef struct {
   uint64_t max_events;    /* 0 = run to completion; > 0 = stop each pass after that many
                              matching sweeps (the result then covers that prefix only and
                              collective_time is the time reached)                           */
-  uint32_t time_kernels;  /* != 0: bracket every launch of the matching kernel with HIP
-                             events on `stream` so tacos_result_kernel_ms is available      */
-  uint32_t reserved;
+  uint32_t time_kernels;  /* != 0: bracket every launch of the kernel that does the matching
+                             with HIP events on `stream` so that tacos_result_kernel_ms is
+                             available                                                      */
+  uint32_t launch_mode;   /* 0 = two plain launches per span (arrivals; matching + next-event
+                             reduction), queued in batches: the default and the faster mode
+                             on MI355X.  1 = persistent: one cooperative launch sweeps many
+                             spans with two grid-wide barriers per span; falls back to 0 if
+                             the device cannot launch cooperatively.  Same results.          */
 } tacos_options_t;
 
 typedef struct tacos_result tacos_result_t; /* opaque; owns device and host buffers */
@@ -155,8 +160,9 @@ int tacos_result_event_trace(const tacos_result_t *r, uint32_t pass,
  *   h ^= h >> 33; h *= 0xFF51AFD7ED558CCD; h ^= h >> 33; h *= 0xC4CEB9FE1A85EC53; h ^= h >> 33.
  */
 uint64_t tacos_result_digest(const tacos_result_t *r);
-/* Milliseconds spent inside the matching kernel (sum over its launches) and the
- * number of launches; 0 unless opts->time_kernels was set. */
+/* Milliseconds spent inside the kernel that does the matching (sum over its launches:
+ * the per-span matching kernel, or the persistent sweep kernel in launch_mode 1) and
+ * the number of launches; 0 unless opts->time_kernels was set. */
 double   tacos_result_kernel_ms(const tacos_result_t *r);
 uint64_t tacos_result_kernel_launches(const tacos_result_t *r);
 /* Host wall-clock milliseconds of the whole tacos_synthesize call. */

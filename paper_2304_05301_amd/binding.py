@@ -44,7 +44,7 @@ class _Topology(ctypes.Structure):
 
 class _Options(ctypes.Structure):
     _fields_ = [("stream", ctypes.c_void_p), ("max_events", ctypes.c_uint64),
-                ("time_kernels", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("time_kernels", ctypes.c_uint32), ("launch_mode", ctypes.c_uint32)]
 
 
 class TacosError(RuntimeError):
@@ -198,12 +198,13 @@ class TacosResult:
 
 def tacos_synthesize(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_per_npu,
                      chunk_bytes, collective, seed, stream: int = 0, max_events: int = 0,
-                     time_kernels: bool = False) -> TacosResult:
+                     time_kernels: bool = False, launch_mode: int = 0) -> TacosResult:
     """tacos_synthesize of include/tacos.h.  `stream` is a raw hipStream_t value (for a
     torch stream: torch.cuda.current_stream().cuda_stream); 0 = the null stream."""
     L = load()
     topo, keep = _topology_struct(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B)
-    opts = _Options(ctypes.c_void_p(int(stream) or None), int(max_events), 1 if time_kernels else 0, 0)
+    opts = _Options(ctypes.c_void_p(int(stream) or None), int(max_events), 1 if time_kernels else 0,
+                    int(launch_mode))
     out = ctypes.c_void_p(None)
     rc = L.tacos_synthesize(ctypes.byref(topo), int(chunks_per_npu), int(chunk_bytes),
                             int(collective), int(seed), ctypes.byref(opts), ctypes.byref(out))

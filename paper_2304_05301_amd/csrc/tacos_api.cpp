@@ -135,10 +135,57 @@ struct EventPool {
   }
 };
 
+// Destination processing order: breadth-first clusters of about kClusterSize NPUs.
+// Purely a locality heuristic for the L2 caches; it never changes the result.
+constexpr uint32_t kClusterSize = 512;
+
+std::vector<uint32_t> cluster_order(uint32_t N, uint32_t L, const std::vector<uint32_t> &in_ptr,
+                                    const std::vector<uint32_t> &in_src, const std::vector<uint32_t> &psrc,
+                                    const std::vector<uint32_t> &pdst)
+{
+  std::vector<uint32_t> order;
+  order.reserve(N);
+  // out-neighbour lists (CSR by psrc) next to the in-neighbour lists we already have
+  std::vector<uint32_t> out_ptr(N + 1, 0), out_dst(L);
+  for (uint32_t l = 0; l < L; ++l) out_ptr[psrc[l] + 1]++;
+  for (uint32_t i = 0; i < N; ++i) out_ptr[i + 1] += out_ptr[i];
+  {
+    std::vector<uint32_t> fill(out_ptr.begin(), out_ptr.end() - 1);
+    for (uint32_t l = 0; l < L; ++l) out_dst[fill[psrc[l]]++] = pdst[l];
+  }
+  std::vector<uint8_t> state(N, 0);  // 0 = free, 1 = queued in the current cluster, 2 = placed
+  std::vector<uint32_t> queue;
+  for (uint32_t seed = 0; seed < N; ++seed) {
+    if (state[seed] != 0) continue;
+    queue.clear();
+    queue.push_back(seed);
+    state[seed] = 1;
+    size_t head = 0;
+    uint32_t placed = 0;
+    while (head < queue.size() && placed < kClusterSize) {
+      const uint32_t u = queue[head++];
+      state[u] = 2;
+      order.push_back(u);
+      placed++;
+      for (uint32_t j = in_ptr[u]; j < in_ptr[u + 1]; ++j) {
+        const uint32_t v = in_src[j];
+        if (state[v] == 0) { state[v] = 1; queue.push_back(v); }
+      }
+      for (uint32_t j = out_ptr[u]; j < out_ptr[u + 1]; ++j) {
+        const uint32_t v = out_dst[j];
+        if (state[v] == 0) { state[v] = 1; queue.push_back(v); }
+      }
+    }
+    for (; head < queue.size(); ++head) state[queue[head]] = 0;  // not placed: free again
+  }
+  return order;
+}
+
 // Runs one All-Gather pass over links psrc[l] -> pdst[l] and stores its schedule rows.
 int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
              const DevBuf &d_cost, uint32_t cpn, uint64_t seed, uint32_t phase, bool reversed,
-             uint64_t max_events, bool time_kernels, hipStream_t stream, tacos_result &res, Pass &pass)
+             uint64_t max_events, bool time_kernels, bool persistent, hipStream_t stream,
+             tacos_result &res, Pass &pass)
 {
   const uint32_t C = N * cpn;
   const uint32_t NP = (C + 8191u) / 8192u;
@@ -159,7 +206,13 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
     }
   }
 
-  DevBuf d_in_ptr, d_in_link, d_in_src, d_link_dst, d_held, d_carry, d_free_at, d_ctl;
+  // Processing order of the destinations: clusters grown breadth-first over the
+  // (undirected) topology, so that NPUs that read each other's rows are matched close
+  // together in time and on the same XCD.  Any permutation gives the same schedule.
+  std::vector<uint32_t> order = cluster_order(N, L, in_ptr, in_src, psrc, pdst);
+
+  DevBuf d_in_ptr, d_in_link, d_in_src, d_link_dst, d_held, d_carry, d_free_at, d_ctl, d_order;
+  upload(d_order, order.data(), order.size(), stream);
   upload(d_in_ptr, in_ptr.data(), in_ptr.size(), stream);
   upload(d_in_link, in_link.data(), in_link.size(), stream);
   upload(d_in_src, in_src.data(), in_src.size(), stream);
@@ -177,6 +230,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   p.held = d_held.as<unsigned long long>();
   p.in_ptr = d_in_ptr.as<uint32_t>(); p.in_link = d_in_link.as<uint32_t>();
   p.in_src = d_in_src.as<uint32_t>(); p.link_dst = d_link_dst.as<uint32_t>();
+  p.order = d_order.as<uint32_t>();
   p.cost = d_cost.as<unsigned long long>();
   p.carry = d_carry.as<uint32_t>(); p.free_at = d_free_at.as<unsigned long long>();
   p.ctl = d_ctl.as<Ctl>();
@@ -200,44 +254,92 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   };
 
   uint64_t e = 0;
-  uint32_t batch = 8;
   bool stopped = false;  // prefix run reached max_events
-  for (;;) {
-    size_t n_timed = 0;
-    if (time_kernels) pool.ensure(2 * (size_t)batch);
-    for (uint32_t i = 0; i < batch; ++i) {
+  // Persistent mode (opt-in): one cooperative launch sweeps many spans with grid-wide
+  // barriers in between.  Its grid must be co-resident: a multiple of 8 workgroups (one
+  // slice of the processing order per XCD), no larger than the device can hold.
+  uint32_t grid = 0;
+  if (persistent) {
+    // few workgroups: the barrier costs about 15 ns per workgroup, and every wavefront
+    // walks several destinations per span anyway
+    const uint32_t max_blocks = tacos::sweep_max_blocks(NP) & ~7u;
+    const uint32_t want = 8u * ((((N + 3u) / 4u) + 31u) / 32u);
+    grid = std::min(max_blocks, want);
+  }
+  if (grid >= 8) {
+    for (;;) {
       if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
       uint32_t *row = nullptr;
       unsigned long long *tslot = nullptr;
       row_slot(e, &row, &tslot);
-      tacos::launch_arrive(p, (uint32_t)e, tslot, reversed ? row : nullptr, stream);
-      if (max_events && e >= max_events) { stopped = true; break; }
-      if (time_kernels) HIP_TRY(hipEventRecord(pool.ev[2 * n_timed], stream));
-      tacos::launch_match(p, (uint32_t)e, reversed ? nullptr : row, stream);
-      if (time_kernels) { HIP_TRY(hipEventRecord(pool.ev[2 * n_timed + 1], stream)); n_timed++; }
-      e++;
-    }
-    HIP_TRY(hipGetLastError());
-    HIP_TRY(hipMemcpyAsync(host_ctl.p, p.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, stream));
-    HIP_TRY(hipStreamSynchronize(stream));
-    const bool done = host_ctl.p->done != 0;
-    if (time_kernels) {
-      // launches after the pass ended return at once; count the ones that did work
-      const uint64_t e_first = e - n_timed, e_end = host_ctl.p->n_events;
-      const uint64_t useful = !done ? n_timed : (e_end > e_first ? std::min<uint64_t>(n_timed, e_end - e_first) : 0);
-      for (size_t i = 0; i < n_timed; ++i) {
-        float ms = 0.f;
-        HIP_TRY(hipEventElapsedTime(&ms, pool.ev[2 * i], pool.ev[2 * i + 1]));
-        if (i < useful) { res.kernel_ms += ms; res.kernel_launches++; }
+      // as many spans as the current segment still has rows for
+      const uint64_t seg_end = (e / pass.rows_per_seg + 1) * pass.rows_per_seg;
+      uint64_t n = std::min<uint64_t>(seg_end - e, 0xFFFFFFFEull - e);
+      uint32_t stop_event = 0xFFFFFFFFu;
+      if (max_events && e + n > max_events) { n = max_events - e + 1; stop_event = (uint32_t)max_events; }
+      hipEvent_t ev0 = nullptr, ev1 = nullptr;
+      if (time_kernels) {
+        pool.ensure(2);
+        ev0 = pool.ev[0]; ev1 = pool.ev[1];
+        HIP_TRY(hipEventRecord(ev0, stream));
       }
+      HIP_TRY(tacos::launch_sweep(p, (uint32_t)e, (uint32_t)n, stop_event, row, tslot, grid, stream));
+      if (time_kernels) HIP_TRY(hipEventRecord(ev1, stream));
+      HIP_TRY(hipMemcpyAsync(host_ctl.p, p.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, stream));
+      HIP_TRY(hipStreamSynchronize(stream));
+      if (time_kernels) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, ev0, ev1));
+        res.kernel_ms += ms;
+        res.kernel_launches++;
+      }
+      e += n;
+      if (host_ctl.p->done) break;
+      if (stop_event != 0xFFFFFFFFu) { stopped = true; break; }
     }
-    if (done || stopped) break;
-    batch = std::min<uint32_t>(batch * 2, 512);
+  } else {
+    uint32_t batch = 8;
+    for (;;) {
+      size_t n_timed = 0;
+      if (time_kernels) pool.ensure(2 * (size_t)batch);
+      for (uint32_t i = 0; i < batch; ++i) {
+        if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
+        uint32_t *row = nullptr;
+        unsigned long long *tslot = nullptr;
+        row_slot(e, &row, &tslot);
+        tacos::launch_arrive(p, (uint32_t)e, tslot, reversed ? row : nullptr, stream);
+        if (max_events && e >= max_events) { stopped = true; break; }
+        if (time_kernels) HIP_TRY(hipEventRecord(pool.ev[2 * n_timed], stream));
+        tacos::launch_match(p, (uint32_t)e, reversed ? nullptr : row, stream);
+        if (time_kernels) { HIP_TRY(hipEventRecord(pool.ev[2 * n_timed + 1], stream)); n_timed++; }
+        e++;
+      }
+      HIP_TRY(hipGetLastError());
+      HIP_TRY(hipMemcpyAsync(host_ctl.p, p.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, stream));
+      HIP_TRY(hipStreamSynchronize(stream));
+      const bool done = host_ctl.p->done != 0;
+      if (time_kernels) {
+        // launches after the pass ended return at once; count the ones that did work
+        const uint64_t e_first = e - n_timed, e_end = host_ctl.p->n_events;
+        const uint64_t useful = !done ? n_timed : (e_end > e_first ? std::min<uint64_t>(n_timed, e_end - e_first) : 0);
+        for (size_t i = 0; i < n_timed; ++i) {
+          float ms = 0.f;
+          HIP_TRY(hipEventElapsedTime(&ms, pool.ev[2 * i], pool.ev[2 * i + 1]));
+          if (i < useful) { res.kernel_ms += ms; res.kernel_launches++; }
+        }
+      }
+      if (done || stopped) break;
+      batch = std::min<uint32_t>(batch * 2, 512);
+    }
   }
 
   const Ctl &c = *host_ctl.p;
   if (c.status == tacos::kStUnreachable) return TACOS_E_UNREACHABLE;
   if (c.status == tacos::kStOverflow) return TACOS_E_OVERFLOW;
+  if (c.status == tacos::kStInternal) {
+    g_last_error = "internal: matching produced a chunk id out of range";
+    return TACOS_E_DEVICE;
+  }
   if (c.done) {
     pass.T = c.T;
     pass.n_events = c.n_events;
@@ -363,6 +465,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
   const uint64_t max_events = opts ? opts->max_events : 0;
   if (max_events && coll != TACOS_ALL_GATHER) return TACOS_E_INVAL;
   const bool time_kernels = opts && opts->time_kernels;
+  const bool persistent = opts && opts->launch_mode == 1;
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
 
   const auto wall0 = std::chrono::steady_clock::now();
@@ -399,7 +502,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
         // reversed pass: every link (s -> d) is used as (d -> s), ids and costs unchanged
         res->passes.emplace_back();
         rc = run_pass(N, L, res->link_dst, res->link_src, d_cost, chunks_per_npu, seed, 1u, true, 0,
-                      time_kernels, stream, *res, res->passes.back());
+                      time_kernels, persistent, stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), 0, &res->digest, stream);
         t_off = res->passes.back().T;
@@ -407,7 +510,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       if (coll == TACOS_ALL_GATHER || coll == TACOS_ALL_REDUCE) {
         res->passes.emplace_back();
         rc = run_pass(N, L, res->link_src, res->link_dst, d_cost, chunks_per_npu, seed, 0u, false,
-                      max_events, time_kernels, stream, *res, res->passes.back());
+                      max_events, time_kernels, persistent, stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), t_off, &res->digest, stream);
       }

@@ -13,6 +13,7 @@ constexpr uint64_t kInf = 0xFFFFFFFFFFFFFFFFull;
 // Status words written by the kernels into Ctl::status (0 = running / fine).
 constexpr uint32_t kStUnreachable = 1;
 constexpr uint32_t kStOverflow = 2;
+constexpr uint32_t kStInternal = 3;
 
 // Device-resident control block of one pass.  next_t is double-buffered by event
 // parity: the matching kernel of event e min-reduces the end times of all transfers
@@ -25,6 +26,10 @@ struct Ctl {
   uint32_t status;
   uint32_t n_events;             // matching sweeps run, valid once done
   uint32_t pad;
+  // grid-wide barrier of the persistent sweep kernel: arrivals only ever grow, the
+  // generation is bumped by the last workgroup to arrive
+  unsigned long long bar_count;
+  unsigned long long bar_gen;
 };
 
 // HBM layout of the per-NPU held bitsets ("precondition" rows).
@@ -49,6 +54,7 @@ struct PassDev {
   const uint32_t *in_link;         // [L] incoming links of each NPU, ascending link id
   const uint32_t *in_src;          // [L] their source NPUs (pass orientation)
   const uint32_t *link_dst;        // [L] destination NPU of link id (pass orientation)
+  const uint32_t *order;           // [N] processing order of the destinations (a permutation)
   const unsigned long long *cost;  // [L]
   uint32_t *carry;                 // [L] chunk in flight or kNone
   unsigned long long *free_at;     // [L]
@@ -68,6 +74,18 @@ void launch_arrive(const PassDev &p, uint32_t event, unsigned long long *event_t
 // a4-a8 (produce): termination test, matching for all destinations, min-reduction of
 // the next event time; a forward pass writes the schedule row of the event
 void launch_match(const PassDev &p, uint32_t event, uint32_t *sched_row, hipStream_t s);
+// a3-a8 fused: ONE cooperative launch runs spans [first_event, first_event+n_events)
+// (arrivals, termination test, matching, next-event reduction, with two grid-wide
+// barriers per span) and returns early when the pass ends.  stop_event: the span at
+// which only the arrivals are applied (prefix runs), or 0xFFFFFFFF.  sched_rows and
+// event_times point at the slots of first_event.  grid_blocks must not exceed
+// sweep_max_blocks(NP).  Returns the HIP status of the launch.
+hipError_t launch_sweep(const PassDev &p, uint32_t first_event, uint32_t n_events, uint32_t stop_event,
+                        uint32_t *sched_rows, unsigned long long *event_times, uint32_t grid_blocks,
+                        hipStream_t s);
+// largest co-resident grid (in workgroups of 256 threads) of the sweep kernel on the
+// current device, 0 if cooperative launches are not available
+uint32_t sweep_max_blocks(uint32_t NP);
 // epilogue: per-row match counts and the schedule digest of a block of rows
 void launch_row_stats(const uint32_t *rows, uint32_t n_rows, uint32_t L,
                       const unsigned long long *row_time, unsigned long long t_base,

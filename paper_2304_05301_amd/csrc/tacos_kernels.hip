@@ -13,6 +13,8 @@
 
 #include "tacos_internal.h"
 
+#include <type_traits>
+
 namespace tacos {
 
 namespace {
@@ -29,20 +31,17 @@ __device__ __forceinline__ u32 read_lane(u32 v, u32 lane)
   return (u32)__builtin_amdgcn_readlane((int)v, (int)lane);
 }
 
-__device__ __forceinline__ u64 read_lane64(u64 v, u32 lane)
+// Inclusive prefix sum over the 64 lanes of a wavefront with DPP adds: a Hillis-Steele
+// scan inside each row of 16 lanes (row_shr 1,2,4,8, zero fill), then lane 15 of rows 0/2
+// is added to rows 1/3 (row_bcast:15) and lane 31 to rows 2 and 3 (row_bcast:31).
+__device__ __forceinline__ u32 wave_inclusive_scan(u32 v)
 {
-  u32 lo = read_lane((u32)v, lane), hi = read_lane((u32)(v >> 32), lane);
-  return ((u64)hi << 32) | lo;
-}
-
-// Inclusive prefix sum over the 64 lanes of a wavefront.
-__device__ __forceinline__ u32 wave_inclusive_scan(u32 v, int lane)
-{
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    u32 o = (u32)__shfl_up((int)v, off, 64);
-    if (lane >= off) v += o;
-  }
+  v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);
+  v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true);
+  v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);
+  v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);
+  v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);
+  v += (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);
   return v;
 }
 
@@ -56,20 +55,6 @@ __device__ __forceinline__ u64 wave_min64(u64 v)
     v = o < v ? o : v;
   }
   return v;
-}
-
-// Position of the k-th (0-based) set bit of w, k < popcount(w): binary search on the
-// popcounts of the low halves.
-__device__ __forceinline__ u32 kth_set_bit(u64 w, u32 k)
-{
-  u32 pos = 0;
-#pragma unroll
-  for (u32 s = 32; s >= 1; s >>= 1) {
-    u64 low = (w >> pos) & ((1ull << s) - 1ull);
-    u32 pc = (u32)__popcll(low);
-    if (k >= pc) { k -= pc; pos += s; }
-  }
-  return pos;
 }
 
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), word 0 of the output block.
@@ -166,10 +151,27 @@ __global__ void init_links_kernel(PassDev p)
     c->status = 0u;
     c->n_events = 0u;
     c->pad = 0u;
+    c->bar_count = 0ull;
+    c->bar_gen = 0ull;
   }
 }
 
 // ---------------------------------------------------------------- a3: arrivals
+
+// a3 for one link: a transfer that ends at t delivers its chunk to the link's
+// destination.  Returns whether it did.
+__device__ __forceinline__ bool arrive_link(const PassDev &p, u32 l, u64 t, u32 *__restrict__ sched_row)
+{
+  const u32 c = p.carry[l];
+  const bool arrived = (c != kNone) && (p.free_at[l] == t);
+  if (arrived) {
+    const u32 d = p.link_dst[l];
+    atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
+    p.carry[l] = kNone;
+  }
+  if (sched_row) sched_row[l] = arrived ? c : kNone;
+  return arrived;
+}
 
 __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *event_time_slot,
                                                      u32 *__restrict__ sched_row)
@@ -187,17 +189,7 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
     }
   }
   if (t == kInf) return;
-  bool arrived = false;
-  if (l < p.L) {
-    const u32 c = p.carry[l];
-    arrived = (c != kNone) && (p.free_at[l] == t);
-    if (arrived) {
-      const u32 d = p.link_dst[l];
-      atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
-      p.carry[l] = kNone;
-    }
-    if (sched_row) sched_row[l] = arrived ? c : kNone;
-  }
+  const bool arrived = l < p.L && arrive_link(p, l, t, sched_row);
   const u32 n = (u32)__popcll(__ballot(arrived));
   __shared__ u32 block_n;
   if (threadIdx.x == 0) block_n = 0;
@@ -209,136 +201,228 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
 
 // ---------------------------------------------------------------- a4-a8: matching
 
-template <int NW>
-__device__ __forceinline__ void clear_chunk(u64 (&need)[NW], u32 c, int lane)
+// A lane's share of a bitset row (NDW dwords) held in native vector registers, so that
+// the compiler can index it with a wave-uniform register index (s_set_gpr_idx) instead
+// of a chain of selects or branches.  Indexable vectors come in 4/8/16/32 dwords; a row
+// of more than 16 dwords that is not 32 is split into a 16-dword part and a remainder
+// so that no registers are wasted on padding.
+template <int N> struct VecOf {
+  typedef u32 type __attribute__((ext_vector_type(N <= 4 ? 4 : N <= 8 ? 8 : N <= 16 ? 16 : 32)));
+};
+// (Two separate vector variables rather than one struct: a struct of two vectors that
+// is indexed dynamically ends up in scratch memory.)
+template <int NDW> struct RowRegs {
+  static constexpr bool kSplit = NDW > 16 && NDW < 32;
+  static constexpr int kA = kSplit ? 16 : NDW;
+  static constexpr int kB = kSplit ? NDW - 16 : 4;  // B is unused unless split
+  typedef typename VecOf<kA>::type A;
+  typedef typename VecOf<kB>::type B;
+  static constexpr u32 kMaskB = sizeof(B) / 4 - 1;
+  template <int I> static __device__ __forceinline__ u32 get(const A &a, const B &b)
+  {
+    if constexpr (!kSplit || I < 16) return a[I];
+    else return b[I - 16];
+  }
+  template <int I> static __device__ __forceinline__ void set(A &a, B &b, u32 x)
+  {
+    if constexpr (!kSplit || I < 16) a[I] = x;
+    else b[I - 16] = x;
+  }
+  // i is wave-uniform: both parts are indexed and the scalar condition picks one
+  static __device__ __forceinline__ u32 at(const A &a, const B &b, u32 i)
+  {
+    if constexpr (!kSplit) return a[i];
+    else {
+      const u32 x = a[i & 15u], y = b[(i - 16u) & kMaskB];
+      return i < 16u ? x : y;
+    }
+  }
+  static __device__ __forceinline__ void put(A &a, B &b, u32 i, u32 v)
+  {
+    if constexpr (!kSplit) a[i] = v;
+    else {
+      const u32 il = i & 15u, ih = (i - 16u) & kMaskB;
+      const u32 x = a[il], y = b[ih];
+      a[il] = i < 16u ? v : x;
+      b[ih] = i < 16u ? y : v;
+    }
+  }
+};
+
+// compile-time loop over the dword indices of a row
+template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&f)
 {
-  // c is wave-uniform; lane-major layout: word w = c>>6 lives in lane w/NW at index w%NW
-  const u32 w = c >> 6;
-  const u32 ln = w / (u32)NW;
-  const u32 idx = w - ln * (u32)NW;
-  const u64 m = ~(1ull << (c & 63u));
-#pragma unroll
-  for (int i = 0; i < NW; ++i)
-    if ((u32)i == idx && (u32)lane == ln) need[i] &= m;
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
 }
 
-template <int NP>
-__global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
+// popcount(x) + acc in one VALU instruction (v_bcnt accumulates); written as asm so that
+// the running count stays a dependent chain whose partial sums are the in-lane prefixes.
+__device__ __forceinline__ u32 popc_acc(u32 x, u32 acc)
 {
-  constexpr int NW = 2 * NP;  // 64-bit words of a row held by one lane
-  const int lane = threadIdx.x & 63;
-  const u32 d = uniform(blockIdx.x * 4u + (threadIdx.x >> 6));
-  if (d >= p.N) return;
+  u32 r;
+  asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(acc));
+  return r;
+}
+
+// Position of the k-th (0-based) set bit of the wave-uniform word (hi:lo): lane i of
+// the wavefront computes the rank of bit i with v_mbcnt, the lane whose bit is set and
+// whose rank equals k is the answer.
+__device__ __forceinline__ u32 kth_set_bit_wave(u32 lo, u32 hi, u32 k)
+{
+  const u32 rank = __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
+  const u64 hit = __ballot(rank == k) & (((u64)hi << 32) | lo);
+  return (u32)__ffsll((long long)hit) - 1u;
+}
+
+// Remove chunk c (wave-uniform) from a lane-major register row: 64-bit word w = c>>6
+// lives in lane w/NW, its dword (c>>5)&1 at vector index 2*(w%NW) + ((c>>5)&1).
+template <int NW, class RT>
+__device__ __forceinline__ void clear_chunk(typename RT::A &na, typename RT::B &nb, u32 c, int lane)
+{
+  const u32 w = c >> 6;
+  const u32 ln = w / (u32)NW;
+  const u32 dw = (w - ln * (u32)NW) * 2u + ((c >> 5) & 1u);
+  const u32 old = RT::at(na, nb, dw);
+  RT::put(na, nb, dw, ((u32)lane == ln) ? (old & ~(1u << (c & 31u))) : old);
+}
+
+// Algorithm 1 for ONE destination d at TEN span `event` (time t), run by one wavefront.
+// Returns (per lane) the earliest end time among the transfers in flight on the links
+// this lane looked at; the caller min-reduces it.
+template <int NP>
+__device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 event, u64 t,
+                                                 u32 *__restrict__ sched_row, int lane)
+{
+  constexpr int NW = 2 * NP;   // 64-bit words of a row held by one lane
+  constexpr int NDW = 4 * NP;  // dwords
+  typedef RowRegs<NDW> RT;
   Ctl *ctl = p.ctl;
-  if (ctl->done) return;
-  const u64 rem = ctl->remaining;
-  const u64 t = ctl->next_t[event & 1u];
-  if (rem == 0) {  // every postcondition satisfied: the collective ends now
-    if (d == 0 && lane == 0) { ctl->T = t; ctl->n_events = event; ctl->done = 1u; }
-    return;
-  }
-
   const u32 jb = p.in_ptr[d], je = p.in_ptr[d + 1];
-  const u32 k0 = p.seed_lo, k1 = p.seed_hi;
-
-  // pass 1 over the incoming links: is any idle?  earliest end among the busy ones
   u64 my_min = kInf;
-  bool any_idle = false;
-  for (u32 base = jb; base < je; base += 64) {
+
+  // incoming links of d, one per lane (batches of 64 for in-degree > 64)
+  u32 l0 = 0, s0 = 0, cr0 = kNone;
+  u64 cs0 = 0;
+  if (jb + lane < je) {
+    l0 = p.in_link[jb + lane]; s0 = p.in_src[jb + lane];
+    cr0 = p.carry[l0]; cs0 = p.cost[l0];
+  }
+  bool any_idle = __ballot(jb + lane < je && cr0 == kNone) != 0ull;
+  for (u32 base = jb + 64; base < je && !any_idle; base += 64) {
     const u32 j = base + lane;
-    bool idle = false;
-    if (j < je) {
-      const u32 l = p.in_link[j];
-      const u32 cr = p.carry[l];
-      idle = cr == kNone;
-      if (!idle) { const u64 fa = p.free_at[l]; my_min = fa < my_min ? fa : my_min; }
-    }
-    any_idle |= __ballot(idle) != 0ull;
+    any_idle = __ballot(j < je && p.carry[p.in_link[j < je ? j : jb]] == kNone) != 0ull;
   }
 
-  u64 need[NW];
+  typename RT::A need_a;
+  typename RT::B need_b;
   bool need_any = false;
   if (any_idle) {
     // need = ~held[d] & ~inflight[d]; inflight[d] = the chunks on d's busy incoming links
     const uint4 *hp = reinterpret_cast<const uint4 *>(p.held + (u64)d * p.row_words) + lane;
-#pragma unroll
-    for (int i = 0; i < NP; ++i) {
+    static_for<0, NP>([&](auto I) {
+      constexpr int i = decltype(I)::value;
       const uint4 v = hp[i * 64];
-      need[2 * i] = ~(((u64)v.y << 32) | v.x);
-      need[2 * i + 1] = ~(((u64)v.w << 32) | v.z);
-    }
+      RT::template set<4 * i>(need_a, need_b, ~v.x); RT::template set<4 * i + 1>(need_a, need_b, ~v.y);
+      RT::template set<4 * i + 2>(need_a, need_b, ~v.z); RT::template set<4 * i + 3>(need_a, need_b, ~v.w);
+    });
     for (u32 base = jb; base < je; base += 64) {
       const u32 j = base + lane;
       u32 cr = kNone;
-      if (j < je) cr = p.carry[p.in_link[j]];
+      if (base == jb) cr = cr0;
+      else if (j < je) cr = p.carry[p.in_link[j]];
       u64 busy = __ballot(cr != kNone);
       while (busy) {
         const u32 b = (u32)__ffsll((long long)busy) - 1u;
         busy &= busy - 1ull;
-        clear_chunk<NW>(need, read_lane(cr, b), lane);
+        clear_chunk<NW, RT>(need_a, need_b, read_lane(cr, b), lane);
       }
     }
-    u64 acc = 0;
-#pragma unroll
-    for (int i = 0; i < NW; ++i) acc |= need[i];
-    need_any = __ballot(acc != 0ull) != 0ull;
+    u32 acc = 0;
+    static_for<0, NDW>([&](auto I) { acc |= RT::template get<decltype(I)::value>(need_a, need_b); });
+    need_any = __ballot(acc != 0u) != 0ull;
   }
 
   for (u32 base = jb; base < je; base += 64) {
     const u32 j = base + lane;
     const bool valid = j < je;
-    u32 l = 0, s = 0, cr = kNone;
-    u64 cs = 0;
-    if (valid) { l = p.in_link[j]; s = p.in_src[j]; cr = p.carry[l]; cs = p.cost[l]; }
+    u32 l = l0, s = s0, cr = cr0;
+    u64 cs = cs0;
+    if (base != jb) {
+      l = 0; s = 0; cr = kNone; cs = 0;
+      if (valid) { l = p.in_link[j]; s = p.in_src[j]; cr = p.carry[l]; cs = p.cost[l]; }
+    }
     u32 res = kNone;  // chunk matched to this lane's link in this span
     if (need_any) {
       u64 idle = __ballot(valid && cr == kNone);
-      const u32 r = philox4x32_10_word0(l, event, p.phase, 0u, k0, k1);
+      const u32 r = philox4x32_10_word0(l, event, p.phase, 0u, p.seed_lo, p.seed_hi);
       while (idle) {
         const u32 b = (u32)__ffsll((long long)idle) - 1u;
         idle &= idle - 1ull;
         const u32 src = read_lane(s, b);
-        // cand = held[src] & need
         const uint4 *sp = reinterpret_cast<const uint4 *>(p.held + (u64)src * p.row_words) + lane;
-        u64 cand[NW];
+        uint4 row[NP];
+#pragma unroll
+        for (int i = 0; i < NP; ++i) row[i] = sp[i * 64];
+        // cand = held[src] & need, with the running in-lane candidate count after each
+        // 64-bit word (pre[i] = candidates in words 0..i of this lane)
+        typename RT::A cand_a;
+        typename RT::B cand_b;
+        u32 pre[NW];
         u32 cnt = 0;
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-          const uint4 v = sp[i * 64];
-          cand[2 * i] = (((u64)v.y << 32) | v.x) & need[2 * i];
-          cand[2 * i + 1] = (((u64)v.w << 32) | v.z) & need[2 * i + 1];
-          cnt += (u32)__popcll(cand[2 * i]) + (u32)__popcll(cand[2 * i + 1]);
-        }
-        const u32 incl = wave_inclusive_scan(cnt, lane);
+        static_for<0, NP>([&](auto I) {
+          constexpr int i = decltype(I)::value;
+          const u32 c0 = row[i].x & RT::template get<4 * i>(need_a, need_b);
+          const u32 c1 = row[i].y & RT::template get<4 * i + 1>(need_a, need_b);
+          const u32 c2 = row[i].z & RT::template get<4 * i + 2>(need_a, need_b);
+          const u32 c3 = row[i].w & RT::template get<4 * i + 3>(need_a, need_b);
+          RT::template set<4 * i>(cand_a, cand_b, c0); RT::template set<4 * i + 1>(cand_a, cand_b, c1);
+          RT::template set<4 * i + 2>(cand_a, cand_b, c2); RT::template set<4 * i + 3>(cand_a, cand_b, c3);
+          cnt = popc_acc(c0, cnt);
+          cnt = popc_acc(c1, cnt);
+          pre[2 * i] = cnt;
+          cnt = popc_acc(c2, cnt);
+          cnt = popc_acc(c3, cnt);
+          pre[2 * i + 1] = cnt;
+        });
+        const u32 incl = wave_inclusive_scan(cnt);
         const u32 pop = read_lane(incl, 63);
-        if (pop == 0) continue;  // nothing this link could carry: no draw is consumed
-        u32 k = read_lane(r, b) % pop;
-        // owning lane = first lane whose inclusive count exceeds k
-        const u64 above = __ballot(incl > k);
-        const u32 ln = (u32)__ffsll((long long)above) - 1u;
-        k -= read_lane(incl - cnt, ln);
-        // owning word inside that lane (ascending word index = ascending chunk id)
-        u32 idx = 0;
-        u64 word = 0;
+        if (pop != 0) {  // else nothing this link could carry: no draw is consumed
+          u32 k = read_lane(r, b) % pop;
+          // owning lane = first lane whose inclusive count exceeds k
+          const u64 above = __ballot(incl > k);
+          const u32 ln = (u32)__ffsll((long long)above) - 1u;
+          k -= read_lane(incl - cnt, ln);
+          // owning 64-bit word inside that lane: the number of words whose inclusive count
+          // is <= k, and the largest such count (pre is non-decreasing).  Counts are far
+          // below 2^31, so "pi <= k" is the complement of the sign bit of k - pi.
+          u32 idx = 0, before = 0;
 #pragma unroll
-        for (int i = 0; i < NW; ++i) {
-          const u64 w = read_lane64(cand[i], ln);
-          const u32 pc = (u32)__popcll(w);
-          if (word == 0) {
-            if (k < pc) { word = w; idx = (u32)i; }
-            else k -= pc;
+          for (int i = 0; i < NW - 1; ++i) {
+            const u32 pi = read_lane(pre[i], ln);
+            const u32 le = ((k - pi) >> 31) ^ 1u;
+            idx += le;
+            const u32 cand_before = pi * le;
+            before = cand_before > before ? cand_before : before;
           }
+          const u32 lo = read_lane(RT::at(cand_a, cand_b, 2u * idx), ln);
+          const u32 hi = read_lane(RT::at(cand_a, cand_b, 2u * idx + 1u), ln);
+          const u32 bit = kth_set_bit_wave(lo, hi, k - before);
+          const u32 chunk = ((ln * (u32)NW + idx) << 6) + bit;
+          clear_chunk<NW, RT>(need_a, need_b, chunk, lane);  // now in flight to d
+          if ((u32)lane == b) res = chunk;
         }
-        const u32 bit = kth_set_bit(word, k);
-        const u32 chunk = ((ln * (u32)NW + idx) << 6) + bit;
-        clear_chunk<NW>(need, chunk, lane);  // now in flight to d: later links skip it
-        if ((u32)lane == b) res = chunk;
       }
     }
     if (valid) {
       if (sched_row) sched_row[l] = res;
       if (res != kNone) {
-        if (cs > kInf - 1ull - t) {
+        if (res >= p.C) {  // cannot happen; never let a bad id reach the arrival kernel
+          ctl->status = kStInternal;
+          ctl->done = 1u;
+        } else if (cs > kInf - 1ull - t) {
           ctl->status = kStOverflow;
           ctl->done = 1u;
         } else {
@@ -347,9 +431,37 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
           p.free_at[l] = fa;
           my_min = fa < my_min ? fa : my_min;
         }
+      } else if (cr != kNone) {
+        const u64 fa = p.free_at[l];
+        my_min = fa < my_min ? fa : my_min;
       }
     }
   }
+  return my_min;
+}
+
+template <int NP>
+__global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
+{
+  const int lane = threadIdx.x & 63;
+  // Workgroups are handed to the 8 XCDs round-robin.  Give XCD x the contiguous slice
+  // [x*per_xcd, (x+1)*per_xcd) of the processing order, so that destinations that are
+  // close in the order (and share source rows) meet in the same L2.
+  // The grid is a multiple of 8 workgroups; slots past N do nothing.
+  const u32 per_xcd = gridDim.x >> 3;
+  const u32 pos = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  const u32 slot = uniform(pos * 4u + (threadIdx.x >> 6));
+  if (slot >= p.N) return;
+  const u32 d = uniform(p.order[slot]);
+  Ctl *ctl = p.ctl;
+  if (ctl->done) return;
+  const u64 rem = ctl->remaining;
+  const u64 t = ctl->next_t[event & 1u];
+  if (rem == 0) {  // every postcondition satisfied: the collective ends now
+    if (d == 0 && lane == 0) { ctl->T = t; ctl->n_events = event; ctl->done = 1u; }
+    return;
+  }
+  const u64 my_min = match_destination<NP>(p, d, event, t, sched_row, lane);
 
   // a8: next span = earliest end of a transfer in flight (min over all destinations)
   const u64 m = wave_min64(my_min);
@@ -357,6 +469,128 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
     u64 *nt = &ctl->next_t[(event + 1u) & 1u];
     const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (m < cur) atomicMin(nt, m);
+  }
+}
+
+// ---------------------------------------------------------------- persistent sweep
+
+// How long a workgroup spins at the grid barrier before it gives up (each probe is a
+// device-scope load plus a sleep of 64 clocks: a few seconds in all, against waits of
+// at most milliseconds).  Reaching it means a workgroup of the grid is
+// not running, which a cooperative launch rules out; it is the exit that every wave
+// reaches whatever happens.
+constexpr u32 kBarrierSpinLimit = 1u << 22;
+
+// Grid-wide barrier for a cooperative launch.  Release: every thread's stores are done
+// at the workgroup barrier, thread 0 then publishes them device-wide (the L2s of the
+// XCDs are not coherent with each other) with its release increment.  Acquire: after
+// the generation moved, thread 0's acquire fence drops stale lines before the workgroup
+// continues.  Returns false if the wait was abandoned.
+__device__ __forceinline__ bool grid_barrier(Ctl *ctl, u32 n_blocks, u64 &generation)
+{
+  __shared__ u32 ok_flag;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    u32 ok = 1u;
+    const u64 target = (generation + 1ull) * n_blocks;
+    const u64 prev = __hip_atomic_fetch_add(&ctl->bar_count, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    if (prev + 1ull == target) {
+      __hip_atomic_store(&ctl->bar_gen, generation + 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      u32 spins = 0;
+      while (__hip_atomic_load(&ctl->bar_gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <= generation) {
+        if (++spins > kBarrierSpinLimit) { ok = 0u; break; }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    ok_flag = ok;
+  }
+  __syncthreads();
+  generation += 1ull;
+  return ok_flag != 0u;
+}
+
+template <int NP>
+__global__ __launch_bounds__(256) void sweep_kernel(PassDev p, u32 first_event, u32 n_events, u32 stop_event,
+                                                    u32 *__restrict__ sched_rows, u64 *__restrict__ event_times)
+{
+  __shared__ u64 wave_min[4];
+  __shared__ u32 wave_cnt[4];
+  const int lane = threadIdx.x & 63;
+  const u32 wave = threadIdx.x >> 6;
+  Ctl *ctl = p.ctl;
+  const u32 n_blocks = gridDim.x;
+  // XCD-aware slots (workgroups go to the 8 XCDs round-robin; the grid is a multiple
+  // of 8): XCD x owns a contiguous slice of the processing order
+  const u32 n_pos = (p.N + 3u) / 4u;                  // positions of 4 destinations
+  const u32 per_xcd_blocks = n_blocks >> 3;
+  const u32 per_xcd_pos = (n_pos + 7u) / 8u;
+  const u32 xcd = blockIdx.x & 7u, rank_in_xcd = blockIdx.x >> 3;
+
+  u64 generation = __hip_atomic_load(&ctl->bar_gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  u64 t = ctl->next_t[first_event & 1u];
+  if (ctl->done) return;
+
+  for (u32 e = first_event; e < first_event + n_events; ++e) {
+    u32 *row = sched_rows ? sched_rows + (u64)(e - first_event) * p.L : nullptr;
+    // ---- arrivals at t (a3)
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      event_times[e - first_event] = t;
+      __hip_atomic_store(&ctl->next_t[(e + 1u) & 1u], kInf, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    u32 n_arr = 0;  // wave-uniform
+    for (u32 l0 = blockIdx.x * 256u; l0 < p.L; l0 += n_blocks * 256u) {
+      const u32 l = l0 + threadIdx.x;
+      const bool arrived = l < p.L && arrive_link(p, l, t, p.reversed ? row : nullptr);
+      n_arr += (u32)__popcll(__ballot(arrived));
+    }
+    if (lane == 0) wave_cnt[wave] = n_arr;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const u32 nb = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+      if (nb) atomicAdd(&ctl->remaining, (u64)0 - (u64)nb);
+    }
+    if (!grid_barrier(ctl, n_blocks, generation)) {
+      if (threadIdx.x == 0) { ctl->status = kStInternal; ctl->done = 1u; }
+      return;
+    }
+    // ---- all postconditions satisfied? (a4)
+    const u64 rem = __hip_atomic_load(&ctl->remaining, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (rem == 0ull) {
+      if (blockIdx.x == 0 && threadIdx.x == 0) { ctl->T = t; ctl->n_events = e; ctl->done = 1u; }
+      return;
+    }
+    if (e == stop_event) return;  // prefix run: time reached is next_t[e & 1]
+    // ---- matching for this span (a5-a7) and the earliest end of a transfer (a8)
+    u64 my_min = kInf;
+    for (u32 q = rank_in_xcd; q < per_xcd_pos; q += per_xcd_blocks) {
+      const u32 slot = uniform((xcd * per_xcd_pos + q) * 4u + wave);
+      if (slot < p.N) {
+        const u64 m = match_destination<NP>(p, uniform(p.order[slot]), e, t, p.reversed ? nullptr : row, lane);
+        my_min = m < my_min ? m : my_min;
+      }
+    }
+    my_min = wave_min64(my_min);
+    if (lane == 0) wave_min[wave] = my_min;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      u64 m = wave_min[0];
+      m = wave_min[1] < m ? wave_min[1] : m;
+      m = wave_min[2] < m ? wave_min[2] : m;
+      m = wave_min[3] < m ? wave_min[3] : m;
+      if (m != kInf) atomicMin(&ctl->next_t[(e + 1u) & 1u], m);
+    }
+    if (!grid_barrier(ctl, n_blocks, generation)) {
+      if (threadIdx.x == 0) { ctl->status = kStInternal; ctl->done = 1u; }
+      return;
+    }
+    if (__hip_atomic_load(&ctl->done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;  // overflow flagged
+    t = __hip_atomic_load(&ctl->next_t[(e + 1u) & 1u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == kInf) {  // chunks missing and nothing in flight
+      if (blockIdx.x == 0 && threadIdx.x == 0) { ctl->status = kStUnreachable; ctl->done = 1u; }
+      return;
+    }
   }
 }
 
@@ -434,7 +668,7 @@ void launch_arrive(const PassDev &p, u32 event, u64 *event_time_slot, u32 *sched
 
 void launch_match(const PassDev &p, u32 event, u32 *sched_row, hipStream_t s)
 {
-  const dim3 grid((p.N + 3) / 4), block(256);
+  const dim3 grid(8u * ((((p.N + 3u) / 4u) + 7u) / 8u)), block(256);
   switch (p.NP) {
     case 1: hipLaunchKernelGGL(match_kernel<1>, grid, block, 0, s, p, event, sched_row); break;
     case 2: hipLaunchKernelGGL(match_kernel<2>, grid, block, 0, s, p, event, sched_row); break;
@@ -445,6 +679,58 @@ void launch_match(const PassDev &p, u32 event, u32 *sched_row, hipStream_t s)
     case 7: hipLaunchKernelGGL(match_kernel<7>, grid, block, 0, s, p, event, sched_row); break;
     case 8: hipLaunchKernelGGL(match_kernel<8>, grid, block, 0, s, p, event, sched_row); break;
     default: break;  // rejected by the host before any launch
+  }
+}
+
+template <int NP> static hipError_t launch_sweep_np(const PassDev &p, u32 first_event, u32 n_events,
+                                                    u32 stop_event, u32 *sched_rows, u64 *event_times,
+                                                    u32 grid_blocks, hipStream_t s)
+{
+  PassDev pc = p;
+  void *args[] = {&pc, &first_event, &n_events, &stop_event, &sched_rows, &event_times};
+  return hipLaunchCooperativeKernel(reinterpret_cast<const void *>(&sweep_kernel<NP>), dim3(grid_blocks),
+                                    dim3(256), args, 0, s);
+}
+
+hipError_t launch_sweep(const PassDev &p, u32 first_event, u32 n_events, u32 stop_event, u32 *sched_rows,
+                        u64 *event_times, u32 grid_blocks, hipStream_t s)
+{
+  switch (p.NP) {
+    case 1: return launch_sweep_np<1>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
+    case 2: return launch_sweep_np<2>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
+    case 3: return launch_sweep_np<3>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
+    case 4: return launch_sweep_np<4>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
+    case 5: return launch_sweep_np<5>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
+    case 6: return launch_sweep_np<6>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
+    case 7: return launch_sweep_np<7>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
+    case 8: return launch_sweep_np<8>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template <int NP> static u32 sweep_blocks_np()
+{
+  int dev = 0, coop = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sweep_kernel<NP>, 256, 0) != hipSuccess) return 0;
+  if (per_cu <= 0 || cus <= 0) return 0;
+  return (u32)per_cu * (u32)cus;
+}
+
+u32 sweep_max_blocks(u32 NP)
+{
+  switch (NP) {
+    case 1: return sweep_blocks_np<1>();
+    case 2: return sweep_blocks_np<2>();
+    case 3: return sweep_blocks_np<3>();
+    case 4: return sweep_blocks_np<4>();
+    case 5: return sweep_blocks_np<5>();
+    case 6: return sweep_blocks_np<6>();
+    case 7: return sweep_blocks_np<7>();
+    case 8: return sweep_blocks_np<8>();
+    default: return 0;
   }
 }
 

@@ -193,9 +193,31 @@ def test_same_seed_same_digest_and_stream_independence(stream):
 
 def test_kernel_timing_is_reported(stream):
     topo = T.torus3d(6, 6, 4)
-    with gpu(topo, 1, MiB, T.ALL_GATHER, 1, stream, time_kernels=True) as r:
-        assert r.kernel_launches == r.num_events
+    with gpu(topo, 1, MiB, T.ALL_GATHER, 1, stream, time_kernels=True, launch_mode=0) as r:
+        assert r.kernel_launches == r.num_events      # one matching launch per span
         assert 0.0 < r.kernel_ms < r.wall_ms
+    with gpu(topo, 1, MiB, T.ALL_GATHER, 1, stream, time_kernels=True, launch_mode=1) as r:
+        assert 1 <= r.kernel_launches < r.num_events  # persistent sweeps
+        assert 0.0 < r.kernel_ms < r.wall_ms
+
+
+@pytest.mark.parametrize("name,mk,cpn,coll", SMALL, ids=[c[0] for c in SMALL])
+def test_persistent_launch_mode_bit_exact(name, mk, cpn, coll, stream):
+    """launch_mode 1 (one cooperative launch sweeping many spans behind grid barriers)
+    gives the same schedule as the per-span launches the other tests use."""
+    topo = mk()
+    cb = 192 << 10
+    ref = cpu(topo, cpn, cb, coll, 5)
+    with gpu(topo, cpn, cb, coll, 5, stream, launch_mode=1) as r:
+        assert_same(r, ref, name)
+
+
+def test_both_launch_modes_on_prefix_runs(stream):
+    topo = T.torus3d(4, 4, 8)
+    ref = cpu(topo, 65, MiB, T.ALL_GATHER, 3, max_events=37)
+    for mode in (0, 1):
+        with gpu(topo, 65, MiB, T.ALL_GATHER, 3, stream, max_events=37, launch_mode=mode) as r:
+            assert_same(r, ref, f"mode {mode}")
 
 
 def test_five_piece_rows_full_run(stream):
