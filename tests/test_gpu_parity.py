@@ -256,3 +256,23 @@ def test_workload_5_prefix_bit_exact(stream):
         for first in range(0, n, step):
             cnt = min(step, n - first)
             assert np.array_equal(r.read(first, cnt), ref.xfers[first:first + cnt]), first
+
+
+def test_workload_5_full_run_against_stored_oracle_result(stream):
+    """The complete 40,960-NPU All-Gather (1.68e9 transfers) against what the oracle
+    stored in tests/golden/workload5_oracle.json (make_golden.py --with-5, minutes of CPU
+    time): collective time, spans, transfers, the digest over every transfer, the per-span
+    (time, match count) trace and the first 4096 records."""
+    with open(os.path.join(os.path.dirname(GOLDEN), "workload5_oracle.json")) as f:
+        g = json.load(f)
+    w = T.workload(5)
+    with binding.synthesize_workload(w, stream=stream) as r:
+        assert r.collective_time_ps == g["collective_time_ps"]
+        assert r.num_events == g["n_events"] and r.num_xfers == g["n_xfers"]
+        assert r.digest == g["digest"]
+        t, m = r.event_trace(0)
+        assert hashlib.sha256(t.tobytes() + m.tobytes()).hexdigest() == g["sha256_event_trace"]
+        assert hashlib.sha256(r.read(0, 4096).tobytes()).hexdigest() == g["sha256_first_4096_xfers"]
+        # the last record of the canonical order ends exactly at the collective time
+        last = r.read(r.num_xfers - 1, 1)[0]
+        assert int(last["t_ps"]) + 10_985_760 == g["collective_time_ps"]
