@@ -31,7 +31,8 @@
  *     1. arrivals: every link whose transfer ends at t delivers its chunk;
  *     2. if every NPU holds every chunk: collective_time = t, stop;
  *     3. matching for this span (Algorithm 1): for every destination NPU d, for every
- *        IDLE incoming link l = (s -> d) in ascending link id:
+ *        IDLE incoming link l = (s -> d) in ascending link id (or cheapest first, see
+ *        tacos_options_t::link_order):
  *          cand = held[s] & ~held[d] & ~inflight[d];  p = |cand|;  if p == 0 skip;
  *          r = word 0 of Philox4x32-10(counter = (l, event, phase, 0),
  *                                      key = (seed mod 2^32, seed div 2^32));
@@ -77,6 +78,10 @@ typedef enum {
 #define TACOS_E_NOMEM       (-4) /* host or device allocation failed                           */
 #define TACOS_E_DEVICE      (-5) /* no HIP device / a HIP call failed (see tacos_last_error)   */
 
+/* tacos_options_t::link_order */
+#define TACOS_LINK_ORDER_ID   0u
+#define TACOS_LINK_ORDER_COST 1u
+
 /* Largest supported number of chunks N*chunks_per_npu (one wavefront keeps a
  * destination's whole "still needed" bitset in registers). */
 #define TACOS_MAX_CHUNKS 65536u
@@ -116,6 +121,11 @@ typedef struct {
                              on MI355X.  1 = persistent: one cooperative launch sweeps many
                              spans with two grid-wide barriers per span; falls back to 0 if
                              the device cannot launch cooperatively.  Same results.          */
+  uint32_t link_order;    /* order in which a destination's idle incoming links are tried:
+                             0 = ascending link id; 1 = cheapest link first, ties by link id
+                             (paper, "Prioritizing Lower-cost Links").  The random draw of a
+                             link does not depend on the order.                              */
+  uint32_t reserved;      /* must be 0                                                       */
 } tacos_options_t;
 
 typedef struct tacos_result tacos_result_t; /* opaque; owns device and host buffers */

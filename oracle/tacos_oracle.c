@@ -15,7 +15,8 @@
  *     times of its links;
  *   - the utilization-maximizing link-chunk matching of Algorithm 1 for one span, in
  *     the link-centric, deterministic form: destinations in turn, each destination's
- *     incoming idle links in ascending link id, every link matched to the
+ *     incoming idle links in ascending link id (or cheapest first, the paper's
+ *     "Prioritizing Lower-cost Links", when asked), every link matched to the
  *     (r mod p)-th smallest chunk of the p chunks its source holds, its destination
  *     lacks and is not already receiving; r is Philox4x32-10 keyed by the seed and
  *     countered by (link, event, phase).  One chunk per link (section "Representing
@@ -206,7 +207,7 @@ static uint32_t kth_bit(uint64_t w, uint32_t k)
  */
 static int ag_pass(uint32_t N, uint32_t L, const uint32_t *psrc, const uint32_t *pdst,
                    const uint64_t *cost, uint32_t cpn, uint64_t seed, uint32_t phase,
-                   uint64_t max_events, int n_threads,
+                   uint64_t max_events, int n_threads, int link_order,
                    pass_out_t *out, uint64_t *T, uint64_t *n_events, int *complete)
 {
   const uint64_t C = (uint64_t)N * cpn;
@@ -233,6 +234,18 @@ static int ag_pass(uint32_t N, uint32_t L, const uint32_t *psrc, const uint32_t 
     memcpy(fill, in_ptr, ((size_t)N + 1) * sizeof(uint32_t));
     for (uint32_t l = 0; l < L; ++l) in_link[fill[pdst[l]]++] = l;
     free(fill);
+  }
+  /* "Prioritizing Lower-cost Links": when asked, a destination's incoming links are
+   * walked from the cheapest to the most expensive (ties by link id) instead of by
+   * link id.  Insertion sort: stable, lists are short. */
+  if (link_order == 1) {
+    for (uint32_t d = 0; d < N; ++d)
+      for (uint32_t j = in_ptr[d] + 1; j < in_ptr[d + 1]; ++j) {
+        uint32_t l = in_link[j];
+        uint32_t k = j;
+        while (k > in_ptr[d] && cost[in_link[k - 1]] > cost[l]) { in_link[k] = in_link[k - 1]; k--; }
+        in_link[k] = l;
+      }
   }
   /* precondition of All-Gather: NPU i holds its own cpn chunks */
   for (uint32_t i = 0; i < N; ++i)
@@ -356,12 +369,15 @@ static void pass_out_free(pass_out_t *o) { free(o->rec); free(o->ev_time); free(
  *                (all are counted and digested); a reversed pass always keeps all.
  *   n_threads  : OpenMP threads for the destination loop of the matching step
  *                (1 = serial; only used when built with -fopenmp).
+ *   link_order : 0 = a destination's incoming links are tried in ascending link id;
+ *                1 = cheapest link first, ties by link id (the paper's "Prioritizing
+ *                Lower-cost Links").  The random draw of a link does not depend on it.
  */
 int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col_idx,
                    const uint64_t *alpha_ps, const uint64_t *beta_fs_per_B,
                    uint32_t chunks_per_npu, uint64_t chunk_bytes, int collective,
                    uint64_t seed, uint64_t max_events, uint64_t keep_first,
-                   uint64_t keep_xfers, int n_threads,
+                   uint64_t keep_xfers, int n_threads, int link_order,
                    orc_result_t **result)
 {
   if (!row_ptr || !result || n_npus == 0 || chunks_per_npu == 0 || chunk_bytes == 0)
@@ -375,6 +391,7 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
   if (L && (!col_idx || !alpha_ps || !beta_fs_per_B)) return ORC_E_INVAL;
   if ((uint64_t)n_npus * chunks_per_npu >= 0xFFFFFFFFull) return ORC_E_INVAL;
   if (n_threads < 1) n_threads = 1;
+  if (link_order != 0 && link_order != 1) return ORC_E_INVAL;
 
   int rc = ORC_OK;
   uint32_t *src = (uint32_t *)malloc((L ? L : 1) * sizeof(uint32_t));
@@ -403,7 +420,7 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
     o->keep_limit = ~0ull;
     uint64_t T = 0, ne = 0; int complete = 0;
     rc = ag_pass(n_npus, L, col_idx, src, cost, chunks_per_npu, seed, 1u, max_events,
-                 n_threads, o, &T, &ne, &complete);
+                 n_threads, link_order, o, &T, &ne, &complete);
     if (rc != ORC_OK) goto fail;
     complete_all &= complete;
     res->pass_time_ps[n_pass] = T; res->pass_events[n_pass] = ne;
@@ -416,7 +433,7 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
     o->fwd = 1; o->t_off = t_off;
     uint64_t T = 0, ne = 0; int complete = 0;
     rc = ag_pass(n_npus, L, src, col_idx, cost, chunks_per_npu, seed, 0u, max_events,
-                 n_threads, o, &T, &ne, &complete);
+                 n_threads, link_order, o, &T, &ne, &complete);
     if (rc != ORC_OK) goto fail;
     complete_all &= complete;
     res->pass_time_ps[n_pass] = T; res->pass_events[n_pass] = ne;
@@ -426,7 +443,11 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
 
   /* assemble the records in canonical order */
   uint64_t total_keep = 0;
-  for (int p = 0; p < n_pass; ++p) total_keep += po[p].n;
+  /* keep_xfers == 0: digest-only run (large inputs): the reversed pass is digested
+   * from its raw records and not materialised */
+  const int digest_only = (keep_xfers == 0);
+  for (int p = 0; p < n_pass; ++p)
+    if (!(digest_only && collective != ORC_ALL_GATHER && p == 0)) total_keep += po[p].n;
   res->xfers = (orc_xfer_t *)malloc((total_keep ? total_keep : 1) * sizeof(orc_xfer_t));
   if (!res->xfers) { rc = ORC_E_NOMEM; goto fail; }
   uint64_t w = 0;
@@ -437,6 +458,12 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
      * [T - t' - cost, T - t') of the Reduce-Scatter */
     const uint64_t T = res->pass_time_ps[0];
     const uint64_t first = w;
+    if (digest_only) {
+      for (uint64_t i = 0; i < po[0].n; ++i) {
+        const pass_rec_t *r = &po[0].rec[i];
+        res->digest += orc_mix(T - r->t - cost[r->link], r->link, r->chunk);
+      }
+    } else
     for (uint64_t i = 0; i < po[0].n; ++i) {
       const pass_rec_t *r = &po[0].rec[i];
       orc_xfer_t x;

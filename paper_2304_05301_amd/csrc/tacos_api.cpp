@@ -184,8 +184,8 @@ std::vector<uint32_t> cluster_order(uint32_t N, uint32_t L, const std::vector<ui
 // Runs one All-Gather pass over links psrc[l] -> pdst[l] and stores its schedule rows.
 int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
              const DevBuf &d_cost, uint32_t cpn, uint64_t seed, uint32_t phase, bool reversed,
-             uint64_t max_events, bool time_kernels, bool persistent, hipStream_t stream,
-             tacos_result &res, Pass &pass)
+             uint64_t max_events, bool time_kernels, bool persistent, const std::vector<uint64_t> *order_cost,
+             hipStream_t stream, tacos_result &res, Pass &pass)
 {
   const uint32_t C = N * cpn;
   const uint32_t NP = (C + 8191u) / 8192u;
@@ -203,6 +203,20 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
       const uint32_t j = fill[pdst[l]]++;
       in_link[j] = l;
       in_src[j] = psrc[l];
+    }
+  }
+  if (order_cost) {
+    // cheapest incoming link first, ties by link id ("Prioritizing Lower-cost Links");
+    // the costs are the ones the device computed
+    std::vector<uint32_t> tmp;
+    for (uint32_t d = 0; d < N; ++d) {
+      tmp.assign(in_link.begin() + in_ptr[d], in_link.begin() + in_ptr[d + 1]);
+      std::stable_sort(tmp.begin(), tmp.end(),
+                       [&](uint32_t a, uint32_t b) { return (*order_cost)[a] < (*order_cost)[b]; });
+      for (size_t k = 0; k < tmp.size(); ++k) {
+        in_link[in_ptr[d] + k] = tmp[k];
+        in_src[in_ptr[d] + k] = psrc[tmp[k]];
+      }
     }
   }
 
@@ -464,6 +478,8 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
   if (rc != TACOS_OK) return rc;
   const uint64_t max_events = opts ? opts->max_events : 0;
   if (max_events && coll != TACOS_ALL_GATHER) return TACOS_E_INVAL;
+  if (opts && (opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 1 || opts->reserved != 0))
+    return TACOS_E_INVAL;
   const bool time_kernels = opts && opts->time_kernels;
   const bool persistent = opts && opts->launch_mode == 1;
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
@@ -495,14 +511,17 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
     } else {
       if (L == 0) return TACOS_E_UNREACHABLE;
       DevBuf d_cost;
-      rc = device_costs(topo, chunk_bytes, stream, d_cost, nullptr);
+      std::vector<uint64_t> host_cost;
+      const bool by_cost = opts && opts->link_order == TACOS_LINK_ORDER_COST;
+      rc = device_costs(topo, chunk_bytes, stream, d_cost, by_cost ? &host_cost : nullptr);
       if (rc != TACOS_OK) return rc;
+      const std::vector<uint64_t> *order_cost = by_cost ? &host_cost : nullptr;
       uint64_t t_off = 0;
       if (coll == TACOS_REDUCE_SCATTER || coll == TACOS_ALL_REDUCE) {
         // reversed pass: every link (s -> d) is used as (d -> s), ids and costs unchanged
         res->passes.emplace_back();
         rc = run_pass(N, L, res->link_dst, res->link_src, d_cost, chunks_per_npu, seed, 1u, true, 0,
-                      time_kernels, persistent, stream, *res, res->passes.back());
+                      time_kernels, persistent, order_cost, stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), 0, &res->digest, stream);
         t_off = res->passes.back().T;
@@ -510,7 +529,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       if (coll == TACOS_ALL_GATHER || coll == TACOS_ALL_REDUCE) {
         res->passes.emplace_back();
         rc = run_pass(N, L, res->link_src, res->link_dst, d_cost, chunks_per_npu, seed, 0u, false,
-                      max_events, time_kernels, persistent, stream, *res, res->passes.back());
+                      max_events, time_kernels, persistent, order_cost, stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), t_off, &res->digest, stream);
       }

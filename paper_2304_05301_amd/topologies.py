@@ -290,7 +290,7 @@ class Workload:
 
 
 def workload(idx: int) -> Workload:
-    """The five benchmark workloads (1-based), all synthetic and seeded.
+    """The benchmark workloads (1-based), all synthetic and seeded.
 
     1: All-Gather, 8-NPU unidirectional ring, 0.5 us / 50 GB/s, 1 x 1 MiB, seed 0
     2: All-Gather, 8x8 2D mesh, 0.5 us / 100 GB/s, 4 x 256 KiB per NPU, seed 1
@@ -298,6 +298,9 @@ def workload(idx: int) -> Workload:
        0.5 us, Z 50 GB/s 1 us), 4 x 1 MiB per NPU, seed 2
     4: All-Gather, random asymmetric 1024 NPUs, out-degree 6, 1 x 4 MiB, seed 3
     5: All-Gather, 32x32x40 3D torus, 0.5 us / 100 GB/s, 1 x 1 MiB, seed 4
+    6: All-Reduce, 200x200 2D mesh (40,000 NPUs), 0.5 us / 50 GB/s, 1 x 1 MiB, seed 6
+    7: All-Reduce, 35x35x35 3D mesh (42,875 NPUs), 0.5 us / 50 GB/s, 1 x 1 MiB, seed 7
+    (6 and 7 are the shapes of the paper's scalability experiment.)
     """
     MiB = 1 << 20
     if idx == 1:
@@ -314,4 +317,12 @@ def workload(idx: int) -> Workload:
     if idx == 5:
         return Workload("torus32x32x40_ag", torus3d(32, 32, 40, 500_000, 10_000), 1, MiB,
                         ALL_GATHER, 4)
-    raise ValueError("workload index must be 1..5")
+    if idx == 6:
+        # the paper's scalability study: All-Reduce on an asymmetric homogeneous 2D mesh
+        # of about 40K NPUs, the paper's default link (0.5 us, 50 GB/s)
+        return Workload("mesh200x200_ar", mesh2d(200, 200, 500_000, 20_000), 1, MiB, ALL_REDUCE, 6)
+    if idx == 7:
+        # ... and on a 3D "hypercube" (3D mesh without wrap-around) of about 43K NPUs
+        return Workload("mesh35x35x35_ar", grid([35, 35, 35], False, 500_000, 20_000), 1, MiB,
+                        ALL_REDUCE, 7)
+    raise ValueError("workload index must be 1..7")

@@ -21,12 +21,44 @@ import oracle  # noqa: E402
 from paper_2304_05301_amd import binding, topologies as T  # noqa: E402
 
 
+def reversed_run(w, threads):
+    """Reduce-Scatter / All-Reduce at full size: the oracle digests its records without
+    materialising them (keep_xfers=0), so collective time, per-pass times and spans, the
+    number of transfers and the digest over all of them are compared."""
+    t0 = time.time()
+    r = binding.synthesize_workload(w)
+    gpu = dict(T=r.collective_time_ps, events=r.num_events, xfers=r.num_xfers, digest=r.digest,
+               pass_T=[r.pass_time_ps(i) for i in range(r.num_passes)],
+               pass_events=[r.pass_events(i) for i in range(r.num_passes)])
+    r.free()
+    print(f"gpu   {gpu} in {time.time() - t0:.1f} s", flush=True)
+    oracle.set_progress(1000)
+    t0 = time.time()
+    ref = oracle.synthesize_workload(w, keep_xfers=0, n_threads=threads)
+    n_pass = len(gpu["pass_T"])
+    print(f"oracle T={ref.collective_time_ps} events={ref.n_events} xfers={ref.n_xfers} digest={ref.digest} "
+          f"pass_T={ref.pass_time_ps[:n_pass]} in {time.time() - t0:.1f} s with {threads} threads", flush=True)
+    ok = (gpu["T"] == ref.collective_time_ps and gpu["events"] == ref.n_events and
+          gpu["xfers"] == ref.n_xfers and gpu["digest"] == ref.digest and
+          gpu["pass_T"] == list(ref.pass_time_ps[:n_pass]) and
+          gpu["pass_events"] == list(ref.pass_events[:n_pass]))
+    print("FULL-SIZE PARITY:", "PASS" if ok else "FAIL", flush=True)
+    sys.exit(0 if ok else 1)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--workload", type=int, default=5)
+    ap.add_argument("--collective", choices=["ag", "rs", "ar"], default=None,
+                    help="override the workload's collective (rs/ar: digest, times and counts only)")
     args = ap.parse_args()
     w = T.workload(args.workload)
+    if args.collective:
+        coll = {"ag": T.ALL_GATHER, "rs": T.REDUCE_SCATTER, "ar": T.ALL_REDUCE}[args.collective]
+        w = T.Workload(w.name + "_" + args.collective, w.topo, w.chunks_per_npu, w.chunk_bytes, coll, w.seed)
+    if w.collective != T.ALL_GATHER:
+        return reversed_run(w, args.threads)
     t0 = time.time()
     r = binding.synthesize_workload(w)
     gpu = dict(T=r.collective_time_ps, events=r.num_events, xfers=r.num_xfers, digest=r.digest)

@@ -276,3 +276,55 @@ def test_workload_5_full_run_against_stored_oracle_result(stream):
         # the last record of the canonical order ends exactly at the collective time
         last = r.read(r.num_xfers - 1, 1)[0]
         assert int(last["t_ps"]) + 10_985_760 == g["collective_time_ps"]
+
+
+@pytest.mark.parametrize("coll", [T.ALL_GATHER, T.ALL_REDUCE])
+def test_lower_cost_link_priority_bit_exact(coll, stream):
+    """link_order = cheapest first ('Prioritizing Lower-cost Links') against the oracle
+    with the same option, on heterogeneous inputs where the order matters."""
+    for topo, cpn in ((T.grid([3, 3, 4], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000]), 3),
+                      (T.random_regular_out(64, 4, seed=12)[0], 2),
+                      (T.from_edge_list(2, [(0, 1, 10, 0), (0, 1, 1, 0), (1, 0, 1, 0)]), 1)):
+        ref = cpu(topo, cpn, 64 << 10, coll, 17, link_order=1)
+        with gpu(topo, cpn, 64 << 10, coll, 17, stream, link_order=1) as r:
+            assert_same(r, ref, topo.name)
+        ref0 = cpu(topo, cpn, 64 << 10, coll, 17, link_order=0)
+        assert ref.digest != ref0.digest
+
+
+@pytest.mark.parametrize("name,mk", [("mesh64x64", lambda: T.mesh2d(64, 64, 500_000, 20_000)),
+                                     ("mesh3d_12", lambda: T.grid([12, 12, 12], False, 500_000, 20_000))])
+def test_scalability_shapes_all_reduce_full(name, mk, stream):
+    """Scaled-down shapes of the paper's scalability experiment (All-Reduce on a 2D mesh
+    and on a 3D mesh without wrap-around; in-degree 2..6), run to completion: Reduce-
+    Scatter and All-Gather halves record by record."""
+    topo = mk()
+    ref = cpu(topo, 1, MiB, T.ALL_REDUCE, 6, n_threads=min(16, oracle.max_threads()))
+    with gpu(topo, 1, MiB, T.ALL_REDUCE, 6, stream) as r:
+        assert r.collective_time_ps == ref.collective_time_ps and r.digest == ref.digest
+        assert [r.pass_time_ps(i) for i in range(2)] == list(ref.pass_time_ps)
+        assert [r.pass_events(i) for i in range(2)] == list(ref.pass_events)
+        n = r.num_xfers
+        assert n == ref.n_xfers
+        step = 1 << 21
+        for first in range(0, n, step):
+            cnt = min(step, n - first)
+            assert np.array_equal(r.read(first, cnt), ref.xfers[first:first + cnt]), (name, first)
+
+
+@pytest.mark.parametrize("idx,n_ev", [(6, 40), (7, 40)])
+def test_scalability_workloads_prefix_bit_exact(idx, n_ev, stream):
+    """Full-size shapes of the paper's scalability experiment (40,000-NPU 2D mesh and
+    42,875-NPU 3D mesh): the first spans of the All-Gather pass record by record."""
+    w = T.workload(idx)
+    t = w.topo
+    ref = oracle.synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B, 1, w.chunk_bytes,
+                            T.ALL_GATHER, w.seed, max_events=n_ev, n_threads=min(16, oracle.max_threads()))
+    with gpu(t, 1, w.chunk_bytes, T.ALL_GATHER, w.seed, stream, max_events=n_ev) as r:
+        assert r.collective_time_ps == ref.collective_time_ps and r.num_xfers == ref.n_xfers
+        assert r.digest == ref.digest
+        n = r.num_xfers
+        step = 1 << 21
+        for first in range(0, n, step):
+            cnt = min(step, n - first)
+            assert np.array_equal(r.read(first, cnt), ref.xfers[first:first + cnt]), first

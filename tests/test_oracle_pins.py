@@ -319,3 +319,34 @@ def test_parallel_links_are_distinct():
     checker.check_all_gather(6, topo.link_src, topo.link_dst, cost, 2, r.xfers,
                              r.collective_time_ps, check_maximal=True)
     assert len(set(r.xfers["link"].tolist())) == topo.n_links
+
+
+# ------------------------------------------------------------------ lower-cost-link priority
+
+def test_lower_cost_link_priority_closed_form():
+    """'Prioritizing Lower-cost Links': two parallel links 0 -> 1, id 0 costing 10 ps and
+    id 1 costing 1 ps, and one chunk to deliver.  In link-id order the expensive link
+    carries it (collective time 10); cheapest-first the cheap one does (time 1)."""
+    topo = T.from_edge_list(2, [(0, 1, 10, 0), (0, 1, 1, 0), (1, 0, 1, 0)])
+    by_id = run(topo, chunk_bytes=1, link_order=0)
+    by_cost = run(topo, chunk_bytes=1, link_order=1)
+    assert by_id.collective_time_ps == 10 and by_cost.collective_time_ps == 1
+    assert [int(x["link"]) for x in by_id.xfers] == [0, 2]
+    assert [int(x["link"]) for x in by_cost.xfers] == [1, 2]
+
+
+def test_lower_cost_link_priority_valid_and_neutral_when_homogeneous():
+    homo = T.torus3d(3, 3, 2)
+    a = run(homo, cpn=2, seed=4, link_order=0)
+    b = run(homo, cpn=2, seed=4, link_order=1)
+    assert np.array_equal(a.xfers, b.xfers)            # equal costs: ties by id = id order
+    het = T.grid([3, 3, 3], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000])
+    cost = costs(het, MiB)
+    r0 = run(het, cpn=2, seed=4, link_order=0)
+    r1 = run(het, cpn=2, seed=4, link_order=1)
+    assert not np.array_equal(r0.xfers, r1.xfers)
+    for r in (r0, r1):
+        checker.check_all_gather(27, het.link_src, het.link_dst, cost, 2, r.xfers,
+                                 r.collective_time_ps, check_maximal=True)
+    rs = run(het, cpn=1, coll=T.REDUCE_SCATTER, seed=4, link_order=1)
+    checker.check_reduce_scatter(27, het.link_src, het.link_dst, cost, 1, rs.xfers, rs.collective_time_ps)
