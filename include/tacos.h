@@ -165,6 +165,13 @@ int tacos_result_read(const tacos_result_t *r, uint64_t first, uint64_t count,
 int tacos_result_event_trace(const tacos_result_t *r, uint32_t pass,
                              uint64_t *event_time_ps, uint32_t *event_matches);
 /*
+ * Number of transfers every link carries in pass `pass`: link_counts[l] (host,
+ * [n_links], caller-owned), column sums of the schedule computed on the device.  With
+ * the link costs this gives the link utilisation the paper reports
+ * (count * cost / pass time; section "Analysis of TACOS-Synthesized Algorithms").
+ */
+int tacos_result_link_counts(const tacos_result_t *r, uint32_t pass, uint64_t *link_counts);
+/*
  * Order-independent digest of the schedule: sum modulo 2^64 over all transfers of
  *   h = t_ps ^ (((link << 32) | chunk) * 0x9E3779B97F4A7C15);
  *   h ^= h >> 33; h *= 0xFF51AFD7ED558CCD; h ^= h >> 33; h *= 0xC4CEB9FE1A85EC53; h ^= h >> 33.

@@ -31,7 +31,7 @@ EXPORTS = [
     "tacos_synthesize", "tacos_result_collective_time_ps", "tacos_result_num_xfers",
     "tacos_result_num_events", "tacos_result_num_passes", "tacos_result_pass_time_ps",
     "tacos_result_pass_events", "tacos_result_read", "tacos_result_event_trace",
-    "tacos_result_digest", "tacos_result_kernel_ms", "tacos_result_kernel_launches",
+    "tacos_result_link_counts", "tacos_result_digest", "tacos_result_kernel_ms", "tacos_result_kernel_launches",
     "tacos_result_wall_ms", "tacos_result_device_bytes", "tacos_result_free",
     "tacos_strerror", "tacos_last_error", "tacos_link_costs", "tacos_version",
 ]
@@ -84,6 +84,7 @@ def load() -> ctypes.CDLL:
         f.restype, f.argtypes = ctypes.c_double, [vp]
     L.tacos_result_read.restype, L.tacos_result_read.argtypes = i32, [vp, u64, u64, vp]
     L.tacos_result_event_trace.restype, L.tacos_result_event_trace.argtypes = i32, [vp, u32, vp, vp]
+    L.tacos_result_link_counts.restype, L.tacos_result_link_counts.argtypes = i32, [vp, u32, vp]
     L.tacos_result_free.restype, L.tacos_result_free.argtypes = None, [vp]
     L.tacos_strerror.restype, L.tacos_strerror.argtypes = ctypes.c_char_p, [i32]
     L.tacos_last_error.restype, L.tacos_last_error.argtypes = ctypes.c_char_p, []
@@ -179,6 +180,14 @@ class TacosResult:
         if rc != TACOS_OK:
             _raise(rc)
         return t, m
+
+    def link_counts(self, pass_index: int, n_links: int) -> np.ndarray:
+        """tacos_result_link_counts: transfers carried by every link in one pass."""
+        out = np.zeros(int(n_links), dtype=np.uint64)
+        rc = load().tacos_result_link_counts(self._req(), pass_index, out.ctypes.data)
+        if rc != TACOS_OK:
+            _raise(rc)
+        return out
 
     def free(self):
         if self._h:

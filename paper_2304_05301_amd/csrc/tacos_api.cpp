@@ -654,6 +654,36 @@ int tacos_result_read(const tacos_result_t *r, uint64_t first, uint64_t count, t
   return TACOS_OK;
 }
 
+int tacos_result_link_counts(const tacos_result_t *r, uint32_t pass, uint64_t *link_counts)
+{
+  g_last_error.clear();
+  if (!r || pass >= r->passes.size() || (r->L && !link_counts)) return TACOS_E_INVAL;
+  const Pass &ps = r->passes[pass];
+  if (r->L == 0) return TACOS_OK;
+  try {
+    int prev = 0;
+    HIP_TRY(hipGetDevice(&prev));
+    if (prev != r->device) HIP_TRY(hipSetDevice(r->device));
+    DevBuf d_counts((size_t)r->L * 8);
+    HIP_TRY(hipMemset(d_counts.p, 0, (size_t)r->L * 8));
+    for (size_t k = 0; k < ps.segs.size(); ++k) {
+      const uint64_t first = (uint64_t)k * ps.rows_per_seg;
+      if (first >= ps.n_rows) break;
+      const uint32_t n = (uint32_t)std::min<uint64_t>(ps.rows_per_seg, ps.n_rows - first);
+      tacos::launch_link_counts(ps.segs[k].rows.as<uint32_t>(), n, ps.L, d_counts.as<unsigned long long>(),
+                                nullptr);
+      HIP_TRY(hipGetLastError());
+    }
+    HIP_TRY(hipMemcpy(link_counts, d_counts.p, (size_t)r->L * 8, hipMemcpyDeviceToHost));
+    if (prev != r->device) HIP_TRY(hipSetDevice(prev));
+  } catch (const HipFail &f) {
+    return f.code;
+  } catch (const std::bad_alloc &) {
+    return TACOS_E_NOMEM;
+  }
+  return TACOS_OK;
+}
+
 void tacos_result_free(tacos_result_t *r)
 {
   if (!r) return;

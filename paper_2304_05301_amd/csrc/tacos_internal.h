@@ -92,4 +92,8 @@ void launch_row_stats(const uint32_t *rows, uint32_t n_rows, uint32_t L,
                       uint32_t reversed, uint32_t *row_count, unsigned long long *digest,
                       hipStream_t s);
 
+// reporting: counts[l] += number of rows of the block in which link l carries a chunk
+void launch_link_counts(const uint32_t *rows, uint32_t n_rows, uint32_t L, unsigned long long *counts,
+                        hipStream_t s);
+
 }  // namespace tacos

@@ -177,9 +177,13 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
                                                      u32 *__restrict__ sched_row)
 {
   Ctl *ctl = p.ctl;
+  const u32 l = blockIdx.x * 256u + threadIdx.x;
+  // the link's state does not depend on the control block: have all loads in flight at once
+  u32 c = kNone, d = 0;
+  u64 fa = 0;
+  if (l < p.L) { c = p.carry[l]; fa = p.free_at[l]; d = p.link_dst[l]; }
   if (ctl->done) return;
   const u64 t = ctl->next_t[event & 1u];
-  const u32 l = blockIdx.x * 256u + threadIdx.x;
   if (l == 0) {
     *event_time_slot = t;
     ctl->next_t[(event + 1u) & 1u] = kInf;
@@ -189,7 +193,12 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
     }
   }
   if (t == kInf) return;
-  const bool arrived = l < p.L && arrive_link(p, l, t, sched_row);
+  const bool arrived = (c != kNone) && (fa == t);
+  if (arrived) {
+    atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
+    p.carry[l] = kNone;
+  }
+  if (sched_row && l < p.L) sched_row[l] = arrived ? c : kNone;
   const u32 n = (u32)__popcll(__ballot(arrived));
   __shared__ u32 block_n;
   if (threadIdx.x == 0) block_n = 0;
@@ -237,16 +246,6 @@ template <int NDW> struct RowRegs {
       return i < 16u ? x : y;
     }
   }
-  static __device__ __forceinline__ void put(A &a, B &b, u32 i, u32 v)
-  {
-    if constexpr (!kSplit) a[i] = v;
-    else {
-      const u32 il = i & 15u, ih = (i - 16u) & kMaskB;
-      const u32 x = a[il], y = b[ih];
-      a[il] = i < 16u ? v : x;
-      b[ih] = i < 16u ? y : v;
-    }
-  }
 };
 
 // compile-time loop over the dword indices of a row
@@ -277,33 +276,26 @@ __device__ __forceinline__ u32 kth_set_bit_wave(u32 lo, u32 hi, u32 k)
   return (u32)__ffsll((long long)hit) - 1u;
 }
 
-// Remove chunk c (wave-uniform) from a lane-major register row: 64-bit word w = c>>6
-// lives in lane w/NW, its dword (c>>5)&1 at vector index 2*(w%NW) + ((c>>5)&1).
-template <int NW, class RT>
-__device__ __forceinline__ void clear_chunk(typename RT::A &na, typename RT::B &nb, u32 c, int lane)
-{
-  const u32 w = c >> 6;
-  const u32 ln = w / (u32)NW;
-  const u32 dw = (w - ln * (u32)NW) * 2u + ((c >> 5) & 1u);
-  const u32 old = RT::at(na, nb, dw);
-  RT::put(na, nb, dw, ((u32)lane == ln) ? (old & ~(1u << (c & 31u))) : old);
-}
-
 // Algorithm 1 for ONE destination d at TEN span `event` (time t), run by one wavefront.
 // Returns (per lane) the earliest end time among the transfers in flight on the links
 // this lane looked at; the caller min-reduces it.
+//
+// The destination's `need` row (chunks it neither holds nor is receiving) lives in LDS:
+// one 1-KiB slab per piece, 16 bytes per lane, conflict-free ds_read_b128; need_lds
+// points at this wavefront's private NP*64 uint4.  Source rows land in two register
+// buffers used in turn, so that the next link's row is in flight while the current link
+// is decided; the candidate set is formed in place in the buffer.
 template <int NP>
 __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 event, u64 t,
-                                                 u32 *__restrict__ sched_row, int lane)
+                                                     u32 *__restrict__ sched_row, int lane, uint4 *need_lds)
 {
-  constexpr int NW = 2 * NP;   // 64-bit words of a row held by one lane
-  constexpr int NDW = 4 * NP;  // dwords
+  constexpr int NW = 2 * NP;
+  constexpr int NDW = 4 * NP;
   typedef RowRegs<NDW> RT;
   Ctl *ctl = p.ctl;
   const u32 jb = p.in_ptr[d], je = p.in_ptr[d + 1];
   u64 my_min = kInf;
 
-  // incoming links of d, one per lane (batches of 64 for in-degree > 64)
   u32 l0 = 0, s0 = 0, cr0 = kNone;
   u64 cs0 = 0;
   if (jb + lane < je) {
@@ -316,33 +308,36 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
     any_idle = __ballot(j < je && p.carry[p.in_link[j < je ? j : jb]] == kNone) != 0ull;
   }
 
-  typename RT::A need_a;
-  typename RT::B need_b;
   bool need_any = false;
   if (any_idle) {
-    // need = ~held[d] & ~inflight[d]; inflight[d] = the chunks on d's busy incoming links
+    // need = ~held[d] & ~inflight[d], written to LDS; inflight[d] = the chunks on d's
+    // busy incoming links, cleared by single-lane read-modify-writes
     const uint4 *hp = reinterpret_cast<const uint4 *>(p.held + (u64)d * p.row_words) + lane;
-    static_for<0, NP>([&](auto I) {
-      constexpr int i = decltype(I)::value;
-      const uint4 v = hp[i * 64];
-      RT::template set<4 * i>(need_a, need_b, ~v.x); RT::template set<4 * i + 1>(need_a, need_b, ~v.y);
-      RT::template set<4 * i + 2>(need_a, need_b, ~v.z); RT::template set<4 * i + 3>(need_a, need_b, ~v.w);
-    });
+    u32 acc = 0;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      uint4 v = hp[i * 64];
+      v.x = ~v.x; v.y = ~v.y; v.z = ~v.z; v.w = ~v.w;
+      need_lds[i * 64 + lane] = v;
+      acc |= v.x | v.y | v.z | v.w;
+    }
+    need_any = __ballot(acc != 0u) != 0ull;  // before the in-flight bits are removed: a superset
     for (u32 base = jb; base < je; base += 64) {
       const u32 j = base + lane;
       u32 cr = kNone;
       if (base == jb) cr = cr0;
       else if (j < je) cr = p.carry[p.in_link[j]];
-      u64 busy = __ballot(cr != kNone);
-      while (busy) {
-        const u32 b = (u32)__ffsll((long long)busy) - 1u;
-        busy &= busy - 1ull;
-        clear_chunk<NW, RT>(need_a, need_b, read_lane(cr, b), lane);
+      const u64 busy = __ballot(cr != kNone);
+      if (busy && cr != kNone) {
+        // every busy lane clears its own link's chunk (distinct chunks; dword updates
+        // of one wavefront are applied in order by the LDS)
+        const u32 w = cr >> 6;
+        const u32 ln = w / (u32)NW;
+        const u32 iw = w - ln * (u32)NW;
+        u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(iw >> 1) * 64u + ln]) + ((iw & 1u) * 2u + ((cr >> 5) & 1u));
+        atomicAnd(ptr, ~(1u << (cr & 31u)));
       }
     }
-    u32 acc = 0;
-    static_for<0, NDW>([&](auto I) { acc |= RT::template get<decltype(I)::value>(need_a, need_b); });
-    need_any = __ballot(acc != 0u) != 0ull;
   }
 
   for (u32 base = jb; base < je; base += 64) {
@@ -354,32 +349,37 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
       l = 0; s = 0; cr = kNone; cs = 0;
       if (valid) { l = p.in_link[j]; s = p.in_src[j]; cr = p.carry[l]; cs = p.cost[l]; }
     }
-    u32 res = kNone;  // chunk matched to this lane's link in this span
+    u32 res = kNone;
     if (need_any) {
       u64 idle = __ballot(valid && cr == kNone);
       const u32 r = philox4x32_10_word0(l, event, p.phase, 0u, p.seed_lo, p.seed_hi);
-      while (idle) {
+      typename RT::A buf0_a, buf1_a;
+      typename RT::B buf0_b, buf1_b;
+      auto fetch = [&](typename RT::A &ba, typename RT::B &bb, u64 pending) {
+        const u32 src = read_lane(s, (u32)__ffsll((long long)pending) - 1u);
+        const uint4 *sp = reinterpret_cast<const uint4 *>(p.held + (u64)src * p.row_words) + lane;
+        static_for<0, NP>([&](auto I) {
+          constexpr int i = decltype(I)::value;
+          const uint4 v = sp[i * 64];
+          RT::template set<4 * i>(ba, bb, v.x); RT::template set<4 * i + 1>(ba, bb, v.y);
+          RT::template set<4 * i + 2>(ba, bb, v.z); RT::template set<4 * i + 3>(ba, bb, v.w);
+        });
+      };
+      auto decide = [&](typename RT::A &ca, typename RT::B &cb, typename RT::A &na, typename RT::B &nb) {
         const u32 b = (u32)__ffsll((long long)idle) - 1u;
         idle &= idle - 1ull;
-        const u32 src = read_lane(s, b);
-        const uint4 *sp = reinterpret_cast<const uint4 *>(p.held + (u64)src * p.row_words) + lane;
-        uint4 row[NP];
-#pragma unroll
-        for (int i = 0; i < NP; ++i) row[i] = sp[i * 64];
-        // cand = held[src] & need, with the running in-lane candidate count after each
-        // 64-bit word (pre[i] = candidates in words 0..i of this lane)
-        typename RT::A cand_a;
-        typename RT::B cand_b;
+        // cand = held[src] & need in place, with the running in-lane candidate counts
         u32 pre[NW];
         u32 cnt = 0;
         static_for<0, NP>([&](auto I) {
           constexpr int i = decltype(I)::value;
-          const u32 c0 = row[i].x & RT::template get<4 * i>(need_a, need_b);
-          const u32 c1 = row[i].y & RT::template get<4 * i + 1>(need_a, need_b);
-          const u32 c2 = row[i].z & RT::template get<4 * i + 2>(need_a, need_b);
-          const u32 c3 = row[i].w & RT::template get<4 * i + 3>(need_a, need_b);
-          RT::template set<4 * i>(cand_a, cand_b, c0); RT::template set<4 * i + 1>(cand_a, cand_b, c1);
-          RT::template set<4 * i + 2>(cand_a, cand_b, c2); RT::template set<4 * i + 3>(cand_a, cand_b, c3);
+          const uint4 nd = need_lds[i * 64 + lane];
+          const u32 c0 = RT::template get<4 * i>(ca, cb) & nd.x;
+          const u32 c1 = RT::template get<4 * i + 1>(ca, cb) & nd.y;
+          const u32 c2 = RT::template get<4 * i + 2>(ca, cb) & nd.z;
+          const u32 c3 = RT::template get<4 * i + 3>(ca, cb) & nd.w;
+          RT::template set<4 * i>(ca, cb, c0); RT::template set<4 * i + 1>(ca, cb, c1);
+          RT::template set<4 * i + 2>(ca, cb, c2); RT::template set<4 * i + 3>(ca, cb, c3);
           cnt = popc_acc(c0, cnt);
           cnt = popc_acc(c1, cnt);
           pre[2 * i] = cnt;
@@ -387,17 +387,17 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
           cnt = popc_acc(c3, cnt);
           pre[2 * i + 1] = cnt;
         });
+        // pin the candidate computation ahead of the next row's loads: it waits for THIS
+        // row only, and the next row's latency hides behind the selection below
+        asm volatile("" ::"v"(cnt));
+        if (idle) fetch(na, nb, idle);
         const u32 incl = wave_inclusive_scan(cnt);
         const u32 pop = read_lane(incl, 63);
-        if (pop != 0) {  // else nothing this link could carry: no draw is consumed
+        if (pop != 0) {
           u32 k = read_lane(r, b) % pop;
-          // owning lane = first lane whose inclusive count exceeds k
           const u64 above = __ballot(incl > k);
           const u32 ln = (u32)__ffsll((long long)above) - 1u;
           k -= read_lane(incl - cnt, ln);
-          // owning 64-bit word inside that lane: the number of words whose inclusive count
-          // is <= k, and the largest such count (pre is non-decreasing).  Counts are far
-          // below 2^31, so "pi <= k" is the complement of the sign bit of k - pi.
           u32 idx = 0, before = 0;
 #pragma unroll
           for (int i = 0; i < NW - 1; ++i) {
@@ -407,19 +407,29 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
             const u32 cand_before = pi * le;
             before = cand_before > before ? cand_before : before;
           }
-          const u32 lo = read_lane(RT::at(cand_a, cand_b, 2u * idx), ln);
-          const u32 hi = read_lane(RT::at(cand_a, cand_b, 2u * idx + 1u), ln);
+          const u32 lo = read_lane(RT::at(ca, cb, 2u * idx), ln);
+          const u32 hi = read_lane(RT::at(ca, cb, 2u * idx + 1u), ln);
           const u32 bit = kth_set_bit_wave(lo, hi, k - before);
           const u32 chunk = ((ln * (u32)NW + idx) << 6) + bit;
-          clear_chunk<NW, RT>(need_a, need_b, chunk, lane);  // now in flight to d
+          // now in flight to d: one lane removes it from the LDS row
+          if (lane == 0) {
+            u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(idx >> 1) * 64u + ln]) + ((idx & 1u) * 2u + (bit >> 5));
+            *ptr &= ~(1u << (bit & 31u));
+          }
           if ((u32)lane == b) res = chunk;
         }
+      };
+      if (idle) fetch(buf0_a, buf0_b, idle);
+      while (idle) {
+        decide(buf0_a, buf0_b, buf1_a, buf1_b);
+        if (!idle) break;
+        decide(buf1_a, buf1_b, buf0_a, buf0_b);
       }
     }
     if (valid) {
       if (sched_row) sched_row[l] = res;
       if (res != kNone) {
-        if (res >= p.C) {  // cannot happen; never let a bad id reach the arrival kernel
+        if (res >= p.C) {
           ctl->status = kStInternal;
           ctl->done = 1u;
         } else if (cs > kInf - 1ull - t) {
@@ -461,7 +471,8 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
     if (d == 0 && lane == 0) { ctl->T = t; ctl->n_events = event; ctl->done = 1u; }
     return;
   }
-  const u64 my_min = match_destination<NP>(p, d, event, t, sched_row, lane);
+  __shared__ uint4 need_lds[4 * NP * 64];
+  const u64 my_min = match_destination<NP>(p, d, event, t, sched_row, lane, need_lds + (threadIdx.x >> 6) * NP * 64);
 
   // a8: next span = earliest end of a transfer in flight (min over all destinations)
   const u64 m = wave_min64(my_min);
@@ -517,6 +528,7 @@ __global__ __launch_bounds__(256) void sweep_kernel(PassDev p, u32 first_event, 
 {
   __shared__ u64 wave_min[4];
   __shared__ u32 wave_cnt[4];
+  __shared__ uint4 need_lds[4 * NP * 64];
   const int lane = threadIdx.x & 63;
   const u32 wave = threadIdx.x >> 6;
   Ctl *ctl = p.ctl;
@@ -567,7 +579,8 @@ __global__ __launch_bounds__(256) void sweep_kernel(PassDev p, u32 first_event, 
     for (u32 q = rank_in_xcd; q < per_xcd_pos; q += per_xcd_blocks) {
       const u32 slot = uniform((xcd * per_xcd_pos + q) * 4u + wave);
       if (slot < p.N) {
-        const u64 m = match_destination<NP>(p, uniform(p.order[slot]), e, t, p.reversed ? nullptr : row, lane);
+        const u64 m = match_destination<NP>(p, uniform(p.order[slot]), e, t, p.reversed ? nullptr : row, lane,
+                                           need_lds + wave * NP * 64);
         my_min = m < my_min ? m : my_min;
       }
     }
@@ -639,6 +652,19 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const u32 *__restrict__ 
     atomicAdd(&row_count[row], n);
     atomicAdd(digest, dg);
   }
+}
+
+// grid = (ceil(L/256), ceil(n_rows/64)): a thread sums 64 rows of one schedule column
+__global__ __launch_bounds__(256) void link_count_kernel(const u32 *__restrict__ rows, u32 n_rows, u32 L,
+                                                         u64 *__restrict__ counts)
+{
+  const u32 l = blockIdx.x * 256u + threadIdx.x;
+  if (l >= L) return;
+  const u32 r0 = blockIdx.y * 64u;
+  const u32 r1 = r0 + 64u < n_rows ? r0 + 64u : n_rows;
+  u32 n = 0;
+  for (u32 r = r0; r < r1; ++r) n += rows[(u64)r * L + l] != kNone ? 1u : 0u;
+  if (n) atomicAdd(&counts[l], (u64)n);
 }
 
 }  // namespace
@@ -731,6 +757,17 @@ u32 sweep_max_blocks(u32 NP)
     case 7: return sweep_blocks_np<7>();
     case 8: return sweep_blocks_np<8>();
     default: return 0;
+  }
+}
+
+void launch_link_counts(const u32 *rows, u32 n_rows, u32 L, u64 *counts, hipStream_t s)
+{
+  if (n_rows == 0 || L == 0) return;
+  // at most 65535 row blocks per launch (grid.y limit)
+  for (u32 r0 = 0; r0 < n_rows; r0 += 65535u * 64u) {
+    const u32 nr = n_rows - r0 < 65535u * 64u ? n_rows - r0 : 65535u * 64u;
+    hipLaunchKernelGGL(link_count_kernel, dim3((L + 255) / 256, (nr + 63) / 64), dim3(256), 0, s,
+                       rows + (u64)r0 * L, nr, L, counts);
   }
 }
 

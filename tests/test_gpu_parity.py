@@ -329,3 +329,15 @@ def test_scalability_workloads_prefix_bit_exact(idx, n_ev, stream):
         for first in range(0, n, step):
             cnt = min(step, n - first)
             assert np.array_equal(r.read(first, cnt), ref.xfers[first:first + cnt]), first
+
+
+def test_link_counts_match_oracle_records(stream):
+    """tacos_result_link_counts (device column sums of the schedule) against a bincount of
+    the oracle's records, per pass of an All-Reduce."""
+    topo = T.grid([4, 3, 3], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000])
+    ref = cpu(topo, 2, MiB, T.ALL_REDUCE, 9)
+    n = len(ref.xfers) // 2
+    with gpu(topo, 2, MiB, T.ALL_REDUCE, 9, stream) as r:
+        for p, part in enumerate((ref.xfers[:n], ref.xfers[n:])):
+            want = np.bincount(part["link"].astype(np.int64), minlength=topo.n_links)
+            assert np.array_equal(r.link_counts(p, topo.n_links), want.astype(np.uint64))
