@@ -310,3 +310,37 @@ def _strong(n, edges):
         fw[s].append(d)
         bw[d].append(s)
     return reach(fw) and reach(bw)
+
+
+# ------------------------------------------------------------------ Philox in python
+
+def philox4x32_10(ctr, key):
+    """Philox4x32-10 of Salmon et al. (SC'11) on python integers.  Test-side only; it is
+    itself checked against the published known-answer vectors before it is used to pin
+    the counter/key layout of the deterministic choice."""
+    M0, M1, W0, W1, MASK = 0xD2511F53, 0xCD9E8D57, 0x9E3779B9, 0xBB67AE85, 0xFFFFFFFF
+    c0, c1, c2, c3 = [int(x) & MASK for x in ctr]
+    k0, k1 = [int(x) & MASK for x in key]
+    for _ in range(10):
+        p0, p1 = M0 * c0, M1 * c2
+        c0, c1, c2, c3 = ((p1 >> 32) ^ c1 ^ k0) & MASK, p1 & MASK, ((p0 >> 32) ^ c3 ^ k1) & MASK, p0 & MASK
+        k0, k1 = (k0 + W0) & MASK, (k1 + W1) & MASK
+    return (c0, c1, c2, c3)
+
+
+def two_npu_all_gather(cpn, seed, phase=0):
+    """Exact expected schedule of the forward pass on the 2-NPU topology with unit-cost
+    links 0 -> 1 (id 0) and 1 -> 0 (id 1): every span each link sends the
+    (Philox(link, span, phase, 0; seed)[0] mod p)-th smallest of the p chunks its source
+    owns and has not sent yet.  Returns [(t, link, chunk)]."""
+    key = (seed & 0xFFFFFFFF, seed >> 32)
+    left = {0: list(range(0, cpn)), 1: list(range(cpn, 2 * cpn))}  # by link = by source
+    out = []
+    for span in range(cpn):
+        for link in (0, 1):
+            cand = left[link]
+            r = philox4x32_10((link, span, phase, 0), key)[0]
+            c = cand[r % len(cand)]
+            cand.remove(c)
+            out.append((span, link, c))
+    return out

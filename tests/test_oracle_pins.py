@@ -64,6 +64,60 @@ def test_digest_matches_numpy_retyping():
     assert oracle.mix(1, 0, 0) != oracle.mix(0, 1, 0) != oracle.mix(0, 0, 1)
 
 
+@pytest.mark.parametrize("cpn", [5, 7, 100, 200])
+def test_selection_rule_against_published_philox_vector(cpn):
+    """The deterministic choice itself: link 0 at span 0 of a forward pass with seed 0
+    draws Philox4x32-10(counter 0, key 0), whose first word 0x6627e8d5 is a published
+    known answer.  On 0 -> 1 with NPU 0 holding chunks 0..cpn-1 the candidates are exactly
+    those chunks, so the link must carry chunk number 0x6627e8d5 mod cpn (the k-th
+    SMALLEST chunk id, 0-based; 200 chunks span four 64-bit words)."""
+    topo = T.from_edge_list(2, [(0, 1, 1, 0), (1, 0, 1, 0)])
+    r = run(topo, cpn=cpn, chunk_bytes=1, seed=0)
+    first = r.xfers[0]
+    assert (int(first["t_ps"]), int(first["link"]), int(first["src"]), int(first["dst"])) == (0, 0, 0, 1)
+    assert int(first["chunk"]) == 0x6627E8D5 % cpn
+
+
+def test_python_philox_known_answers():
+    with open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            v = [int(x, 16) for x in line.split()]
+            assert checker.philox4x32_10(v[0:4], v[4:6]) == tuple(v[6:10])
+
+
+@pytest.mark.parametrize("cpn,seed", [(9, 0x0123456789ABCDEF), (70, 7)])
+def test_two_npu_exact_replay_pins_counter_and_key_layout(cpn, seed):
+    """Two NPUs, unit-cost links 0 -> 1 and 1 -> 0: the whole schedule follows from the
+    rule alone (counter = (link, span, phase, 0), key = (seed low, seed high), r mod p,
+    k-th smallest remaining chunk), replayed in python with a Philox that is pinned to
+    the published vectors.  Forward pass (phase 0) and the reversed pass of a
+    Reduce-Scatter (phase 1, links used backwards, schedule reversed in time)."""
+    topo = T.from_edge_list(2, [(0, 1, 1, 0), (1, 0, 1, 0)])
+    r = run(topo, cpn=cpn, chunk_bytes=1, seed=seed)
+    want = checker.two_npu_all_gather(cpn, seed, phase=0)
+    got = [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in r.xfers]
+    assert got == want and r.collective_time_ps == cpn
+    # Reduce-Scatter: link 0 (0 -> 1) is used as 1 -> 0 in the reversed pass, so it carries
+    # the chunks NPU 1 owns; a transfer of the reversed pass at span t' is the
+    # Reduce-Scatter transfer at T - t' - 1 on the original link
+    rs = run(topo, cpn=cpn, chunk_bytes=1, coll=T.REDUCE_SCATTER, seed=seed)
+    key = (seed & 0xFFFFFFFF, seed >> 32)
+    left = {0: list(range(cpn, 2 * cpn)), 1: list(range(0, cpn))}
+    want_rs = []
+    for span in range(cpn):
+        for link in (0, 1):
+            cand = left[link]
+            c = cand[checker.philox4x32_10((link, span, 1, 0), key)[0] % len(cand)]
+            cand.remove(c)
+            want_rs.append((cpn - span - 1, link, c))
+    want_rs.sort()
+    got_rs = [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in rs.xfers]
+    assert got_rs == want_rs
+    assert [(int(x["src"]), int(x["dst"])) for x in rs.xfers if int(x["link"]) == 0][0] == (0, 1)
+
+
 # ------------------------------------------------------------------ closed forms
 
 @pytest.mark.parametrize("n", [2, 3, 4, 8, 13])
