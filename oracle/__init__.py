@@ -67,7 +67,7 @@ def lib() -> ctypes.CDLL:
         L.orc_synthesize.argtypes = [
             ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
-            ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,
+            ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.POINTER(ctypes.POINTER(_CResult))]
         L.orc_result_free.restype = None
         L.orc_result_free.argtypes = [ctypes.POINTER(_CResult)]
@@ -129,7 +129,7 @@ def max_threads() -> int:
 def synthesize(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_per_npu, chunk_bytes,
                collective, seed, max_events: int = 0, keep_first: int = 0,
                keep_xfers: int = (1 << 64) - 1, n_threads: int = 1,
-               link_order: int = 0) -> OracleResult:
+               link_order: int = 0, matching: int = 0) -> OracleResult:
     rp = np.ascontiguousarray(row_ptr, dtype=np.uint32)
     ci = np.ascontiguousarray(col_idx, dtype=np.uint32)
     al = np.ascontiguousarray(alpha_ps, dtype=np.uint64)
@@ -138,7 +138,8 @@ def synthesize(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_per_npu
     rc = lib().orc_synthesize(int(n_npus), rp.ctypes.data, ci.ctypes.data, al.ctypes.data,
                               be.ctypes.data, int(chunks_per_npu), int(chunk_bytes),
                               int(collective), int(seed), int(max_events), int(keep_first),
-                              int(keep_xfers), int(n_threads), int(link_order), ctypes.byref(res))
+                              int(keep_xfers), int(n_threads), int(link_order), int(matching),
+                              ctypes.byref(res))
     if rc != OK:
         raise OracleError(rc)
     try:

@@ -105,6 +105,19 @@ static uint32_t draw(uint64_t seed, uint32_t link, uint32_t event, uint32_t phas
   return out[0];
 }
 
+/* The two random words of step i of destination d in the postcondition-centric
+ * matching: word 0 picks the chunk, word 1 the source link. */
+static void draw_pair(uint64_t seed, uint32_t d, uint32_t event, uint32_t phase, uint32_t i,
+                      uint32_t *r_chunk, uint32_t *r_link)
+{
+  uint32_t ctr[4] = { d, event, phase + 2u, i };
+  uint32_t key[2] = { (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32) };
+  uint32_t out[4];
+  orc_philox4x32_10(ctr, key, out);
+  *r_chunk = out[0];
+  *r_link = out[1];
+}
+
 /* ------------------------------------------------------------------------ digest */
 /* Order-independent schedule digest: every record contributes a 64-bit mix of its
  * start time, link id and chunk id; contributions add modulo 2^64. */
@@ -207,7 +220,7 @@ static uint32_t kth_bit(uint64_t w, uint32_t k)
  */
 static int ag_pass(uint32_t N, uint32_t L, const uint32_t *psrc, const uint32_t *pdst,
                    const uint64_t *cost, uint32_t cpn, uint64_t seed, uint32_t phase,
-                   uint64_t max_events, int n_threads, int link_order,
+                   uint64_t max_events, int n_threads, int link_order, int matching,
                    pass_out_t *out, uint64_t *T, uint64_t *n_events, int *complete)
 {
   const uint64_t C = (uint64_t)N * cpn;
@@ -284,6 +297,59 @@ static int ag_pass(uint32_t N, uint32_t L, const uint32_t *psrc, const uint32_t 
     for (uint32_t d = 0; d < N; ++d) {
       const uint64_t *hd = held + (size_t)d * W;
       uint64_t *fd = inflight + (size_t)d * W;
+      if (matching == 1) {
+        /* Algorithm 1 as printed: unsatisfied postconditions (d, c) are visited in random
+         * order, each is given a random in-neighbour that holds c and whose link is free.
+         * Visiting a uniformly shuffled list and skipping the pairs no free link can
+         * serve is the same as repeatedly drawing a chunk uniformly from the servable
+         * ones (links are only ever used up), which is what is done here, with the draws
+         * fixed by Philox(d, event, phase + 2, step). */
+        for (uint32_t step = 0;; ++step) {
+          uint64_t p = 0;
+          for (uint64_t w = 0; w < W; ++w) {
+            uint64_t any = 0;
+            for (uint32_t j = in_ptr[d]; j < in_ptr[d + 1]; ++j) {
+              uint32_t l = in_link[j];
+              if (carry[l] == ORC_NONE && fresh[l] == ORC_NONE) any |= held[(size_t)psrc[l] * W + w];
+            }
+            p += (uint64_t)__builtin_popcountll(any & ~hd[w] & ~fd[w]);
+          }
+          attempts_d[d]++;
+          if (p == 0) break;                 /* no free link can serve any missing chunk */
+          uint32_t r_chunk, r_link;
+          draw_pair(seed, d, (uint32_t)event, phase, step, &r_chunk, &r_link);
+          uint32_t k = r_chunk % (uint32_t)p, c = ORC_NONE;
+          for (uint64_t w = 0; w < W && c == ORC_NONE; ++w) {
+            uint64_t any = 0;
+            for (uint32_t j = in_ptr[d]; j < in_ptr[d + 1]; ++j) {
+              uint32_t l = in_link[j];
+              if (carry[l] == ORC_NONE && fresh[l] == ORC_NONE) any |= held[(size_t)psrc[l] * W + w];
+            }
+            uint64_t serv = any & ~hd[w] & ~fd[w];
+            uint32_t pc = (uint32_t)__builtin_popcountll(serv);
+            if (k < pc) c = (uint32_t)(w * 64) + kth_bit(serv, k);
+            else k -= pc;
+          }
+          /* the free links whose source holds c, in list order (ascending link id, or
+           * cheapest first); a random one, or with link_order 1 the cheapest */
+          uint32_t n_hold = 0;
+          for (uint32_t j = in_ptr[d]; j < in_ptr[d + 1]; ++j) {
+            uint32_t l = in_link[j];
+            if (carry[l] == ORC_NONE && fresh[l] == ORC_NONE &&
+                (held[(size_t)psrc[l] * W + (c >> 6)] >> (c & 63) & 1ull)) n_hold++;
+          }
+          uint32_t pick = (link_order == 1) ? 0u : r_link % n_hold;
+          for (uint32_t j = in_ptr[d]; j < in_ptr[d + 1]; ++j) {
+            uint32_t l = in_link[j];
+            if (carry[l] == ORC_NONE && fresh[l] == ORC_NONE &&
+                (held[(size_t)psrc[l] * W + (c >> 6)] >> (c & 63) & 1ull)) {
+              if (pick == 0) { fresh[l] = c; fd[c >> 6] |= 1ull << (c & 63); break; }
+              pick--;
+            }
+          }
+        }
+        continue;
+      }
       for (uint32_t j = in_ptr[d]; j < in_ptr[d + 1]; ++j) {
         uint32_t l = in_link[j];
         if (carry[l] != ORC_NONE) continue;            /* link busy */
@@ -372,12 +438,15 @@ static void pass_out_free(pass_out_t *o) { free(o->rec); free(o->ev_time); free(
  *   link_order : 0 = a destination's incoming links are tried in ascending link id;
  *                1 = cheapest link first, ties by link id (the paper's "Prioritizing
  *                Lower-cost Links").  The random draw of a link does not depend on it.
+ *   matching   : 0 = link-centric (every idle link draws a chunk); 1 = Algorithm 1 as
+ *                printed, postcondition-centric (every missing chunk draws a source
+ *                link); see the comment in ag_pass.
  */
 int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col_idx,
                    const uint64_t *alpha_ps, const uint64_t *beta_fs_per_B,
                    uint32_t chunks_per_npu, uint64_t chunk_bytes, int collective,
                    uint64_t seed, uint64_t max_events, uint64_t keep_first,
-                   uint64_t keep_xfers, int n_threads, int link_order,
+                   uint64_t keep_xfers, int n_threads, int link_order, int matching,
                    orc_result_t **result)
 {
   if (!row_ptr || !result || n_npus == 0 || chunks_per_npu == 0 || chunk_bytes == 0)
@@ -392,6 +461,7 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
   if ((uint64_t)n_npus * chunks_per_npu >= 0xFFFFFFFFull) return ORC_E_INVAL;
   if (n_threads < 1) n_threads = 1;
   if (link_order != 0 && link_order != 1) return ORC_E_INVAL;
+  if (matching != 0 && matching != 1) return ORC_E_INVAL;
 
   int rc = ORC_OK;
   uint32_t *src = (uint32_t *)malloc((L ? L : 1) * sizeof(uint32_t));
@@ -420,7 +490,7 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
     o->keep_limit = ~0ull;
     uint64_t T = 0, ne = 0; int complete = 0;
     rc = ag_pass(n_npus, L, col_idx, src, cost, chunks_per_npu, seed, 1u, max_events,
-                 n_threads, link_order, o, &T, &ne, &complete);
+                 n_threads, link_order, matching, o, &T, &ne, &complete);
     if (rc != ORC_OK) goto fail;
     complete_all &= complete;
     res->pass_time_ps[n_pass] = T; res->pass_events[n_pass] = ne;
@@ -433,7 +503,7 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
     o->fwd = 1; o->t_off = t_off;
     uint64_t T = 0, ne = 0; int complete = 0;
     rc = ag_pass(n_npus, L, src, col_idx, cost, chunks_per_npu, seed, 0u, max_events,
-                 n_threads, link_order, o, &T, &ne, &complete);
+                 n_threads, link_order, matching, o, &T, &ne, &complete);
     if (rc != ORC_OK) goto fail;
     complete_all &= complete;
     res->pass_time_ps[n_pass] = T; res->pass_events[n_pass] = ne;

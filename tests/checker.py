@@ -344,3 +344,57 @@ def two_npu_all_gather(cpn, seed, phase=0):
             cand.remove(c)
             out.append((span, link, c))
     return out
+
+
+def alg1_postcondition_centric(n_npus, link_src, link_dst, cost, cpn, seed, phase=0, cheapest_first=False):
+    """Second, set-based implementation (python, small inputs) of the postcondition-
+    centric matching: per destination, repeatedly draw a servable missing chunk with
+    Philox(d, span, phase+2, step)[0] and a free holder link with word [1] (or the
+    cheapest).  Returns ([(t, link, chunk)], collective_time).  It is a cross-check of the
+    C oracle's word/bit handling, written independently; the pins proper are the
+    validity checker, the closed forms and the brute force."""
+    N, L = int(n_npus), len(link_src)
+    C = N * cpn
+    key = (seed & 0xFFFFFFFF, seed >> 32)
+    held = [set(range(i * cpn, (i + 1) * cpn)) for i in range(N)]
+    inflight = [set() for _ in range(N)]
+    carry = [None] * L
+    free_at = [0] * L
+    in_links = [[l for l in range(L) if link_dst[l] == d] for d in range(N)]
+    if cheapest_first:
+        in_links = [sorted(ls, key=lambda l: (cost[l], l)) for ls in in_links]
+    remaining = N * C - C
+    t, span, out = 0, 0, []
+    while True:
+        for l in range(L):
+            if carry[l] is not None and free_at[l] == t:
+                d = link_dst[l]
+                held[d].add(carry[l]); inflight[d].discard(carry[l]); carry[l] = None; remaining -= 1
+        if remaining == 0:
+            return sorted(out), t
+        new = {}
+        for d in range(N):
+            free = [l for l in in_links[d] if carry[l] is None]
+            step = 0
+            while True:
+                serv = set()
+                for l in free:
+                    serv |= held[link_src[l]]
+                serv -= held[d]
+                serv -= inflight[d]
+                if not serv:
+                    break
+                r = philox4x32_10((d, span, phase + 2, step), key)
+                c = sorted(serv)[r[0] % len(serv)]
+                holders = [l for l in free if c in held[link_src[l]]]
+                l = holders[0] if cheapest_first else holders[r[1] % len(holders)]
+                new[l] = c
+                inflight[d].add(c)
+                free.remove(l)
+                step += 1
+        for l, c in new.items():
+            carry[l] = c; free_at[l] = t + cost[l]; out.append((t, l, c))
+        nxt = [free_at[l] for l in range(L) if carry[l] is not None]
+        assert nxt, "unreachable"
+        t = min(nxt)
+        span += 1

@@ -74,14 +74,14 @@ def _build(name):
     return lib
 
 
-def _run(lib, topo, cpn=1, cb=MiB, coll=0, seed=0, link_order=0):
+def _run(lib, topo, cpn=1, cb=MiB, coll=0, seed=0, link_order=0, matching=0):
     res = ctypes.POINTER(oracle._CResult)()
     rp = np.ascontiguousarray(topo.row_ptr, dtype=np.uint32)
     ci = np.ascontiguousarray(topo.col_idx, dtype=np.uint32)
     al = np.ascontiguousarray(topo.alpha_ps, dtype=np.uint64)
     be = np.ascontiguousarray(topo.beta_fs_per_B, dtype=np.uint64)
     rc = lib.orc_synthesize(topo.n_npus, rp.ctypes.data, ci.ctypes.data, al.ctypes.data, be.ctypes.data,
-                            cpn, cb, coll, seed, 0, 0, (1 << 64) - 1, 1, link_order, ctypes.byref(res))
+                            cpn, cb, coll, seed, 0, 0, (1 << 64) - 1, 1, link_order, matching, ctypes.byref(res))
     if rc != 0:
         raise RuntimeError(f"rc={rc}")
     r = res.contents

@@ -404,3 +404,62 @@ def test_lower_cost_link_priority_valid_and_neutral_when_homogeneous():
                                  r.collective_time_ps, check_maximal=True)
     rs = run(het, cpn=1, coll=T.REDUCE_SCATTER, seed=4, link_order=1)
     checker.check_reduce_scatter(27, het.link_src, het.link_dst, cost, 1, rs.xfers, rs.collective_time_ps)
+
+
+# ------------------------------------------------------------------ Algorithm 1 as printed
+
+@pytest.mark.parametrize("name,mk,cpn", CASES, ids=[c[0] for c in CASES])
+def test_postcondition_centric_matching_valid_maximal_and_bounded(name, mk, cpn):
+    """matching = 1 (Algorithm 1's own order: missing chunks draw source links): same
+    validity, maximality and lower bounds as the link-centric form."""
+    topo = mk()
+    cb = 64 << 10
+    cost = costs(topo, cb)
+    for lo in (0, 1):
+        r = run(topo, cpn=cpn, chunk_bytes=cb, seed=5, matching=1, link_order=lo)
+        Tend = checker.check_all_gather(topo.n_npus, topo.link_src, topo.link_dst, cost, cpn,
+                                        r.xfers, r.collective_time_ps, check_maximal=True)
+        assert Tend >= checker.ingress_lower_bound(topo.n_npus, topo.link_dst, cost, cpn)
+        assert Tend >= checker.diameter_lower_bound(topo.n_npus, topo.link_src, topo.link_dst, cost)
+
+
+def test_postcondition_centric_closed_forms():
+    for n in (3, 8):
+        r = run(T.ring(n), seed=n, matching=1)
+        assert r.n_events == n - 1 and r.collective_time_ps == (n - 1) * 21_471_520
+        r = run(T.fully_connected(n), seed=n, matching=1)
+        assert r.n_events == 1 and np.array_equal(r.xfers["chunk"], r.xfers["src"])
+        r = run(T.ring(n, bidirectional=True), seed=n, matching=1)
+        assert r.n_events == n // 2
+
+
+def test_postcondition_centric_bruteforce_n4():
+    graphs = checker.strongly_connected_digraphs(4)
+    for edges in graphs[::7]:
+        opt = checker.optimal_steps_unit(4, edges)
+        topo = _topo_from_edges(4, edges)
+        for seed in range(2):
+            r = run(topo, chunk_bytes=1, seed=seed, matching=1)
+            assert opt <= r.n_events <= opt + 1, (edges, opt, r.n_events)
+
+
+@pytest.mark.parametrize("lo", [0, 1])
+def test_postcondition_centric_against_set_based_implementation(lo):
+    """Cross-check of the C oracle's bit handling with the independent set-based python
+    implementation (same rule, same Philox counters) on small inputs, All-Gather and
+    the reversed pass of a Reduce-Scatter."""
+    for topo, cpn, seed in ((T.mesh2d(3, 3), 2, 1), (T.random_regular_out(10, 3, seed=5)[0], 3, 0xABCDEF0123),
+                            (T.grid([2, 3], True, [300_000, 700_000], [5_000, 20_000]), 2, 9)):
+        cb = 32 << 10
+        cost = costs(topo, cb)
+        r = run(topo, cpn=cpn, chunk_bytes=cb, seed=seed, matching=1, link_order=lo)
+        want, Tw = checker.alg1_postcondition_centric(topo.n_npus, topo.link_src.tolist(), topo.link_dst.tolist(),
+                                                      cost, cpn, seed, 0, cheapest_first=bool(lo))
+        got = [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in r.xfers]
+        assert got == want and r.collective_time_ps == Tw
+        rs = run(topo, cpn=cpn, chunk_bytes=cb, coll=T.REDUCE_SCATTER, seed=seed, matching=1, link_order=lo)
+        rev, Tr = checker.alg1_postcondition_centric(topo.n_npus, topo.link_dst.tolist(), topo.link_src.tolist(),
+                                                     cost, cpn, seed, 1, cheapest_first=bool(lo))
+        want_rs = sorted((Tr - t - cost[l], l, c) for (t, l, c) in rev)
+        got_rs = [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in rs.xfers]
+        assert got_rs == want_rs and rs.collective_time_ps == Tr
