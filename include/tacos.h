@@ -82,6 +82,10 @@ typedef enum {
 #define TACOS_LINK_ORDER_ID   0u
 #define TACOS_LINK_ORDER_COST 1u
 
+/* tacos_options_t::matching */
+#define TACOS_MATCH_LINK_CENTRIC  0u
+#define TACOS_MATCH_POSTCONDITION 1u
+
 /* Largest supported number of chunks N*chunks_per_npu (one wavefront keeps a
  * destination's whole "still needed" bitset in registers). */
 #define TACOS_MAX_CHUNKS 65536u
@@ -125,7 +129,19 @@ typedef struct {
                              0 = ascending link id; 1 = cheapest link first, ties by link id
                              (paper, "Prioritizing Lower-cost Links").  The random draw of a
                              link does not depend on the order.                              */
-  uint32_t reserved;      /* must be 0                                                       */
+  uint32_t matching;      /* 0 = link-centric: every idle link draws a chunk (the rule in the
+                             header comment).  1 = Algorithm 1 in the order the paper prints
+                             it, postcondition-centric: for every destination d, step by step,
+                               serv = (chunks d misses) & OR over d's FREE incoming links of
+                                      held[src];  stop when serv is empty;
+                               (r0, r1) = words 0, 1 of Philox4x32-10(counter = (d, event,
+                                      phase + 2, step), key as above);
+                               chunk c = the (r0 mod |serv|)-th smallest of serv;
+                               link = the (r1 mod n)-th of the n free links whose source
+                                      holds c, in list order (link_order 1: the cheapest);
+                             which equals visiting a shuffled list of unsatisfied (d, c)
+                             pairs and giving each a random free holder.  Needs in-degree
+                             <= 64 and launch_mode 0 (TACOS_E_INVAL otherwise).              */
 } tacos_options_t;
 
 typedef struct tacos_result tacos_result_t; /* opaque; owns device and host buffers */

@@ -185,7 +185,7 @@ std::vector<uint32_t> cluster_order(uint32_t N, uint32_t L, const std::vector<ui
 int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
              const DevBuf &d_cost, uint32_t cpn, uint64_t seed, uint32_t phase, bool reversed,
              uint64_t max_events, bool time_kernels, bool persistent, const std::vector<uint64_t> *order_cost,
-             hipStream_t stream, tacos_result &res, Pass &pass)
+             uint32_t match_mode, hipStream_t stream, tacos_result &res, Pass &pass)
 {
   const uint32_t C = N * cpn;
   const uint32_t NP = (C + 8191u) / 8192u;
@@ -324,7 +324,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
         tacos::launch_arrive(p, (uint32_t)e, tslot, reversed ? row : nullptr, stream);
         if (max_events && e >= max_events) { stopped = true; break; }
         if (time_kernels) HIP_TRY(hipEventRecord(pool.ev[2 * n_timed], stream));
-        tacos::launch_match(p, (uint32_t)e, reversed ? nullptr : row, stream);
+        tacos::launch_match(p, (uint32_t)e, reversed ? nullptr : row, match_mode, stream);
         if (time_kernels) { HIP_TRY(hipEventRecord(pool.ev[2 * n_timed + 1], stream)); n_timed++; }
         e++;
       }
@@ -478,8 +478,25 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
   if (rc != TACOS_OK) return rc;
   const uint64_t max_events = opts ? opts->max_events : 0;
   if (max_events && coll != TACOS_ALL_GATHER) return TACOS_E_INVAL;
-  if (opts && (opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 1 || opts->reserved != 0))
+  if (opts && (opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 1 ||
+               opts->matching > TACOS_MATCH_POSTCONDITION))
     return TACOS_E_INVAL;
+  // kernel variant: 0 link-centric; 1 postcondition-centric, random holder; 2 first holder
+  uint32_t match_mode = 0;
+  if (opts && opts->matching == TACOS_MATCH_POSTCONDITION) {
+    if (opts->launch_mode != 0) return TACOS_E_INVAL;
+    std::vector<uint32_t> deg_in(topo->n_npus, 0), deg_out(topo->n_npus, 0);
+    for (uint32_t i = 0; i < topo->n_npus; ++i) {
+      deg_out[i] = topo->row_ptr[i + 1] - topo->row_ptr[i];
+      for (uint32_t l = topo->row_ptr[i]; l < topo->row_ptr[i + 1]; ++l) deg_in[topo->col_idx[l]]++;
+    }
+    for (uint32_t i = 0; i < topo->n_npus; ++i) {
+      // the reversed pass of a Reduce-Scatter walks the out-links as incoming links
+      const bool fwd = coll != TACOS_REDUCE_SCATTER, rev = coll != TACOS_ALL_GATHER;
+      if ((fwd && deg_in[i] > 64) || (rev && deg_out[i] > 64)) return TACOS_E_INVAL;
+    }
+    match_mode = opts->link_order == TACOS_LINK_ORDER_COST ? 2u : 1u;
+  }
   const bool time_kernels = opts && opts->time_kernels;
   const bool persistent = opts && opts->launch_mode == 1;
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
@@ -521,7 +538,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
         // reversed pass: every link (s -> d) is used as (d -> s), ids and costs unchanged
         res->passes.emplace_back();
         rc = run_pass(N, L, res->link_dst, res->link_src, d_cost, chunks_per_npu, seed, 1u, true, 0,
-                      time_kernels, persistent, order_cost, stream, *res, res->passes.back());
+                      time_kernels, persistent, order_cost, match_mode, stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), 0, &res->digest, stream);
         t_off = res->passes.back().T;
@@ -529,7 +546,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       if (coll == TACOS_ALL_GATHER || coll == TACOS_ALL_REDUCE) {
         res->passes.emplace_back();
         rc = run_pass(N, L, res->link_src, res->link_dst, d_cost, chunks_per_npu, seed, 0u, false,
-                      max_events, time_kernels, persistent, order_cost, stream, *res, res->passes.back());
+                      max_events, time_kernels, persistent, order_cost, match_mode, stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), t_off, &res->digest, stream);
       }

@@ -73,7 +73,9 @@ void launch_arrive(const PassDev &p, uint32_t event, unsigned long long *event_t
                    uint32_t *sched_row, hipStream_t s);
 // a4-a8 (produce): termination test, matching for all destinations, min-reduction of
 // the next event time; a forward pass writes the schedule row of the event
-void launch_match(const PassDev &p, uint32_t event, uint32_t *sched_row, hipStream_t s);
+// mode 0: link-centric; 1: postcondition-centric with a random holder link; 2: postcondition-
+// centric with the first holder of the incoming list (in-degree <= 64 for modes 1, 2)
+void launch_match(const PassDev &p, uint32_t event, uint32_t *sched_row, uint32_t mode, hipStream_t s);
 // a3-a8 fused: ONE cooperative launch runs spans [first_event, first_event+n_events)
 // (arrivals, termination test, matching, next-event reduction, with two grid-wide
 // barriers per span) and returns early when the pass ends.  stop_event: the span at

@@ -450,7 +450,171 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
   return my_min;
 }
 
+// Philox4x32-10, words 0 and 1 of the output block.
+__device__ __forceinline__ void philox4x32_10_words01(u32 c0, u32 c1, u32 c2, u32 c3, u32 k0, u32 k1,
+                                                      u32 &w0, u32 &w1)
+{
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const u32 lo0 = 0xD2511F53u * c0, hi0 = __umulhi(0xD2511F53u, c0);
+    const u32 lo1 = 0xCD9E8D57u * c2, hi1 = __umulhi(0xCD9E8D57u, c2);
+    const u32 n0 = hi1 ^ c1 ^ k0;
+    const u32 n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  w0 = c0;
+  w1 = c1;
+}
+
+// Algorithm 1 in the order the paper prints it, for ONE destination d (in-degree <= 64),
+// run by one wavefront: unsatisfied postconditions (d, c) are visited in random order and
+// each is given a random in-neighbour that holds c and whose link is free.  Visiting a
+// shuffled list and skipping the pairs no free link can serve equals drawing, step by
+// step, a chunk uniformly from the servable ones (links are only used up), so each step
+//   serv = need & OR_{free links} held[src];  c = (r0 mod |serv|)-th smallest of serv;
+//   holders = free links whose source holds c (list order);  link = holders[r1 mod n]
+//   (or the first holder when the list is sorted cheapest-first),
+// with (r0, r1) = words 0, 1 of Philox(d, event, phase + 2, step; seed).  The rows of the
+// free links are re-streamed (from L2) in every step.
 template <int NP>
+__device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, u32 event, u64 t,
+                                                       u32 *__restrict__ sched_row, int lane, uint4 *need_lds,
+                                                       bool first_holder)
+{
+  constexpr int NW = 2 * NP;
+  constexpr int NDW = 4 * NP;
+  typedef RowRegs<NDW> RT;
+  Ctl *ctl = p.ctl;
+  const u32 jb = p.in_ptr[d], je = p.in_ptr[d + 1];
+  u64 my_min = kInf;
+  const bool valid = jb + lane < je;
+  u32 l = 0, s = 0, cr = kNone;
+  u64 cs = 0;
+  if (valid) { l = p.in_link[jb + lane]; s = p.in_src[jb + lane]; cr = p.carry[l]; cs = p.cost[l]; }
+  u64 free_links = __ballot(valid && cr == kNone);
+  u32 res = kNone;
+
+  if (free_links) {
+    const uint4 *hp = reinterpret_cast<const uint4 *>(p.held + (u64)d * p.row_words) + lane;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      uint4 v = hp[i * 64];
+      v.x = ~v.x; v.y = ~v.y; v.z = ~v.z; v.w = ~v.w;
+      need_lds[i * 64 + lane] = v;
+    }
+    if (cr != kNone) {  // chunks in flight to d are not needed
+      const u32 w = cr >> 6;
+      const u32 ln = w / (u32)NW;
+      const u32 iw = w - ln * (u32)NW;
+      u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(iw >> 1) * 64u + ln]) + ((iw & 1u) * 2u + ((cr >> 5) & 1u));
+      atomicAnd(ptr, ~(1u << (cr & 31u)));
+    }
+    for (u32 step = 0; free_links; ++step) {
+      // serv = need & (OR of the rows of the free links), in registers
+      typename RT::A acc_a = {};
+      typename RT::B acc_b = {};
+      u64 todo = free_links;
+      while (todo) {
+        const u32 b = (u32)__ffsll((long long)todo) - 1u;
+        todo &= todo - 1ull;
+        const u32 src = read_lane(s, b);
+        const uint4 *sp = reinterpret_cast<const uint4 *>(p.held + (u64)src * p.row_words) + lane;
+        static_for<0, NP>([&](auto I) {
+          constexpr int i = decltype(I)::value;
+          const uint4 v = sp[i * 64];
+          RT::template set<4 * i>(acc_a, acc_b, RT::template get<4 * i>(acc_a, acc_b) | v.x);
+          RT::template set<4 * i + 1>(acc_a, acc_b, RT::template get<4 * i + 1>(acc_a, acc_b) | v.y);
+          RT::template set<4 * i + 2>(acc_a, acc_b, RT::template get<4 * i + 2>(acc_a, acc_b) | v.z);
+          RT::template set<4 * i + 3>(acc_a, acc_b, RT::template get<4 * i + 3>(acc_a, acc_b) | v.w);
+        });
+      }
+      u32 pre[NW];
+      u32 cnt = 0;
+      static_for<0, NP>([&](auto I) {
+        constexpr int i = decltype(I)::value;
+        const uint4 nd = need_lds[i * 64 + lane];
+        const u32 c0 = RT::template get<4 * i>(acc_a, acc_b) & nd.x;
+        const u32 c1 = RT::template get<4 * i + 1>(acc_a, acc_b) & nd.y;
+        const u32 c2 = RT::template get<4 * i + 2>(acc_a, acc_b) & nd.z;
+        const u32 c3 = RT::template get<4 * i + 3>(acc_a, acc_b) & nd.w;
+        RT::template set<4 * i>(acc_a, acc_b, c0); RT::template set<4 * i + 1>(acc_a, acc_b, c1);
+        RT::template set<4 * i + 2>(acc_a, acc_b, c2); RT::template set<4 * i + 3>(acc_a, acc_b, c3);
+        cnt = popc_acc(c0, cnt);
+        cnt = popc_acc(c1, cnt);
+        pre[2 * i] = cnt;
+        cnt = popc_acc(c2, cnt);
+        cnt = popc_acc(c3, cnt);
+        pre[2 * i + 1] = cnt;
+      });
+      const u32 incl = wave_inclusive_scan(cnt);
+      const u32 pop = read_lane(incl, 63);
+      if (pop == 0) break;  // no free link can serve any missing chunk
+      u32 r0, r1;
+      philox4x32_10_words01(d, event, p.phase + 2u, step, p.seed_lo, p.seed_hi, r0, r1);
+      u32 k = r0 % pop;
+      const u64 above = __ballot(incl > k);
+      const u32 ln = (u32)__ffsll((long long)above) - 1u;
+      k -= read_lane(incl - cnt, ln);
+      u32 idx = 0, before = 0;
+#pragma unroll
+      for (int i = 0; i < NW - 1; ++i) {
+        const u32 pi = read_lane(pre[i], ln);
+        const u32 le = ((k - pi) >> 31) ^ 1u;
+        idx += le;
+        const u32 cand_before = pi * le;
+        before = cand_before > before ? cand_before : before;
+      }
+      const u32 lo = read_lane(RT::at(acc_a, acc_b, 2u * idx), ln);
+      const u32 hi = read_lane(RT::at(acc_a, acc_b, 2u * idx + 1u), ln);
+      const u32 bit = kth_set_bit_wave(lo, hi, k - before);
+      const u32 chunk = ((ln * (u32)NW + idx) << 6) + bit;
+      // which free links' sources hold the chunk: lane j tests its own source's dword
+      const u32 dword = ((idx >> 1) * 128u + ln * 2u + (idx & 1u)) * 2u + (bit >> 5);
+      bool holds = false;
+      if ((free_links >> lane) & 1ull) {
+        const u32 wv = reinterpret_cast<const u32 *>(p.held + (u64)s * p.row_words)[dword];
+        holds = (wv >> (bit & 31u)) & 1u;
+      }
+      const u64 holders = __ballot(holds);
+      u32 pick;
+      if (first_holder) pick = (u32)__ffsll((long long)holders) - 1u;
+      else pick = kth_set_bit_wave((u32)holders, (u32)(holders >> 32), r1 % (u32)__popcll(holders));
+      if ((u32)lane == pick) res = chunk;
+      free_links &= ~(1ull << pick);
+      if (lane == 0) {  // now in flight to d
+        u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(idx >> 1) * 64u + ln]) + ((idx & 1u) * 2u + (bit >> 5));
+        *ptr &= ~(1u << (bit & 31u));
+      }
+    }
+  }
+  if (valid) {
+    if (sched_row) sched_row[l] = res;
+    if (res != kNone) {
+      if (res >= p.C) {
+        ctl->status = kStInternal;
+        ctl->done = 1u;
+      } else if (cs > kInf - 1ull - t) {
+        ctl->status = kStOverflow;
+        ctl->done = 1u;
+      } else {
+        const u64 fa = t + cs;
+        p.carry[l] = res;
+        p.free_at[l] = fa;
+        my_min = fa < my_min ? fa : my_min;
+      }
+    } else if (cr != kNone) {
+      const u64 fa = p.free_at[l];
+      my_min = fa < my_min ? fa : my_min;
+    }
+  }
+  return my_min;
+}
+
+// MODE 0: link-centric matching; 1: postcondition-centric, random holder; 2: postcondition-
+// centric, first holder of the (cheapest-first) list.
+template <int NP, int MODE>
 __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
 {
   const int lane = threadIdx.x & 63;
@@ -472,7 +636,10 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
     return;
   }
   __shared__ uint4 need_lds[4 * NP * 64];
-  const u64 my_min = match_destination<NP>(p, d, event, t, sched_row, lane, need_lds + (threadIdx.x >> 6) * NP * 64);
+  uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
+  u64 my_min;
+  if constexpr (MODE == 0) my_min = match_destination<NP>(p, d, event, t, sched_row, lane, my_need);
+  else my_min = match_destination_pairs<NP>(p, d, event, t, sched_row, lane, my_need, MODE == 2);
 
   // a8: next span = earliest end of a transfer in flight (min over all destinations)
   const u64 m = wave_min64(my_min);
@@ -692,20 +859,27 @@ void launch_arrive(const PassDev &p, u32 event, u64 *event_time_slot, u32 *sched
                      event_time_slot, sched_row);
 }
 
-void launch_match(const PassDev &p, u32 event, u32 *sched_row, hipStream_t s)
+template <int MODE> static void launch_match_mode(const PassDev &p, u32 event, u32 *sched_row, hipStream_t s)
 {
   const dim3 grid(8u * ((((p.N + 3u) / 4u) + 7u) / 8u)), block(256);
   switch (p.NP) {
-    case 1: hipLaunchKernelGGL(match_kernel<1>, grid, block, 0, s, p, event, sched_row); break;
-    case 2: hipLaunchKernelGGL(match_kernel<2>, grid, block, 0, s, p, event, sched_row); break;
-    case 3: hipLaunchKernelGGL(match_kernel<3>, grid, block, 0, s, p, event, sched_row); break;
-    case 4: hipLaunchKernelGGL(match_kernel<4>, grid, block, 0, s, p, event, sched_row); break;
-    case 5: hipLaunchKernelGGL(match_kernel<5>, grid, block, 0, s, p, event, sched_row); break;
-    case 6: hipLaunchKernelGGL(match_kernel<6>, grid, block, 0, s, p, event, sched_row); break;
-    case 7: hipLaunchKernelGGL(match_kernel<7>, grid, block, 0, s, p, event, sched_row); break;
-    case 8: hipLaunchKernelGGL(match_kernel<8>, grid, block, 0, s, p, event, sched_row); break;
+    case 1: hipLaunchKernelGGL((match_kernel<1, MODE>), grid, block, 0, s, p, event, sched_row); break;
+    case 2: hipLaunchKernelGGL((match_kernel<2, MODE>), grid, block, 0, s, p, event, sched_row); break;
+    case 3: hipLaunchKernelGGL((match_kernel<3, MODE>), grid, block, 0, s, p, event, sched_row); break;
+    case 4: hipLaunchKernelGGL((match_kernel<4, MODE>), grid, block, 0, s, p, event, sched_row); break;
+    case 5: hipLaunchKernelGGL((match_kernel<5, MODE>), grid, block, 0, s, p, event, sched_row); break;
+    case 6: hipLaunchKernelGGL((match_kernel<6, MODE>), grid, block, 0, s, p, event, sched_row); break;
+    case 7: hipLaunchKernelGGL((match_kernel<7, MODE>), grid, block, 0, s, p, event, sched_row); break;
+    case 8: hipLaunchKernelGGL((match_kernel<8, MODE>), grid, block, 0, s, p, event, sched_row); break;
     default: break;  // rejected by the host before any launch
   }
+}
+
+void launch_match(const PassDev &p, u32 event, u32 *sched_row, u32 mode, hipStream_t s)
+{
+  if (mode == 0) launch_match_mode<0>(p, event, sched_row, s);
+  else if (mode == 1) launch_match_mode<1>(p, event, sched_row, s);
+  else launch_match_mode<2>(p, event, sched_row, s);
 }
 
 template <int NP> static hipError_t launch_sweep_np(const PassDev &p, u32 first_event, u32 n_events,

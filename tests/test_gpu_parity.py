@@ -341,3 +341,48 @@ def test_link_counts_match_oracle_records(stream):
         for p, part in enumerate((ref.xfers[:n], ref.xfers[n:])):
             want = np.bincount(part["link"].astype(np.int64), minlength=topo.n_links)
             assert np.array_equal(r.link_counts(p, topo.n_links), want.astype(np.uint64))
+
+
+PAIR_CASES = [
+    ("mesh5x4_cpn7", lambda: T.mesh2d(5, 4), 7, T.ALL_GATHER),
+    ("biring9_cpn3", lambda: T.ring(9, bidirectional=True), 3, T.ALL_REDUCE),
+    ("fc16", lambda: T.fully_connected(16), 2, T.ALL_GATHER),
+    ("torus2x3_parallel_links", lambda: T.grid([2, 3], True), 2, T.REDUCE_SCATTER),
+    ("hetero_torus", lambda: T.grid([3, 3, 4], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000]), 3, T.ALL_REDUCE),
+    ("random40", lambda: T.random_regular_out(40, 3, seed=7)[0], 2, T.ALL_GATHER),
+    ("torus4x4x8_c8320", lambda: T.torus3d(4, 4, 8), 65, T.ALL_GATHER),
+]
+
+
+@pytest.mark.parametrize("name,mk,cpn,coll", PAIR_CASES, ids=[c[0] for c in PAIR_CASES])
+@pytest.mark.parametrize("link_order", [0, 1])
+def test_postcondition_centric_matching_bit_exact(name, mk, cpn, coll, link_order, stream):
+    """matching = 1 (Algorithm 1 in the order the paper prints it) against the oracle's
+    same mode, with random and with cheapest-first holder links."""
+    topo = mk()
+    cb = 96 << 10
+    kw = dict(max_events=60) if cpn == 65 else {}
+    ref = cpu(topo, cpn, cb, coll, 23, matching=1, link_order=link_order, **kw)
+    with gpu(topo, cpn, cb, coll, 23, stream, matching=1, link_order=link_order, **kw) as r:
+        assert_same(r, ref, name)
+
+
+def test_postcondition_centric_limits(stream):
+    fc70 = T.fully_connected(70)  # in-degree 69 > 64
+    with pytest.raises(binding.TacosError) as e:
+        gpu(fc70, 1, MiB, T.ALL_GATHER, 0, stream, matching=1)
+    assert e.value.code == binding.TACOS_E_INVAL
+    with pytest.raises(binding.TacosError) as e:
+        gpu(T.ring(4), 1, MiB, T.ALL_GATHER, 0, stream, matching=1, launch_mode=1)
+    assert e.value.code == binding.TACOS_E_INVAL
+
+
+def test_postcondition_centric_workload_5_prefix(stream):
+    """Algorithm 1's own order on the 40,960-NPU torus: first 16 spans record by record."""
+    w = T.workload(5)
+    n_ev = 16
+    ref = oracle.synthesize_workload(w, max_events=n_ev, matching=1, n_threads=min(16, oracle.max_threads()))
+    with binding.synthesize_workload(w, stream=stream, max_events=n_ev, matching=1) as r:
+        assert r.num_xfers == ref.n_xfers and r.digest == ref.digest
+        assert np.array_equal(r.read(0, 1 << 20), ref.xfers[:1 << 20])
+        assert np.array_equal(r.read(r.num_xfers - (1 << 20), 1 << 20), ref.xfers[-(1 << 20):])
