@@ -53,36 +53,82 @@ def measured_traffic(workload_name):
 
 
 def cpu_baseline(w, target_s=15.0):
+    """The CPU oracle on a bounded sample of the workload: the whole workload if that takes
+    about target_s or less, else the first spans of its All-Gather pass (the reversed pass
+    of a Reduce-Scatter does the same work per span on the transposed topology)."""
     import oracle
     threads = min(oracle.max_threads(), 16)
     t = w.topo
 
-    def run(n_events):
+    def run(coll, n_events):
         t0 = time.perf_counter()
         r = oracle.synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B,
-                              w.chunks_per_npu, w.chunk_bytes, w.collective, w.seed,
+                              w.chunks_per_npu, w.chunk_bytes, coll, w.seed,
                               max_events=n_events, keep_xfers=0, n_threads=threads)
         return time.perf_counter() - t0, r
 
-    dt2, _ = run(2)
-    dt6, r = run(6)
-    per_event = max((dt6 - dt2) / 4, 1e-6)   # set-up time cancels
-    n = int(max(2, min(2000, target_s / per_event)))
-    complete = False
-    if w.collective == 0 and n < 2000:
-        dt, r = run(n)
-        sample = f"first {n} TEN spans of the workload ({r.n_xfers} matches)"
-    else:
-        # small workloads: run the whole thing
-        t0 = time.perf_counter()
-        r = oracle.synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B,
-                              w.chunks_per_npu, w.chunk_bytes, w.collective, w.seed,
-                              keep_xfers=0, n_threads=threads)
-        dt = time.perf_counter() - t0
-        complete = True
-        sample = f"whole workload ({r.n_xfers} matches)"
+    dt2, _ = run(0, 2)
+    dt6, r6 = run(0, 6)
+    per_event = max((dt6 - dt2) / 4, 1e-7)   # set-up time cancels
+    n = int(max(6, target_s / per_event))
+    oracle.set_progress(max(1, int(20.0 / per_event)))  # a line about every 20 s
+    try:
+        small = t.n_npus * w.chunks_per_npu <= 2048
+        if small and w.collective != 0:
+            t0 = time.perf_counter()
+            r = oracle.synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B,
+                                  w.chunks_per_npu, w.chunk_bytes, w.collective, w.seed,
+                                  keep_xfers=0, n_threads=threads)
+            dt = time.perf_counter() - t0
+            sample = f"whole workload ({r.n_xfers} matches)"
+            complete = True
+        else:
+            dt, r = run(0, n)
+            complete = r.n_events < n and w.collective == 0
+            what = "whole workload" if complete else f"first {r.n_events} TEN spans of the All-Gather pass"
+            sample = f"{what} ({r.n_xfers} matches)"
+    finally:
+        oracle.set_progress(0)
     return {"value": r.n_xfers / dt, "unit": "matches/s", "cores": threads, "kind": "oracle",
             "sample": sample, "seconds": dt, "complete": complete}
+
+
+def report_all(binding, T, stream, with_cpu):
+    """One synthesis of every workload (after a warm-up run for the small ones) and the
+    oracle beside it; prints a markdown table."""
+    rows = []
+    for idx in (1, 2, 3, 4, 5, 6, 7):
+        w = T.workload(idx)
+        topo = w.topo
+        n_chunks = topo.n_npus * w.chunks_per_npu
+        if idx != 4:
+            binding.synthesize_workload(w, stream=stream).free()
+        t0 = time.perf_counter()
+        r = binding.synthesize_workload(w, stream=stream, time_kernels=True)
+        wall = time.perf_counter() - t0
+        alg = algorithmic_bytes(r.num_xfers, topo.n_npus, topo.n_links, n_chunks)
+        k_s = r.kernel_ms * 1e-3
+        row = {"idx": idx, "name": w.name, "npus": topo.n_npus, "links": topo.n_links, "spans": r.num_events,
+               "matches": r.num_xfers, "T_ps": r.collective_time_ps, "wall_s": wall, "kernel_s": k_s,
+               "matches_per_s": r.num_xfers / wall, "alg_GBps": alg / k_s / 1e9 if k_s > 0 else 0.0}
+        r.free()
+        if with_cpu:
+            cb = cpu_baseline(w, target_s=10.0)
+            row["cpu"] = cb
+        rows.append(row)
+        print(f"[report] workload {idx} done", file=sys.stderr, flush=True)
+    print("| # | workload | NPUs | links | TEN spans | matches | collective time (ps) | GPU synthesis (s) | "
+          "matches/s | matching kernel (s) | algorithmic GB/s in the matching kernel | fraction of 8 TB/s | "
+          "oracle matches/s (host threads; sample) |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    for r in rows:
+        cpu = "-"
+        if "cpu" in r:
+            c = r["cpu"]
+            cpu = f"{c['value']:.3g} ({c['cores']}; {c['sample']}, {c['seconds']:.1f} s)"
+        print(f"| {r['idx']} | {r['name']} | {r['npus']} | {r['links']} | {r['spans']} | {r['matches']} | {r['T_ps']} | "
+              f"{r['wall_s']:.4f} | {r['matches_per_s']:.3g} | {r['kernel_s']:.4f} | {r['alg_GBps']:.1f} | "
+              f"{r['alg_GBps'] / HBM_PEAK_GBS:.4f} | {cpu} |")
 
 
 def main():
@@ -92,6 +138,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", type=int, default=5, help="1..5 (default 5: 40,960-NPU torus)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--report-all", action="store_true",
+                    help="instead of the one JSON line: a table over workloads 1..7 (GPU time, spans, "
+                         "matches/s, fraction of the HBM roofline, oracle time on the host cores)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for HBM counters)")
     args = ap.parse_args()
@@ -108,6 +157,9 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream().cuda_stream
+    if args.report_all:
+        report_all(binding, T, stream, not args.no_cpu_baseline)
+        return
     w = T.workload(args.workload)
     topo = w.topo
     n_chunks = topo.n_npus * w.chunks_per_npu

@@ -120,11 +120,14 @@ typedef struct {
   uint32_t time_kernels;  /* != 0: bracket every launch of the kernel that does the matching
                              with HIP events on `stream` so that tacos_result_kernel_ms is
                              available                                                      */
-  uint32_t launch_mode;   /* 0 = two plain launches per span (arrivals; matching + next-event
-                             reduction), queued in batches: the default and the faster mode
-                             on MI355X.  1 = persistent: one cooperative launch sweeps many
-                             spans with two grid-wide barriers per span; falls back to 0 if
-                             the device cannot launch cooperatively.  Same results.          */
+  uint32_t launch_mode;   /* 0 = automatic (2 when the shape allows it, else 1).
+                             1 = two plain launches per span (arrivals; matching + next-event
+                             reduction), queued in batches.
+                             2 = small topologies: ONE workgroup sweeps many spans per launch
+                             with the per-link state and a work list in LDS and matches only
+                             the destinations something changed for; needs links, NPUs and
+                             need rows to fit the LDS of one CU (<= 16,384 chunks, a few
+                             thousand links), else TACOS_E_INVAL.  Same results in all modes. */
   uint32_t link_order;    /* order in which a destination's idle incoming links are tried:
                              0 = ascending link id; 1 = cheapest link first, ties by link id
                              (paper, "Prioritizing Lower-cost Links").  The random draw of a
@@ -194,7 +197,7 @@ int tacos_result_link_counts(const tacos_result_t *r, uint32_t pass, uint64_t *l
  */
 uint64_t tacos_result_digest(const tacos_result_t *r);
 /* Milliseconds spent inside the kernel that does the matching (sum over its launches:
- * the per-span matching kernel, or the persistent sweep kernel in launch_mode 1) and
+ * the per-span matching kernel, or the single-workgroup sweep kernel of launch_mode 2) and
  * the number of launches; 0 unless opts->time_kernels was set. */
 double   tacos_result_kernel_ms(const tacos_result_t *r);
 uint64_t tacos_result_kernel_launches(const tacos_result_t *r);

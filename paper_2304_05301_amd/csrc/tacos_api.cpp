@@ -99,6 +99,7 @@ struct Pass {
   uint64_t n_rows = 0;    // schedule rows that may hold records
   uint64_t t_off = 0;     // start of the pass inside the collective
   uint64_t n_xfers = 0;
+  bool prefill = false;   // new segments are filled with TACOS_NO_CHUNK
   std::vector<uint64_t> row_time;   // [n_rows] by event index
   std::vector<uint32_t> row_count;  // [n_rows] by event index
   std::vector<uint64_t> canon_base; // [n_rows+1] prefix of counts in canonical row order
@@ -141,12 +142,14 @@ constexpr uint32_t kClusterSize = 512;
 
 std::vector<uint32_t> cluster_order(uint32_t N, uint32_t L, const std::vector<uint32_t> &in_ptr,
                                     const std::vector<uint32_t> &in_src, const std::vector<uint32_t> &psrc,
-                                    const std::vector<uint32_t> &pdst)
+                                    const std::vector<uint32_t> &pdst, std::vector<uint32_t> &out_ptr,
+                                    std::vector<uint32_t> &out_dst)
 {
   std::vector<uint32_t> order;
   order.reserve(N);
   // out-neighbour lists (CSR by psrc) next to the in-neighbour lists we already have
-  std::vector<uint32_t> out_ptr(N + 1, 0), out_dst(L);
+  out_ptr.assign(N + 1, 0);
+  out_dst.assign(L, 0);
   for (uint32_t l = 0; l < L; ++l) out_ptr[psrc[l] + 1]++;
   for (uint32_t i = 0; i < N; ++i) out_ptr[i + 1] += out_ptr[i];
   {
@@ -184,7 +187,7 @@ std::vector<uint32_t> cluster_order(uint32_t N, uint32_t L, const std::vector<ui
 // Runs one All-Gather pass over links psrc[l] -> pdst[l] and stores its schedule rows.
 int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
              const DevBuf &d_cost, uint32_t cpn, uint64_t seed, uint32_t phase, bool reversed,
-             uint64_t max_events, bool time_kernels, bool persistent, const std::vector<uint64_t> *order_cost,
+             uint64_t max_events, bool time_kernels, uint32_t launch_mode, const std::vector<uint64_t> *order_cost,
              uint32_t match_mode, hipStream_t stream, tacos_result &res, Pass &pass)
 {
   const uint32_t C = N * cpn;
@@ -223,7 +226,8 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   // Processing order of the destinations: clusters grown breadth-first over the
   // (undirected) topology, so that NPUs that read each other's rows are matched close
   // together in time and on the same XCD.  Any permutation gives the same schedule.
-  std::vector<uint32_t> order = cluster_order(N, L, in_ptr, in_src, psrc, pdst);
+  std::vector<uint32_t> out_ptr, out_dst;
+  std::vector<uint32_t> order = cluster_order(N, L, in_ptr, in_src, psrc, pdst, out_ptr, out_dst);
 
   DevBuf d_in_ptr, d_in_link, d_in_src, d_link_dst, d_held, d_carry, d_free_at, d_ctl, d_order;
   upload(d_order, order.data(), order.size(), stream);
@@ -259,6 +263,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
       Segment s;
       s.rows.alloc((size_t)pass.rows_per_seg * L * 4);
       s.row_time.alloc((size_t)pass.rows_per_seg * 8);
+      if (pass.prefill) HIP_TRY(hipMemsetAsync(s.rows.p, 0xFF, s.rows.bytes, stream));  // TACOS_NO_CHUNK
       res.device_bytes += s.rows.bytes + s.row_time.bytes;
       pass.segs.push_back(std::move(s));
     }
@@ -269,18 +274,25 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
 
   uint64_t e = 0;
   bool stopped = false;  // prefix run reached max_events
-  // Persistent mode (opt-in): one cooperative launch sweeps many spans with grid-wide
-  // barriers in between.  Its grid must be co-resident: a multiple of 8 workgroups (one
-  // slice of the processing order per XCD), no larger than the device can hold.
-  uint32_t grid = 0;
-  if (persistent) {
-    // few workgroups: the barrier costs about 15 ns per workgroup, and every wavefront
-    // walks several destinations per span anyway
-    const uint32_t max_blocks = tacos::sweep_max_blocks(NP) & ~7u;
-    const uint32_t want = 8u * ((((N + 3u) / 4u) + 31u) / 32u);
-    grid = std::min(max_blocks, want);
+  // Small topologies: one workgroup sweeps many spans with the link state in LDS.  Chosen
+  // automatically when the shape fits (launch_mode 0), forced by launch_mode 2.
+  bool small = false;
+  DevBuf d_out_ptr, d_out_dst;
+  if (launch_mode != 1 && match_mode == 0) {
+    int dev = 0, lds_max = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+    const size_t need = tacos::small_sweep_lds_bytes(N, L, NP);
+    small = need != (size_t)-1 && need <= (size_t)lds_max;
+    if (!small && launch_mode == 2) {
+      g_last_error = "launch_mode 2: links, NPUs and need rows do not fit the LDS of one workgroup";
+      return TACOS_E_INVAL;
+    }
   }
-  if (grid >= 8) {
+  pass.prefill = small;  // the small-topology kernel writes matches only
+  if (small) {
+    upload(d_out_ptr, out_ptr.data(), out_ptr.size(), stream);
+    upload(d_out_dst, out_dst.data(), out_dst.size(), stream);
     for (;;) {
       if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
       uint32_t *row = nullptr;
@@ -297,7 +309,8 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
         ev0 = pool.ev[0]; ev1 = pool.ev[1];
         HIP_TRY(hipEventRecord(ev0, stream));
       }
-      HIP_TRY(tacos::launch_sweep(p, (uint32_t)e, (uint32_t)n, stop_event, row, tslot, grid, stream));
+      HIP_TRY(tacos::launch_small_sweep(p, d_out_ptr.as<uint32_t>(), d_out_dst.as<uint32_t>(), (uint32_t)e,
+                                        (uint32_t)n, stop_event, row, tslot, stream));
       if (time_kernels) HIP_TRY(hipEventRecord(ev1, stream));
       HIP_TRY(hipMemcpyAsync(host_ctl.p, p.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, stream));
       HIP_TRY(hipStreamSynchronize(stream));
@@ -478,13 +491,13 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
   if (rc != TACOS_OK) return rc;
   const uint64_t max_events = opts ? opts->max_events : 0;
   if (max_events && coll != TACOS_ALL_GATHER) return TACOS_E_INVAL;
-  if (opts && (opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 1 ||
+  if (opts && (opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 2 ||
                opts->matching > TACOS_MATCH_POSTCONDITION))
     return TACOS_E_INVAL;
   // kernel variant: 0 link-centric; 1 postcondition-centric, random holder; 2 first holder
   uint32_t match_mode = 0;
   if (opts && opts->matching == TACOS_MATCH_POSTCONDITION) {
-    if (opts->launch_mode != 0) return TACOS_E_INVAL;
+    if (opts->launch_mode == 2) return TACOS_E_INVAL;
     std::vector<uint32_t> deg_in(topo->n_npus, 0), deg_out(topo->n_npus, 0);
     for (uint32_t i = 0; i < topo->n_npus; ++i) {
       deg_out[i] = topo->row_ptr[i + 1] - topo->row_ptr[i];
@@ -498,7 +511,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
     match_mode = opts->link_order == TACOS_LINK_ORDER_COST ? 2u : 1u;
   }
   const bool time_kernels = opts && opts->time_kernels;
-  const bool persistent = opts && opts->launch_mode == 1;
+  const uint32_t launch_mode = opts ? opts->launch_mode : 0;
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
 
   const auto wall0 = std::chrono::steady_clock::now();
@@ -538,7 +551,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
         // reversed pass: every link (s -> d) is used as (d -> s), ids and costs unchanged
         res->passes.emplace_back();
         rc = run_pass(N, L, res->link_dst, res->link_src, d_cost, chunks_per_npu, seed, 1u, true, 0,
-                      time_kernels, persistent, order_cost, match_mode, stream, *res, res->passes.back());
+                      time_kernels, launch_mode, order_cost, match_mode, stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), 0, &res->digest, stream);
         t_off = res->passes.back().T;
@@ -546,7 +559,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       if (coll == TACOS_ALL_GATHER || coll == TACOS_ALL_REDUCE) {
         res->passes.emplace_back();
         rc = run_pass(N, L, res->link_src, res->link_dst, d_cost, chunks_per_npu, seed, 0u, false,
-                      max_events, time_kernels, persistent, order_cost, match_mode, stream, *res, res->passes.back());
+                      max_events, time_kernels, launch_mode, order_cost, match_mode, stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), t_off, &res->digest, stream);
       }

@@ -26,10 +26,6 @@ struct Ctl {
   uint32_t status;
   uint32_t n_events;             // matching sweeps run, valid once done
   uint32_t pad;
-  // grid-wide barrier of the persistent sweep kernel: arrivals only ever grow, the
-  // generation is bumped by the last workgroup to arrive
-  unsigned long long bar_count;
-  unsigned long long bar_gen;
 };
 
 // HBM layout of the per-NPU held bitsets ("precondition" rows).
@@ -76,18 +72,18 @@ void launch_arrive(const PassDev &p, uint32_t event, unsigned long long *event_t
 // mode 0: link-centric; 1: postcondition-centric with a random holder link; 2: postcondition-
 // centric with the first holder of the incoming list (in-degree <= 64 for modes 1, 2)
 void launch_match(const PassDev &p, uint32_t event, uint32_t *sched_row, uint32_t mode, hipStream_t s);
-// a3-a8 fused: ONE cooperative launch runs spans [first_event, first_event+n_events)
-// (arrivals, termination test, matching, next-event reduction, with two grid-wide
-// barriers per span) and returns early when the pass ends.  stop_event: the span at
-// which only the arrivals are applied (prefix runs), or 0xFFFFFFFF.  sched_rows and
-// event_times point at the slots of first_event.  grid_blocks must not exceed
-// sweep_max_blocks(NP).  Returns the HIP status of the launch.
-hipError_t launch_sweep(const PassDev &p, uint32_t first_event, uint32_t n_events, uint32_t stop_event,
-                        uint32_t *sched_rows, unsigned long long *event_times, uint32_t grid_blocks,
-                        hipStream_t s);
-// largest co-resident grid (in workgroups of 256 threads) of the sweep kernel on the
-// current device, 0 if cooperative launches are not available
-uint32_t sweep_max_blocks(uint32_t NP);
+// a3-a8 fused for small topologies: ONE workgroup sweeps spans [first_event,
+// first_event+n_events) with the per-link state in LDS (arrivals, termination test,
+// matching of the destinations something changed for, next-event min-reduction) and
+// returns early when the pass ends.  stop_event: the span at which only the arrivals are
+// applied (prefix runs), or 0xFFFFFFFF.  sched_rows / event_times point at the slots of
+// first_event; the rows must be pre-filled with kNone.  out_ptr/out_dst: out-neighbour
+// lists of the pass orientation.  Needs small_sweep_lds_bytes(...) of dynamic LDS.
+hipError_t launch_small_sweep(const PassDev &p, const uint32_t *out_ptr, const uint32_t *out_dst,
+                              uint32_t first_event, uint32_t n_events, uint32_t stop_event,
+                              uint32_t *sched_rows, unsigned long long *event_times, hipStream_t s);
+// LDS the small-topology kernel needs, (size_t)-1 if the shape is not supported
+size_t small_sweep_lds_bytes(uint32_t N, uint32_t L, uint32_t NP);
 // epilogue: per-row match counts and the schedule digest of a block of rows
 void launch_row_stats(const uint32_t *rows, uint32_t n_rows, uint32_t L,
                       const unsigned long long *row_time, unsigned long long t_base,

@@ -151,27 +151,10 @@ __global__ void init_links_kernel(PassDev p)
     c->status = 0u;
     c->n_events = 0u;
     c->pad = 0u;
-    c->bar_count = 0ull;
-    c->bar_gen = 0ull;
   }
 }
 
 // ---------------------------------------------------------------- a3: arrivals
-
-// a3 for one link: a transfer that ends at t delivers its chunk to the link's
-// destination.  Returns whether it did.
-__device__ __forceinline__ bool arrive_link(const PassDev &p, u32 l, u64 t, u32 *__restrict__ sched_row)
-{
-  const u32 c = p.carry[l];
-  const bool arrived = (c != kNone) && (p.free_at[l] == t);
-  if (arrived) {
-    const u32 d = p.link_dst[l];
-    atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
-    p.carry[l] = kNone;
-  }
-  if (sched_row) sched_row[l] = arrived ? c : kNone;
-  return arrived;
-}
 
 __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *event_time_slot,
                                                      u32 *__restrict__ sched_row)
@@ -650,127 +633,131 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
   }
 }
 
-// ---------------------------------------------------------------- persistent sweep
+// ---------------------------------------------------------------- small topologies
 
-// How long a workgroup spins at the grid barrier before it gives up (each probe is a
-// device-scope load plus a sleep of 64 clocks: a few seconds in all, against waits of
-// at most milliseconds).  Reaching it means a workgroup of the grid is
-// not running, which a cooperative launch rules out; it is the exit that every wave
-// reaches whatever happens.
-constexpr u32 kBarrierSpinLimit = 1u << 22;
-
-// Grid-wide barrier for a cooperative launch.  Release: every thread's stores are done
-// at the workgroup barrier, thread 0 then publishes them device-wide (the L2s of the
-// XCDs are not coherent with each other) with its release increment.  Acquire: after
-// the generation moved, thread 0's acquire fence drops stale lines before the workgroup
-// continues.  Returns false if the wait was abandoned.
-__device__ __forceinline__ bool grid_barrier(Ctl *ctl, u32 n_blocks, u64 &generation)
+// One workgroup of 16 wavefronts sweeps many TEN spans without leaving the chip: the
+// per-link state (chunk carried, busy-until time) and the work list live in LDS, the
+// next event is a min-reduction over the busy-until times in LDS, and a span touches
+// only the destinations something changed for.  Used when links, NPUs and the need slabs
+// fit the LDS of one CU; such inputs are bound by the latency of a span, not by memory
+// bandwidth (a heterogeneous topology has about one arrival per span).
+//
+// A destination d must be matched at a span only if a link into d became idle at it, or
+// an in-neighbour of d gained a chunk at it (or at span 0): otherwise every idle link
+// into d found no candidate the last time it was tried, its source holds nothing new and
+// d needs nothing more than then.  No random number is drawn for a link without
+// candidates, so skipping it cannot change the result.
+//
+// LDS layout (dynamic): u64 free_at[L8] | u32 carry[L] | u32 stamp[N] | u32 work[N] |
+// uint4 need[16][NP][64] | u64 red[16] | u32 counters[4].
+__host__ __device__ inline size_t small_lds_bytes(u32 N, u32 L, u32 NP)
 {
-  __shared__ u32 ok_flag;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    u32 ok = 1u;
-    const u64 target = (generation + 1ull) * n_blocks;
-    const u64 prev = __hip_atomic_fetch_add(&ctl->bar_count, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    if (prev + 1ull == target) {
-      __hip_atomic_store(&ctl->bar_gen, generation + 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    } else {
-      u32 spins = 0;
-      while (__hip_atomic_load(&ctl->bar_gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <= generation) {
-        if (++spins > kBarrierSpinLimit) { ok = 0u; break; }
-        __builtin_amdgcn_s_sleep(1);
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    ok_flag = ok;
-  }
-  __syncthreads();
-  generation += 1ull;
-  return ok_flag != 0u;
+  size_t b = (size_t)L * 8;
+  b += ((size_t)L * 4 + 15) & ~(size_t)15;
+  b += ((size_t)N * 4 + 15) & ~(size_t)15;
+  b += ((size_t)N * 4 + 15) & ~(size_t)15;
+  b += (size_t)16 * NP * 1024;
+  b += 16 * 8 + 16;
+  return b;
 }
 
 template <int NP>
-__global__ __launch_bounds__(256) void sweep_kernel(PassDev p, u32 first_event, u32 n_events, u32 stop_event,
-                                                    u32 *__restrict__ sched_rows, u64 *__restrict__ event_times)
+__global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 *__restrict__ out_ptr,
+                                                           const u32 *__restrict__ out_dst, u32 first_event,
+                                                           u32 n_events, u32 stop_event,
+                                                           u32 *__restrict__ sched_rows,
+                                                           u64 *__restrict__ event_times)
 {
-  __shared__ u64 wave_min[4];
-  __shared__ u32 wave_cnt[4];
-  __shared__ uint4 need_lds[4 * NP * 64];
-  const int lane = threadIdx.x & 63;
-  const u32 wave = threadIdx.x >> 6;
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  unsigned char *cur = lds_raw;
+  u64 *s_free = reinterpret_cast<u64 *>(cur); cur += (size_t)p.L * 8;
+  u32 *s_carry = reinterpret_cast<u32 *>(cur); cur += ((size_t)p.L * 4 + 15) & ~(size_t)15;
+  u32 *s_stamp = reinterpret_cast<u32 *>(cur); cur += ((size_t)p.N * 4 + 15) & ~(size_t)15;
+  u32 *s_work = reinterpret_cast<u32 *>(cur); cur += ((size_t)p.N * 4 + 15) & ~(size_t)15;
+  uint4 *s_need = reinterpret_cast<uint4 *>(cur); cur += (size_t)16 * NP * 1024;
+  u64 *s_red = reinterpret_cast<u64 *>(cur); cur += 16 * 8;
+  u32 *s_cnt = reinterpret_cast<u32 *>(cur);  // [0] = work-list length, [1] = arrivals, [2] = stop flag
+
+  const u32 tid = threadIdx.x;
+  const int lane = tid & 63;
+  const u32 wave = tid >> 6;
   Ctl *ctl = p.ctl;
-  const u32 n_blocks = gridDim.x;
-  // XCD-aware slots (workgroups go to the 8 XCDs round-robin; the grid is a multiple
-  // of 8): XCD x owns a contiguous slice of the processing order
-  const u32 n_pos = (p.N + 3u) / 4u;                  // positions of 4 destinations
-  const u32 per_xcd_blocks = n_blocks >> 3;
-  const u32 per_xcd_pos = (n_pos + 7u) / 8u;
-  const u32 xcd = blockIdx.x & 7u, rank_in_xcd = blockIdx.x >> 3;
-
-  u64 generation = __hip_atomic_load(&ctl->bar_gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  u64 t = ctl->next_t[first_event & 1u];
   if (ctl->done) return;
+  for (u32 l = tid; l < p.L; l += 1024u) { s_free[l] = p.free_at[l]; s_carry[l] = p.carry[l]; }
+  for (u32 n = tid; n < p.N; n += 1024u) s_stamp[n] = kNone;
+  PassDev q = p;  // the matching code works on the LDS copy of the link state
+  q.carry = s_carry;
+  q.free_at = s_free;
+  u64 t = ctl->next_t[first_event & 1u];
+  u64 remaining = ctl->remaining;
+  u32 e = first_event;
+  bool finished = false;  // uniform
+  __syncthreads();
 
-  for (u32 e = first_event; e < first_event + n_events; ++e) {
-    u32 *row = sched_rows ? sched_rows + (u64)(e - first_event) * p.L : nullptr;
-    // ---- arrivals at t (a3)
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-      event_times[e - first_event] = t;
-      __hip_atomic_store(&ctl->next_t[(e + 1u) & 1u], kInf, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    u32 n_arr = 0;  // wave-uniform
-    for (u32 l0 = blockIdx.x * 256u; l0 < p.L; l0 += n_blocks * 256u) {
-      const u32 l = l0 + threadIdx.x;
-      const bool arrived = l < p.L && arrive_link(p, l, t, p.reversed ? row : nullptr);
-      n_arr += (u32)__popcll(__ballot(arrived));
-    }
-    if (lane == 0) wave_cnt[wave] = n_arr;
+  for (; e < first_event + n_events; ++e) {
+    u32 *row = sched_rows + (u64)(e - first_event) * p.L;
+    if (tid == 0) { event_times[e - first_event] = t; s_cnt[0] = 0u; s_cnt[1] = 0u; }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      const u32 nb = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
-      if (nb) atomicAdd(&ctl->remaining, (u64)0 - (u64)nb);
-    }
-    if (!grid_barrier(ctl, n_blocks, generation)) {
-      if (threadIdx.x == 0) { ctl->status = kStInternal; ctl->done = 1u; }
-      return;
-    }
-    // ---- all postconditions satisfied? (a4)
-    const u64 rem = __hip_atomic_load(&ctl->remaining, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (rem == 0ull) {
-      if (blockIdx.x == 0 && threadIdx.x == 0) { ctl->T = t; ctl->n_events = e; ctl->done = 1u; }
-      return;
-    }
-    if (e == stop_event) return;  // prefix run: time reached is next_t[e & 1]
-    // ---- matching for this span (a5-a7) and the earliest end of a transfer (a8)
-    u64 my_min = kInf;
-    for (u32 q = rank_in_xcd; q < per_xcd_pos; q += per_xcd_blocks) {
-      const u32 slot = uniform((xcd * per_xcd_pos + q) * 4u + wave);
-      if (slot < p.N) {
-        const u64 m = match_destination<NP>(p, uniform(p.order[slot]), e, t, p.reversed ? nullptr : row, lane,
-                                           need_lds + wave * NP * 64);
-        my_min = m < my_min ? m : my_min;
+    // ---- arrivals at t (a3); every NPU whose state changed, and its out-neighbours, go
+    //      on the work list once
+    for (u32 l = tid; l < p.L; l += 1024u) {
+      const u32 c = s_carry[l];
+      if (c != kNone && s_free[l] == t) {
+        const u32 d = p.link_dst[l];
+        atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
+        s_carry[l] = kNone;
+        atomicAdd(&s_cnt[1], 1u);
+        if (p.reversed) row[l] = c;
+        if (atomicExch(&s_stamp[d], e) != e) s_work[atomicAdd(&s_cnt[0], 1u)] = d;
+        for (u32 j = out_ptr[d]; j < out_ptr[d + 1]; ++j) {
+          const u32 o = out_dst[j];
+          if (atomicExch(&s_stamp[o], e) != e) s_work[atomicAdd(&s_cnt[0], 1u)] = o;
+        }
       }
     }
-    my_min = wave_min64(my_min);
-    if (lane == 0) wave_min[wave] = my_min;
     __syncthreads();
-    if (threadIdx.x == 0) {
-      u64 m = wave_min[0];
-      m = wave_min[1] < m ? wave_min[1] : m;
-      m = wave_min[2] < m ? wave_min[2] : m;
-      m = wave_min[3] < m ? wave_min[3] : m;
-      if (m != kInf) atomicMin(&ctl->next_t[(e + 1u) & 1u], m);
+    remaining -= (u64)s_cnt[1];
+    // ---- all postconditions satisfied? (a4)
+    if (remaining == 0ull) {
+      if (tid == 0) { ctl->T = t; ctl->n_events = e; ctl->done = 1u; }
+      finished = true;
+      break;
     }
-    if (!grid_barrier(ctl, n_blocks, generation)) {
-      if (threadIdx.x == 0) { ctl->status = kStInternal; ctl->done = 1u; }
-      return;
+    if (e == stop_event) break;  // prefix run: time reached is next_t[e & 1]
+    // ---- matching (a5-a7) for the destinations on the work list (all of them at span 0)
+    const u32 n_work = (e == 0u) ? p.N : s_cnt[0];
+    for (u32 i = wave; i < n_work; i += 16u) {
+      const u32 d = uniform((e == 0u) ? i : s_work[i]);
+      (void)match_destination<NP>(q, d, e, t, p.reversed ? nullptr : row, lane, s_need + wave * NP * 64);
     }
-    if (__hip_atomic_load(&ctl->done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;  // overflow flagged
-    t = __hip_atomic_load(&ctl->next_t[(e + 1u) & 1u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (t == kInf) {  // chunks missing and nothing in flight
-      if (blockIdx.x == 0 && threadIdx.x == 0) { ctl->status = kStUnreachable; ctl->done = 1u; }
-      return;
+    __syncthreads();
+    // ---- next span = earliest end of a transfer in flight (a8), reduced in LDS
+    u64 m = kInf;
+    for (u32 l = tid; l < p.L; l += 1024u)
+      if (s_carry[l] != kNone) { const u64 fa = s_free[l]; m = fa < m ? fa : m; }
+    m = wave_min64(m);
+    if (lane == 0) s_red[wave] = m;
+    if (tid == 0)  // an overflow flagged during matching; broadcast so that every thread leaves
+      s_cnt[2] = __hip_atomic_load(&ctl->done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    m = s_red[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) { const u64 v = s_red[i]; m = v < m ? v : m; }
+    if (s_cnt[2]) { finished = true; break; }
+    if (m == kInf) {  // chunks missing and nothing in flight
+      if (tid == 0) { ctl->status = kStUnreachable; ctl->done = 1u; }
+      finished = true;
+      break;
     }
+    t = m;
+    __syncthreads();
+  }
+  // ---- hand the state back for the next launch
+  __syncthreads();
+  for (u32 l = tid; l < p.L; l += 1024u) { p.free_at[l] = s_free[l]; p.carry[l] = s_carry[l]; }
+  if (tid == 0 && !finished) {
+    ctl->next_t[e & 1u] = t;
+    ctl->remaining = remaining;
   }
 }
 
@@ -882,57 +869,30 @@ void launch_match(const PassDev &p, u32 event, u32 *sched_row, u32 mode, hipStre
   else launch_match_mode<2>(p, event, sched_row, s);
 }
 
-template <int NP> static hipError_t launch_sweep_np(const PassDev &p, u32 first_event, u32 n_events,
-                                                    u32 stop_event, u32 *sched_rows, u64 *event_times,
-                                                    u32 grid_blocks, hipStream_t s)
+template <int NP> static hipError_t launch_small_np(const PassDev &p, const u32 *out_ptr, const u32 *out_dst,
+                                                    u32 first_event, u32 n_events, u32 stop_event,
+                                                    u32 *sched_rows, u64 *event_times, hipStream_t s)
 {
-  PassDev pc = p;
-  void *args[] = {&pc, &first_event, &n_events, &stop_event, &sched_rows, &event_times};
-  return hipLaunchCooperativeKernel(reinterpret_cast<const void *>(&sweep_kernel<NP>), dim3(grid_blocks),
-                                    dim3(256), args, 0, s);
+  const size_t lds = small_lds_bytes(p.N, p.L, NP);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&small_sweep_kernel<NP>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(small_sweep_kernel<NP>, dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst, first_event,
+                     n_events, stop_event, sched_rows, event_times);
+  return hipGetLastError();
 }
 
-hipError_t launch_sweep(const PassDev &p, u32 first_event, u32 n_events, u32 stop_event, u32 *sched_rows,
-                        u64 *event_times, u32 grid_blocks, hipStream_t s)
+hipError_t launch_small_sweep(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
+                              u32 n_events, u32 stop_event, u32 *sched_rows, u64 *event_times, hipStream_t s)
 {
   switch (p.NP) {
-    case 1: return launch_sweep_np<1>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
-    case 2: return launch_sweep_np<2>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
-    case 3: return launch_sweep_np<3>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
-    case 4: return launch_sweep_np<4>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
-    case 5: return launch_sweep_np<5>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
-    case 6: return launch_sweep_np<6>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
-    case 7: return launch_sweep_np<7>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
-    case 8: return launch_sweep_np<8>(p, first_event, n_events, stop_event, sched_rows, event_times, grid_blocks, s);
+    case 1: return launch_small_np<1>(p, out_ptr, out_dst, first_event, n_events, stop_event, sched_rows, event_times, s);
+    case 2: return launch_small_np<2>(p, out_ptr, out_dst, first_event, n_events, stop_event, sched_rows, event_times, s);
     default: return hipErrorInvalidValue;
   }
 }
 
-template <int NP> static u32 sweep_blocks_np()
-{
-  int dev = 0, coop = 0, cus = 0, per_cu = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 0;
-  if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return 0;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sweep_kernel<NP>, 256, 0) != hipSuccess) return 0;
-  if (per_cu <= 0 || cus <= 0) return 0;
-  return (u32)per_cu * (u32)cus;
-}
-
-u32 sweep_max_blocks(u32 NP)
-{
-  switch (NP) {
-    case 1: return sweep_blocks_np<1>();
-    case 2: return sweep_blocks_np<2>();
-    case 3: return sweep_blocks_np<3>();
-    case 4: return sweep_blocks_np<4>();
-    case 5: return sweep_blocks_np<5>();
-    case 6: return sweep_blocks_np<6>();
-    case 7: return sweep_blocks_np<7>();
-    case 8: return sweep_blocks_np<8>();
-    default: return 0;
-  }
-}
+size_t small_sweep_lds_bytes(u32 N, u32 L, u32 NP) { return NP <= 2 ? small_lds_bytes(N, L, NP) : (size_t)-1; }
 
 void launch_link_counts(const u32 *rows, u32 n_rows, u32 L, u64 *counts, hipStream_t s)
 {

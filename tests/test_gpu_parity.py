@@ -193,31 +193,42 @@ def test_same_seed_same_digest_and_stream_independence(stream):
 
 def test_kernel_timing_is_reported(stream):
     topo = T.torus3d(6, 6, 4)
-    with gpu(topo, 1, MiB, T.ALL_GATHER, 1, stream, time_kernels=True, launch_mode=0) as r:
+    with gpu(topo, 1, MiB, T.ALL_GATHER, 1, stream, time_kernels=True, launch_mode=1) as r:
         assert r.kernel_launches == r.num_events      # one matching launch per span
         assert 0.0 < r.kernel_ms < r.wall_ms
-    with gpu(topo, 1, MiB, T.ALL_GATHER, 1, stream, time_kernels=True, launch_mode=1) as r:
-        assert 1 <= r.kernel_launches < r.num_events  # persistent sweeps
+    with gpu(topo, 1, MiB, T.ALL_GATHER, 1, stream, time_kernels=True, launch_mode=2) as r:
+        assert 1 <= r.kernel_launches < r.num_events  # single-workgroup sweeps
         assert 0.0 < r.kernel_ms < r.wall_ms
 
 
 @pytest.mark.parametrize("name,mk,cpn,coll", SMALL, ids=[c[0] for c in SMALL])
-def test_persistent_launch_mode_bit_exact(name, mk, cpn, coll, stream):
-    """launch_mode 1 (one cooperative launch sweeping many spans behind grid barriers)
-    gives the same schedule as the per-span launches the other tests use."""
+@pytest.mark.parametrize("mode", [1, 2])
+def test_explicit_launch_modes_bit_exact(name, mk, cpn, coll, mode, stream):
+    """launch_mode 1 (two launches per span) and 2 (one workgroup sweeping many spans with
+    the link state in LDS) give the schedule of the oracle, like the automatic mode the
+    other tests use."""
     topo = mk()
     cb = 192 << 10
     ref = cpu(topo, cpn, cb, coll, 5)
-    with gpu(topo, cpn, cb, coll, 5, stream, launch_mode=1) as r:
+    with gpu(topo, cpn, cb, coll, 5, stream, launch_mode=mode) as r:
         assert_same(r, ref, name)
 
 
 def test_both_launch_modes_on_prefix_runs(stream):
     topo = T.torus3d(4, 4, 8)
     ref = cpu(topo, 65, MiB, T.ALL_GATHER, 3, max_events=37)
-    for mode in (0, 1):
+    for mode in (0, 1, 2):
         with gpu(topo, 65, MiB, T.ALL_GATHER, 3, stream, max_events=37, launch_mode=mode) as r:
             assert_same(r, ref, f"mode {mode}")
+
+
+def test_small_topology_mode_limits(stream):
+    big = T.torus3d(16, 16, 20)  # 30,720 links do not fit one workgroup's LDS
+    with pytest.raises(binding.TacosError) as e:
+        gpu(big, 1, MiB, T.ALL_GATHER, 0, stream, launch_mode=2, max_events=2)
+    assert e.value.code == binding.TACOS_E_INVAL
+    with gpu(big, 1, MiB, T.ALL_GATHER, 0, stream, launch_mode=0, max_events=2) as r:  # automatic: per-span
+        assert r.num_events == 2
 
 
 def test_five_piece_rows_full_run(stream):
@@ -373,7 +384,7 @@ def test_postcondition_centric_limits(stream):
         gpu(fc70, 1, MiB, T.ALL_GATHER, 0, stream, matching=1)
     assert e.value.code == binding.TACOS_E_INVAL
     with pytest.raises(binding.TacosError) as e:
-        gpu(T.ring(4), 1, MiB, T.ALL_GATHER, 0, stream, matching=1, launch_mode=1)
+        gpu(T.ring(4), 1, MiB, T.ALL_GATHER, 0, stream, matching=1, launch_mode=2)
     assert e.value.code == binding.TACOS_E_INVAL
 
 
