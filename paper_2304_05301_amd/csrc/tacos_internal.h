@@ -20,12 +20,16 @@ constexpr uint32_t kStInternal = 3;
 // in flight into next_t[(e+1)&1]; the arrival kernel of event e+1 reads it as "now".
 struct Ctl {
   unsigned long long next_t[2];
-  unsigned long long remaining;  // unsatisfied postconditions (NPU, chunk)
+  unsigned long long remaining;  // unsatisfied postconditions (NPU, chunk) at the start of the pass,
+                                 // net of what the single-workgroup kernel has delivered
   unsigned long long T;          // time of the last arrival, valid once done
   uint32_t done;
   uint32_t status;
   uint32_t n_events;             // matching sweeps run, valid once done
   uint32_t pad;
+  // arrivals counted by the per-span arrival kernel, spread over 64 words so that its
+  // workgroups do not serialise on one address; unsatisfied = remaining - sum(arrived)
+  unsigned long long arrived[64];
 };
 
 // HBM layout of the per-NPU held bitsets ("precondition" rows).

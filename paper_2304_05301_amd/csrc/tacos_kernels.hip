@@ -45,6 +45,17 @@ __device__ __forceinline__ u32 wave_inclusive_scan(u32 v)
   return v;
 }
 
+__device__ __forceinline__ u64 wave_sum64(u64 v)
+{
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const u32 lo = (u32)__shfl_xor((int)(u32)v, off, 64);
+    const u32 hi = (u32)__shfl_xor((int)(u32)(v >> 32), off, 64);
+    v += ((u64)hi << 32) | lo;
+  }
+  return v;
+}
+
 __device__ __forceinline__ u64 wave_min64(u64 v)
 {
 #pragma unroll
@@ -151,6 +162,7 @@ __global__ void init_links_kernel(PassDev p)
     c->status = 0u;
     c->n_events = 0u;
     c->pad = 0u;
+    for (int i = 0; i < 64; ++i) c->arrived[i] = 0ull;
   }
 }
 
@@ -188,7 +200,7 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
   __syncthreads();
   if ((threadIdx.x & 63u) == 0 && n) atomicAdd(&block_n, n);
   __syncthreads();
-  if (threadIdx.x == 0 && block_n) atomicAdd(&ctl->remaining, (u64)0 - (u64)block_n);
+  if (threadIdx.x == 0 && block_n) atomicAdd(&ctl->arrived[blockIdx.x & 63u], (u64)block_n);
 }
 
 // ---------------------------------------------------------------- a4-a8: matching
@@ -612,7 +624,7 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
   const u32 d = uniform(p.order[slot]);
   Ctl *ctl = p.ctl;
   if (ctl->done) return;
-  const u64 rem = ctl->remaining;
+  const u64 rem = ctl->remaining - wave_sum64(ctl->arrived[lane]);
   const u64 t = ctl->next_t[event & 1u];
   if (rem == 0) {  // every postcondition satisfied: the collective ends now
     if (d == 0 && lane == 0) { ctl->T = t; ctl->n_events = event; ctl->done = 1u; }
@@ -689,7 +701,7 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
   q.carry = s_carry;
   q.free_at = s_free;
   u64 t = ctl->next_t[first_event & 1u];
-  u64 remaining = ctl->remaining;
+  u64 remaining = ctl->remaining - wave_sum64(ctl->arrived[lane]);
   u32 e = first_event;
   bool finished = false;  // uniform
   __syncthreads();
@@ -755,10 +767,9 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
   // ---- hand the state back for the next launch
   __syncthreads();
   for (u32 l = tid; l < p.L; l += 1024u) { p.free_at[l] = s_free[l]; p.carry[l] = s_carry[l]; }
-  if (tid == 0 && !finished) {
-    ctl->next_t[e & 1u] = t;
-    ctl->remaining = remaining;
-  }
+  if (tid < 64) ctl->arrived[tid] = 0ull;  // folded into `remaining` above
+  if (tid == 0 && !finished) ctl->next_t[e & 1u] = t;
+  if (tid == 0) ctl->remaining = remaining;
 }
 
 // ---------------------------------------------------------------- epilogue
