@@ -229,7 +229,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   std::vector<uint32_t> out_ptr, out_dst;
   std::vector<uint32_t> order = cluster_order(N, L, in_ptr, in_src, psrc, pdst, out_ptr, out_dst);
 
-  DevBuf d_in_ptr, d_in_link, d_in_src, d_link_dst, d_held, d_carry, d_free_at, d_ctl, d_order;
+  DevBuf d_in_ptr, d_in_link, d_in_src, d_in_rec, d_link_dst, d_held, d_carry, d_free_at, d_ctl, d_order;
   upload(d_order, order.data(), order.size(), stream);
   upload(d_in_ptr, in_ptr.data(), in_ptr.size(), stream);
   upload(d_in_link, in_link.data(), in_link.size(), stream);
@@ -238,6 +238,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   const uint32_t row_words = NP * 128u;
   d_held.alloc((size_t)N * row_words * 8);
   d_carry.alloc((size_t)L * 4);
+  d_in_rec.alloc((size_t)L * 16);
   d_free_at.alloc((size_t)L * 8);
   d_ctl.alloc(sizeof(Ctl));
 
@@ -248,6 +249,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   p.held = d_held.as<unsigned long long>();
   p.in_ptr = d_in_ptr.as<uint32_t>(); p.in_link = d_in_link.as<uint32_t>();
   p.in_src = d_in_src.as<uint32_t>(); p.link_dst = d_link_dst.as<uint32_t>();
+  p.in_rec = d_in_rec.as<uint4>();
   p.order = d_order.as<uint32_t>();
   p.cost = d_cost.as<unsigned long long>();
   p.carry = d_carry.as<uint32_t>(); p.free_at = d_free_at.as<unsigned long long>();

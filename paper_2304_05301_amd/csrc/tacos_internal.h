@@ -53,6 +53,8 @@ struct PassDev {
   const uint32_t *in_ptr;          // [N+1]
   const uint32_t *in_link;         // [L] incoming links of each NPU, ascending link id
   const uint32_t *in_src;          // [L] their source NPUs (pass orientation)
+  uint4 *in_rec;                   // [L] the in-lists as one record per entry: (link, source, cost lo, cost hi),
+                                   //     written by the set-up kernel from in_link / in_src / cost
   const uint32_t *link_dst;        // [L] destination NPU of link id (pass orientation)
   const uint32_t *order;           // [N] processing order of the destinations (a permutation)
   const unsigned long long *cost;  // [L]

@@ -151,7 +151,13 @@ __global__ void init_rows_kernel(PassDev p)
 __global__ void init_links_kernel(PassDev p)
 {
   const u32 l = blockIdx.x * blockDim.x + threadIdx.x;
-  if (l < p.L) { p.carry[l] = kNone; p.free_at[l] = 0ull; }
+  if (l < p.L) {
+    p.carry[l] = kNone; p.free_at[l] = 0ull;
+    // entry l of the in-lists gathered into one 16-byte record
+    const u32 lk = p.in_link[l];
+    const u64 cs = p.cost[lk];
+    p.in_rec[l] = make_uint4(lk, p.in_src[l], (u32)cs, (u32)(cs >> 32));
+  }
   if (l == 0) {
     Ctl *c = p.ctl;
     c->next_t[0] = 0ull;
@@ -291,27 +297,34 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
   const u32 jb = p.in_ptr[d], je = p.in_ptr[d + 1];
   u64 my_min = kInf;
 
+  // d's own row is asked for together with the in-list records, before it is known
+  // whether any incoming link is idle: one memory round trip instead of two
+  const uint4 *hp = reinterpret_cast<const uint4 *>(p.held + (u64)d * p.row_words) + lane;
+  uint4 own[NP];
+#pragma unroll
+  for (int i = 0; i < NP; ++i) own[i] = hp[i * 64];
+
   u32 l0 = 0, s0 = 0, cr0 = kNone;
   u64 cs0 = 0;
   if (jb + lane < je) {
-    l0 = p.in_link[jb + lane]; s0 = p.in_src[jb + lane];
-    cr0 = p.carry[l0]; cs0 = p.cost[l0];
+    const uint4 rec = p.in_rec[jb + lane];
+    l0 = rec.x; s0 = rec.y; cs0 = ((u64)rec.w << 32) | rec.z;
+    cr0 = p.carry[l0];
   }
   bool any_idle = __ballot(jb + lane < je && cr0 == kNone) != 0ull;
   for (u32 base = jb + 64; base < je && !any_idle; base += 64) {
     const u32 j = base + lane;
-    any_idle = __ballot(j < je && p.carry[p.in_link[j < je ? j : jb]] == kNone) != 0ull;
+    any_idle = __ballot(j < je && p.carry[p.in_rec[j < je ? j : jb].x] == kNone) != 0ull;
   }
 
   bool need_any = false;
   if (any_idle) {
     // need = ~held[d] & ~inflight[d], written to LDS; inflight[d] = the chunks on d's
     // busy incoming links, cleared by single-lane read-modify-writes
-    const uint4 *hp = reinterpret_cast<const uint4 *>(p.held + (u64)d * p.row_words) + lane;
     u32 acc = 0;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-      uint4 v = hp[i * 64];
+      uint4 v = own[i];
       v.x = ~v.x; v.y = ~v.y; v.z = ~v.z; v.w = ~v.w;
       need_lds[i * 64 + lane] = v;
       acc |= v.x | v.y | v.z | v.w;
@@ -321,7 +334,7 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
       const u32 j = base + lane;
       u32 cr = kNone;
       if (base == jb) cr = cr0;
-      else if (j < je) cr = p.carry[p.in_link[j]];
+      else if (j < je) cr = p.carry[p.in_rec[j].x];
       const u64 busy = __ballot(cr != kNone);
       if (busy && cr != kNone) {
         // every busy lane clears its own link's chunk (distinct chunks; dword updates
@@ -342,7 +355,11 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
     u64 cs = cs0;
     if (base != jb) {
       l = 0; s = 0; cr = kNone; cs = 0;
-      if (valid) { l = p.in_link[j]; s = p.in_src[j]; cr = p.carry[l]; cs = p.cost[l]; }
+      if (valid) {
+        const uint4 rec = p.in_rec[j];
+        l = rec.x; s = rec.y; cs = ((u64)rec.w << 32) | rec.z;
+        cr = p.carry[l];
+      }
     }
     u32 res = kNone;
     if (need_any) {
@@ -487,7 +504,11 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
   const bool valid = jb + lane < je;
   u32 l = 0, s = 0, cr = kNone;
   u64 cs = 0;
-  if (valid) { l = p.in_link[jb + lane]; s = p.in_src[jb + lane]; cr = p.carry[l]; cs = p.cost[l]; }
+  if (valid) {
+    const uint4 rec = p.in_rec[jb + lane];
+    l = rec.x; s = rec.y; cs = ((u64)rec.w << 32) | rec.z;
+    cr = p.carry[l];
+  }
   u64 free_links = __ballot(valid && cr == kNone);
   u32 res = kNone;
 
@@ -660,18 +681,29 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
 // d needs nothing more than then.  No random number is drawn for a link without
 // candidates, so skipping it cannot change the result.
 //
-// LDS layout (dynamic): u64 free_at[L8] | u32 carry[L] | u32 stamp[N] | u32 work[N] |
-// uint4 need[16][NP][64] | u64 red[16] | u32 counters[4].
+// In LDS an idle link's busy-until time is kInf, so the next event is a plain minimum
+// over the array, and a thread whose own links' minimum is not the span's time has no
+// arrival to look for.  A span costs four workgroup barriers; three of them order LDS
+// traffic only, so the global stores of schedule records are never waited for and the
+// arrival atomics are waited for once, after the work list has been built.
+//
+// LDS layout (dynamic): u64 free_at[L rounded up to even] | u32 carry[L] | u32 stamp[N] |
+// u32 work[N] | uint4 need[16][NP][64] | u64 red[16] | u32 counters[4] | Ctl shadow.
 __host__ __device__ inline size_t small_lds_bytes(u32 N, u32 L, u32 NP)
 {
-  size_t b = (size_t)L * 8;
+  size_t b = (((size_t)L + 1) & ~(size_t)1) * 8;
   b += ((size_t)L * 4 + 15) & ~(size_t)15;
   b += ((size_t)N * 4 + 15) & ~(size_t)15;
   b += ((size_t)N * 4 + 15) & ~(size_t)15;
   b += (size_t)16 * NP * 1024;
   b += 16 * 8 + 16;
+  b += (sizeof(Ctl) + 15) & ~(size_t)15;
   return b;
 }
+
+// Workgroup barrier that orders LDS traffic only: the wavefront's outstanding global
+// stores and atomics are not waited for.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 template <int NP>
 __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 *__restrict__ out_ptr,
@@ -681,53 +713,89 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
                                                            u64 *__restrict__ event_times)
 {
   extern __shared__ __align__(16) unsigned char lds_raw[];
+  const u32 Lp = (p.L + 1u) & ~1u;
   unsigned char *cur = lds_raw;
-  u64 *s_free = reinterpret_cast<u64 *>(cur); cur += (size_t)p.L * 8;
+  u64 *s_free = reinterpret_cast<u64 *>(cur); cur += (size_t)Lp * 8;
   u32 *s_carry = reinterpret_cast<u32 *>(cur); cur += ((size_t)p.L * 4 + 15) & ~(size_t)15;
   u32 *s_stamp = reinterpret_cast<u32 *>(cur); cur += ((size_t)p.N * 4 + 15) & ~(size_t)15;
   u32 *s_work = reinterpret_cast<u32 *>(cur); cur += ((size_t)p.N * 4 + 15) & ~(size_t)15;
   uint4 *s_need = reinterpret_cast<uint4 *>(cur); cur += (size_t)16 * NP * 1024;
   u64 *s_red = reinterpret_cast<u64 *>(cur); cur += 16 * 8;
-  u32 *s_cnt = reinterpret_cast<u32 *>(cur);  // [0] = work-list length, [1] = arrivals, [2] = stop flag
+  // [0] = destinations appended as out-neighbours, [1] = arrivals, [3] = NPUs arrived at
+  u32 *s_cnt = reinterpret_cast<u32 *>(cur); cur += 16;
+  Ctl *s_ctl = reinterpret_cast<Ctl *>(cur);  // status / done as set by the matching code
 
   const u32 tid = threadIdx.x;
   const int lane = tid & 63;
   const u32 wave = tid >> 6;
   Ctl *ctl = p.ctl;
   if (ctl->done) return;
-  for (u32 l = tid; l < p.L; l += 1024u) { s_free[l] = p.free_at[l]; s_carry[l] = p.carry[l]; }
+  for (u32 l = tid; l < Lp; l += 1024u) {
+    const u32 c = l < p.L ? p.carry[l] : kNone;
+    if (l < p.L) s_carry[l] = c;
+    s_free[l] = c != kNone ? p.free_at[l] : kInf;
+  }
   for (u32 n = tid; n < p.N; n += 1024u) s_stamp[n] = kNone;
+  if (tid == 0) {
+    s_cnt[0] = 0u; s_cnt[1] = 0u; s_cnt[3] = 0u;
+    s_ctl->status = 0u; s_ctl->done = 0u;
+  }
   PassDev q = p;  // the matching code works on the LDS copy of the link state
   q.carry = s_carry;
   q.free_at = s_free;
+  q.ctl = s_ctl;
   u64 t = ctl->next_t[first_event & 1u];
   u64 remaining = ctl->remaining - wave_sum64(ctl->arrived[lane]);
   u32 e = first_event;
   bool finished = false;  // uniform
   __syncthreads();
 
+  // a thread owns the link pairs (2*tid + 2048*i, +1); own_min = earliest busy-until of them
+  auto own_min = [&]() {
+    u64 m = kInf;
+    for (u32 l = tid * 2u; l < Lp; l += 2048u) {
+      const ulonglong2 f = *reinterpret_cast<const ulonglong2 *>(&s_free[l]);
+      m = f.x < m ? f.x : m;
+      m = f.y < m ? f.y : m;
+    }
+    return m;
+  };
+  u64 lm = own_min();
+
   for (; e < first_event + n_events; ++e) {
     u32 *row = sched_rows + (u64)(e - first_event) * p.L;
-    if (tid == 0) { event_times[e - first_event] = t; s_cnt[0] = 0u; s_cnt[1] = 0u; }
-    __syncthreads();
-    // ---- arrivals at t (a3); every NPU whose state changed, and its out-neighbours, go
-    //      on the work list once
-    for (u32 l = tid; l < p.L; l += 1024u) {
-      const u32 c = s_carry[l];
-      if (c != kNone && s_free[l] == t) {
-        const u32 d = p.link_dst[l];
-        atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
-        s_carry[l] = kNone;
-        atomicAdd(&s_cnt[1], 1u);
-        if (p.reversed) row[l] = c;
-        if (atomicExch(&s_stamp[d], e) != e) s_work[atomicAdd(&s_cnt[0], 1u)] = d;
-        for (u32 j = out_ptr[d]; j < out_ptr[d + 1]; ++j) {
-          const u32 o = out_dst[j];
-          if (atomicExch(&s_stamp[o], e) != e) s_work[atomicAdd(&s_cnt[0], 1u)] = o;
+    if (tid == 0) event_times[e - first_event] = t;
+    // ---- arrivals at t (a3): the NPUs a chunk arrived at start the work list
+    if (lm == t) {
+      for (u32 l2 = tid * 2u; l2 < Lp; l2 += 2048u) {
+#pragma unroll
+        for (u32 k = 0; k < 2u; ++k) {
+          const u32 l = l2 + k;
+          if (s_free[l] != t) continue;
+          const u32 c = s_carry[l];
+          const u32 d = p.link_dst[l];
+          atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
+          s_carry[l] = kNone;
+          s_free[l] = kInf;
+          atomicAdd(&s_cnt[1], 1u);
+          if (p.reversed) row[l] = c;
+          if (atomicExch(&s_stamp[d], e) != e) s_work[atomicAdd(&s_cnt[3], 1u)] = d;
         }
       }
     }
-    __syncthreads();
+    lds_barrier();
+    // ---- every NPU whose state changed, and its out-neighbours, go on the work list
+    //      once: one wavefront per NPU arrived at, one lane per out-neighbour
+    const u32 n_arr = s_cnt[3];
+    for (u32 i = wave; i < n_arr; i += 16u) {
+      const u32 a = uniform(s_work[i]);
+      const u32 ob = out_ptr[a], oe = out_ptr[a + 1];
+      for (u32 j = ob + (u32)lane; j < oe; j += 64u) {
+        const u32 o = out_dst[j];
+        if (atomicExch(&s_stamp[o], e) != e) s_work[n_arr + atomicAdd(&s_cnt[0], 1u)] = o;
+      }
+    }
+    __syncthreads();  // also: the arrival atomics have been performed
     remaining -= (u64)s_cnt[1];
     // ---- all postconditions satisfied? (a4)
     if (remaining == 0ull) {
@@ -737,32 +805,32 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
     }
     if (e == stop_event) break;  // prefix run: time reached is next_t[e & 1]
     // ---- matching (a5-a7) for the destinations on the work list (all of them at span 0)
-    const u32 n_work = (e == 0u) ? p.N : s_cnt[0];
+    const u32 n_work = (e == 0u) ? p.N : n_arr + s_cnt[0];
     for (u32 i = wave; i < n_work; i += 16u) {
       const u32 d = uniform((e == 0u) ? i : s_work[i]);
       (void)match_destination<NP>(q, d, e, t, p.reversed ? nullptr : row, lane, s_need + wave * NP * 64);
     }
-    __syncthreads();
+    lds_barrier();
     // ---- next span = earliest end of a transfer in flight (a8), reduced in LDS
-    u64 m = kInf;
-    for (u32 l = tid; l < p.L; l += 1024u)
-      if (s_carry[l] != kNone) { const u64 fa = s_free[l]; m = fa < m ? fa : m; }
-    m = wave_min64(m);
-    if (lane == 0) s_red[wave] = m;
-    if (tid == 0)  // an overflow flagged during matching; broadcast so that every thread leaves
-      s_cnt[2] = __hip_atomic_load(&ctl->done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    m = s_red[0];
+    lm = own_min();
+    const u64 wm = wave_min64(lm);
+    if (lane == 0) s_red[wave] = wm;
+    if (tid == 0) { s_cnt[0] = 0u; s_cnt[1] = 0u; s_cnt[3] = 0u; }
+    lds_barrier();
+    u64 m = s_red[0];
 #pragma unroll
     for (int i = 1; i < 16; ++i) { const u64 v = s_red[i]; m = v < m ? v : m; }
-    if (s_cnt[2]) { finished = true; break; }
+    if (s_ctl->done) {  // an overflow flagged during matching
+      if (tid == 0) { ctl->status = s_ctl->status; ctl->done = 1u; }
+      finished = true;
+      break;
+    }
     if (m == kInf) {  // chunks missing and nothing in flight
       if (tid == 0) { ctl->status = kStUnreachable; ctl->done = 1u; }
       finished = true;
       break;
     }
     t = m;
-    __syncthreads();
   }
   // ---- hand the state back for the next launch
   __syncthreads();
