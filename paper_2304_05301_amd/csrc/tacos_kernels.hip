@@ -56,16 +56,26 @@ __device__ __forceinline__ u64 wave_sum64(u64 v)
   return v;
 }
 
+// Minimum over the 64 lanes (uniform result) with DPP moves: a reduction towards the last
+// lane of each row of 16 (row_shr 1,2,4,8), then across rows (row_bcast:15, row_bcast:31);
+// lanes a move does not reach keep the identity (all ones).  The result is read from lane 63.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ u64 dpp_min_step(u64 v)
+{
+  const u32 lo = (u32)__builtin_amdgcn_update_dpp(-1, (int)(u32)v, CTRL, ROW_MASK, 0xF, false);
+  const u32 hi = (u32)__builtin_amdgcn_update_dpp(-1, (int)(u32)(v >> 32), CTRL, ROW_MASK, 0xF, false);
+  const u64 o = ((u64)hi << 32) | lo;
+  return o < v ? o : v;
+}
+
 __device__ __forceinline__ u64 wave_min64(u64 v)
 {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    u32 lo = (u32)__shfl_xor((int)(u32)v, off, 64);
-    u32 hi = (u32)__shfl_xor((int)(u32)(v >> 32), off, 64);
-    u64 o = ((u64)hi << 32) | lo;
-    v = o < v ? o : v;
-  }
-  return v;
+  v = dpp_min_step<0x111, 0xF>(v);
+  v = dpp_min_step<0x112, 0xF>(v);
+  v = dpp_min_step<0x114, 0xF>(v);
+  v = dpp_min_step<0x118, 0xF>(v);
+  v = dpp_min_step<0x142, 0xA>(v);
+  v = dpp_min_step<0x143, 0xC>(v);
+  return ((u64)read_lane((u32)(v >> 32), 63) << 32) | read_lane((u32)v, 63);
 }
 
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), word 0 of the output block.
@@ -688,7 +698,8 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
 // arrival atomics are waited for once, after the work list has been built.
 //
 // LDS layout (dynamic): u64 free_at[L rounded up to even] | u32 carry[L] | u32 stamp[N] |
-// u32 work[N] | uint4 need[16][NP][64] | u64 red[16] | u32 counters[4] | Ctl shadow.
+// u32 work[N] | uint4 need[16][NP][64] | u64 next[2] | u32 counters[4] | Ctl shadow |
+// (if it still fits) u32 link_dst[L].
 __host__ __device__ inline size_t small_lds_bytes(u32 N, u32 L, u32 NP)
 {
   size_t b = (((size_t)L + 1) & ~(size_t)1) * 8;
@@ -696,10 +707,11 @@ __host__ __device__ inline size_t small_lds_bytes(u32 N, u32 L, u32 NP)
   b += ((size_t)N * 4 + 15) & ~(size_t)15;
   b += ((size_t)N * 4 + 15) & ~(size_t)15;
   b += (size_t)16 * NP * 1024;
-  b += 16 * 8 + 16;
+  b += 2 * 8 + 16;
   b += (sizeof(Ctl) + 15) & ~(size_t)15;
   return b;
 }
+constexpr size_t kLdsPerWorkgroup = 160 * 1024;  // gfx950
 
 // Workgroup barrier that orders LDS traffic only: the wavefront's outstanding global
 // stores and atomics are not waited for.
@@ -710,7 +722,7 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
                                                            const u32 *__restrict__ out_dst, u32 first_event,
                                                            u32 n_events, u32 stop_event,
                                                            u32 *__restrict__ sched_rows,
-                                                           u64 *__restrict__ event_times)
+                                                           u64 *__restrict__ event_times, u32 dst_in_lds)
 {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const u32 Lp = (p.L + 1u) & ~1u;
@@ -720,10 +732,11 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
   u32 *s_stamp = reinterpret_cast<u32 *>(cur); cur += ((size_t)p.N * 4 + 15) & ~(size_t)15;
   u32 *s_work = reinterpret_cast<u32 *>(cur); cur += ((size_t)p.N * 4 + 15) & ~(size_t)15;
   uint4 *s_need = reinterpret_cast<uint4 *>(cur); cur += (size_t)16 * NP * 1024;
-  u64 *s_red = reinterpret_cast<u64 *>(cur); cur += 16 * 8;
+  u64 *s_next = reinterpret_cast<u64 *>(cur); cur += 2 * 8;  // next event time, one slot per span parity
   // [0] = destinations appended as out-neighbours, [1] = arrivals, [3] = NPUs arrived at
   u32 *s_cnt = reinterpret_cast<u32 *>(cur); cur += 16;
-  Ctl *s_ctl = reinterpret_cast<Ctl *>(cur);  // status / done as set by the matching code
+  Ctl *s_ctl = reinterpret_cast<Ctl *>(cur); cur += (sizeof(Ctl) + 15) & ~(size_t)15;  // status / done of the matching code
+  u32 *s_dst = reinterpret_cast<u32 *>(cur);
 
   const u32 tid = threadIdx.x;
   const int lane = tid & 63;
@@ -739,6 +752,12 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
   if (tid == 0) {
     s_cnt[0] = 0u; s_cnt[1] = 0u; s_cnt[3] = 0u;
     s_ctl->status = 0u; s_ctl->done = 0u;
+    s_next[0] = kInf; s_next[1] = kInf;
+  }
+  const u32 *link_dst = p.link_dst;
+  if (dst_in_lds) {
+    for (u32 l = tid; l < p.L; l += 1024u) s_dst[l] = p.link_dst[l];
+    link_dst = s_dst;
   }
   PassDev q = p;  // the matching code works on the LDS copy of the link state
   q.carry = s_carry;
@@ -773,7 +792,7 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
           const u32 l = l2 + k;
           if (s_free[l] != t) continue;
           const u32 c = s_carry[l];
-          const u32 d = p.link_dst[l];
+          const u32 d = link_dst[l];
           atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
           s_carry[l] = kNone;
           s_free[l] = kInf;
@@ -814,12 +833,10 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
     // ---- next span = earliest end of a transfer in flight (a8), reduced in LDS
     lm = own_min();
     const u64 wm = wave_min64(lm);
-    if (lane == 0) s_red[wave] = wm;
-    if (tid == 0) { s_cnt[0] = 0u; s_cnt[1] = 0u; s_cnt[3] = 0u; }
+    if (lane == 0 && wm != kInf) atomicMin(&s_next[e & 1u], wm);
+    if (tid == 0) { s_cnt[0] = 0u; s_cnt[1] = 0u; s_cnt[3] = 0u; s_next[(e + 1u) & 1u] = kInf; }
     lds_barrier();
-    u64 m = s_red[0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) { const u64 v = s_red[i]; m = v < m ? v : m; }
+    const u64 m = s_next[e & 1u];
     if (s_ctl->done) {  // an overflow flagged during matching
       if (tid == 0) { ctl->status = s_ctl->status; ctl->done = 1u; }
       finished = true;
@@ -952,12 +969,15 @@ template <int NP> static hipError_t launch_small_np(const PassDev &p, const u32 
                                                     u32 first_event, u32 n_events, u32 stop_event,
                                                     u32 *sched_rows, u64 *event_times, hipStream_t s)
 {
-  const size_t lds = small_lds_bytes(p.N, p.L, NP);
+  size_t lds = small_lds_bytes(p.N, p.L, NP);
+  const size_t dst_bytes = ((size_t)p.L * 4 + 15) & ~(size_t)15;
+  const u32 dst_in_lds = lds + dst_bytes <= kLdsPerWorkgroup ? 1u : 0u;
+  if (dst_in_lds) lds += dst_bytes;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&small_sweep_kernel<NP>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(small_sweep_kernel<NP>, dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst, first_event,
-                     n_events, stop_event, sched_rows, event_times);
+                     n_events, stop_event, sched_rows, event_times, dst_in_lds);
   return hipGetLastError();
 }
 
