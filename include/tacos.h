@@ -144,7 +144,7 @@ typedef struct {
                                       holds c, in list order (link_order 1: the cheapest);
                              which equals visiting a shuffled list of unsatisfied (d, c)
                              pairs and giving each a random free holder.  Needs in-degree
-                             <= 64 and launch_mode 0 (TACOS_E_INVAL otherwise).              */
+                             <= 64 (TACOS_E_INVAL otherwise).                                */
 } tacos_options_t;
 
 typedef struct tacos_result tacos_result_t; /* opaque; owns device and host buffers */
@@ -157,6 +157,25 @@ typedef struct tacos_result tacos_result_t; /* opaque; owns device and host buff
 int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu,
                      uint64_t chunk_bytes, tacos_collective_t coll, uint64_t seed,
                      const tacos_options_t *opts, tacos_result_t **out);
+
+/*
+ * Best of several seeds.  The matching draws at random, so the collective time varies
+ * from seed to seed (paper, "Utilization-maximizing Link-Chunk Matching": randomised
+ * choices; results of independent runs differ).  time_ps[i] (host, [n_seeds], caller-
+ * owned) receives exactly the collective time tacos_synthesize(..., seeds[i], ...)
+ * gives, num_events[i] (optional, may be NULL) its number of spans, *best (optional) the
+ * index of the smallest time, lowest index on ties.  No schedule is kept: synthesize
+ * seeds[*best] again for it.  When the topology fits the single-workgroup kernel
+ * (launch_mode 2 of tacos_synthesize) every pass of every seed is one workgroup and all
+ * of them sweep their spans concurrently, one CU each; otherwise (or with launch_mode 1)
+ * the seeds run one after the other.  opts: stream, launch_mode, link_order, matching as
+ * for tacos_synthesize; max_events must be 0.  Errors as tacos_synthesize; on error the
+ * outputs are unspecified.
+ */
+int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint64_t chunk_bytes,
+                      tacos_collective_t coll, const uint64_t *seeds, uint32_t n_seeds,
+                      const tacos_options_t *opts, uint64_t *time_ps, uint64_t *num_events,
+                      uint32_t *best);
 
 /* Time of the last arrival (All-Reduce: Reduce-Scatter time + All-Gather time). */
 uint64_t tacos_result_collective_time_ps(const tacos_result_t *r);

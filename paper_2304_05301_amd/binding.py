@@ -29,7 +29,7 @@ XFER_DTYPE = np.dtype([("t_ps", "<u8"), ("src", "<u4"), ("dst", "<u4"),
 
 # every symbol include/tacos.h declares
 EXPORTS = [
-    "tacos_synthesize", "tacos_result_collective_time_ps", "tacos_result_num_xfers",
+    "tacos_synthesize", "tacos_seed_search", "tacos_result_collective_time_ps", "tacos_result_num_xfers",
     "tacos_result_num_events", "tacos_result_num_passes", "tacos_result_pass_time_ps",
     "tacos_result_pass_events", "tacos_result_read", "tacos_result_event_trace",
     "tacos_result_link_counts", "tacos_result_digest", "tacos_result_kernel_ms", "tacos_result_kernel_launches",
@@ -72,6 +72,9 @@ def load() -> ctypes.CDLL:
     L.tacos_synthesize.restype = i32
     L.tacos_synthesize.argtypes = [ctypes.POINTER(_Topology), u32, u64, i32, u64,
                                    ctypes.POINTER(_Options), ctypes.POINTER(vp)]
+    L.tacos_seed_search.restype = i32
+    L.tacos_seed_search.argtypes = [ctypes.POINTER(_Topology), u32, u64, i32, vp, u32,
+                                    ctypes.POINTER(_Options), vp, vp, ctypes.POINTER(u32)]
     for name in ("collective_time_ps", "num_xfers", "num_events", "digest", "kernel_launches",
                  "device_bytes"):
         f = getattr(L, "tacos_result_" + name)
@@ -227,6 +230,27 @@ def tacos_synthesize(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_p
     return TacosResult(out.value)
 
 
+def tacos_seed_search(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_per_npu,
+                      chunk_bytes, collective, seeds, stream: int = 0, launch_mode: int = 0,
+                      link_order: int = 0, matching: int = 0):
+    """tacos_seed_search of include/tacos.h: (time_ps[n_seeds], num_events[n_seeds], best index)."""
+    L = load()
+    topo, keep = _topology_struct(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B)
+    opts = _Options(ctypes.c_void_p(int(stream) or None), 0, 0, int(launch_mode), int(link_order),
+                    int(matching))
+    seeds = np.ascontiguousarray(np.asarray(seeds, dtype=np.uint64))
+    times = np.zeros(len(seeds), dtype=np.uint64)
+    events = np.zeros(len(seeds), dtype=np.uint64)
+    best = ctypes.c_uint32(0)
+    rc = L.tacos_seed_search(ctypes.byref(topo), int(chunks_per_npu), int(chunk_bytes), int(collective),
+                             seeds.ctypes.data if len(seeds) else None, len(seeds), ctypes.byref(opts),
+                             times.ctypes.data, events.ctypes.data, ctypes.byref(best))
+    del keep
+    if rc != TACOS_OK:
+        _raise(rc)
+    return times, events, int(best.value)
+
+
 def tacos_link_costs(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunk_bytes) -> np.ndarray:
     L = load()
     topo, keep = _topology_struct(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B)
@@ -240,6 +264,13 @@ def tacos_link_costs(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunk_by
 
 def tacos_version() -> str:
     return load().tacos_version().decode()
+
+
+def seed_search_workload(w, seeds, **kw):
+    """Convenience: tacos_seed_search on a workload object (its own seed is not used)."""
+    t = w.topo
+    return tacos_seed_search(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B,
+                             w.chunks_per_npu, w.chunk_bytes, w.collective, seeds, **kw)
 
 
 def synthesize_workload(w, **kw) -> TacosResult:

@@ -74,6 +74,20 @@ struct PinnedCtl {
   ~PinnedCtl() { if (p) (void)hipHostFree(p); }
 };
 
+struct PinnedBuf {
+  void *p = nullptr;
+  explicit PinnedBuf(size_t n) { HIP_TRY(hipHostMalloc(&p, n ? n : 1, hipHostMallocDefault)); }
+  PinnedBuf(const PinnedBuf &) = delete;
+  PinnedBuf &operator=(const PinnedBuf &) = delete;
+  ~PinnedBuf() { if (p) (void)hipHostFree(p); }
+};
+
+// Seed search: passes per launch (one workgroup each), device bytes of their state, and
+// spans every unfinished pass advances per launch.
+constexpr size_t kSearchJobs = 2048;
+constexpr size_t kSearchBytes = 16ull << 30;
+constexpr uint64_t kSearchSpansPerLaunch = 1u << 16;
+
 template <class T> void upload(DevBuf &b, const T *src, size_t n, hipStream_t s)
 {
   b.alloc(n * sizeof(T));
@@ -184,18 +198,18 @@ std::vector<uint32_t> cluster_order(uint32_t N, uint32_t L, const std::vector<ui
   return order;
 }
 
-// Runs one All-Gather pass over links psrc[l] -> pdst[l] and stores its schedule rows.
-int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
-             const DevBuf &d_cost, uint32_t cpn, uint64_t seed, uint32_t phase, bool reversed,
-             uint64_t max_events, bool time_kernels, uint32_t launch_mode, const std::vector<uint64_t> *order_cost,
-             uint32_t match_mode, hipStream_t stream, tacos_result &res, Pass &pass)
-{
-  const uint32_t C = N * cpn;
-  const uint32_t NP = (C + 8191u) / 8192u;
-  pass.reversed = reversed;
-  pass.L = L;
-  pass.rows_per_seg = (uint32_t)std::max<size_t>(1, std::min<size_t>(kSegmentBytes / ((size_t)L * 4), 1u << 20));
+// The graph of one pass orientation on the device: in-lists (ascending link id, or
+// cheapest first), out-neighbour lists, link destinations, processing order.
+struct PassGraph {
+  uint32_t N = 0, L = 0;
+  DevBuf in_ptr, in_link, in_src, in_rec, link_dst, order, out_ptr, out_dst;
+};
 
+void build_pass_graph(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
+                      const std::vector<uint64_t> *order_cost, hipStream_t stream, PassGraph &g)
+{
+  g.N = N;
+  g.L = L;
   // incoming links of every NPU in ascending link id (stable counting sort by destination)
   std::vector<uint32_t> in_ptr(N + 1, 0), in_link(L), in_src(L);
   for (uint32_t l = 0; l < L; ++l) in_ptr[pdst[l] + 1]++;
@@ -229,31 +243,73 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   std::vector<uint32_t> out_ptr, out_dst;
   std::vector<uint32_t> order = cluster_order(N, L, in_ptr, in_src, psrc, pdst, out_ptr, out_dst);
 
-  DevBuf d_in_ptr, d_in_link, d_in_src, d_in_rec, d_link_dst, d_held, d_carry, d_free_at, d_ctl, d_order;
-  upload(d_order, order.data(), order.size(), stream);
-  upload(d_in_ptr, in_ptr.data(), in_ptr.size(), stream);
-  upload(d_in_link, in_link.data(), in_link.size(), stream);
-  upload(d_in_src, in_src.data(), in_src.size(), stream);
-  upload(d_link_dst, pdst.data(), pdst.size(), stream);
+  upload(g.order, order.data(), order.size(), stream);
+  upload(g.in_ptr, in_ptr.data(), in_ptr.size(), stream);
+  upload(g.in_link, in_link.data(), in_link.size(), stream);
+  upload(g.in_src, in_src.data(), in_src.size(), stream);
+  upload(g.link_dst, pdst.data(), pdst.size(), stream);
+  upload(g.out_ptr, out_ptr.data(), out_ptr.size(), stream);
+  upload(g.out_dst, out_dst.data(), out_dst.size(), stream);
+  g.in_rec.alloc((size_t)L * 16);
+  // the uploads read host vectors that die with this scope
+  HIP_TRY(hipStreamSynchronize(stream));
+}
+
+// Per-pass device state descriptor over a graph; held / carry / free_at / ctl are the
+// pass's own buffers.
+PassDev make_pass_dev(const PassGraph &g, const DevBuf &d_cost, uint32_t cpn, uint64_t seed, uint32_t phase,
+                      bool reversed, unsigned long long *held, uint32_t *carry, unsigned long long *free_at,
+                      Ctl *ctl)
+{
+  const uint32_t C = g.N * cpn;
+  const uint32_t NP = (C + 8191u) / 8192u;
+  PassDev p{};
+  p.N = g.N; p.L = g.L; p.cpn = cpn; p.NP = NP; p.C = C; p.phase = phase;
+  p.seed_lo = (uint32_t)(seed & 0xFFFFFFFFull); p.seed_hi = (uint32_t)(seed >> 32);
+  p.row_words = NP * 128u; p.reversed = reversed ? 1u : 0u;
+  p.held = held;
+  p.in_ptr = g.in_ptr.as<uint32_t>(); p.in_link = g.in_link.as<uint32_t>();
+  p.in_src = g.in_src.as<uint32_t>(); p.link_dst = g.link_dst.as<uint32_t>();
+  p.in_rec = g.in_rec.as<uint4>();
+  p.order = g.order.as<uint32_t>();
+  p.cost = d_cost.as<unsigned long long>();
+  p.carry = carry; p.free_at = free_at;
+  p.ctl = ctl;
+  return p;
+}
+
+// Whether the single-workgroup kernel can take this shape on the current device.
+bool fits_small_kernel(uint32_t N, uint32_t L, uint32_t NP)
+{
+  int dev = 0, lds_max = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+  const size_t need = tacos::small_sweep_lds_bytes(N, L, NP);
+  return need != (size_t)-1 && need <= (size_t)lds_max;
+}
+
+// Runs one All-Gather pass over links psrc[l] -> pdst[l] and stores its schedule rows.
+int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
+             const DevBuf &d_cost, uint32_t cpn, uint64_t seed, uint32_t phase, bool reversed,
+             uint64_t max_events, bool time_kernels, uint32_t launch_mode, const std::vector<uint64_t> *order_cost,
+             uint32_t match_mode, hipStream_t stream, tacos_result &res, Pass &pass)
+{
+  const uint32_t C = N * cpn;
+  const uint32_t NP = (C + 8191u) / 8192u;
+  pass.reversed = reversed;
+  pass.L = L;
+  pass.rows_per_seg = (uint32_t)std::max<size_t>(1, std::min<size_t>(kSegmentBytes / ((size_t)L * 4), 1u << 20));
+
+  PassGraph g;
+  build_pass_graph(N, L, psrc, pdst, order_cost, stream, g);
+  DevBuf d_held, d_carry, d_free_at, d_ctl;
   const uint32_t row_words = NP * 128u;
   d_held.alloc((size_t)N * row_words * 8);
   d_carry.alloc((size_t)L * 4);
-  d_in_rec.alloc((size_t)L * 16);
   d_free_at.alloc((size_t)L * 8);
   d_ctl.alloc(sizeof(Ctl));
-
-  PassDev p{};
-  p.N = N; p.L = L; p.cpn = cpn; p.NP = NP; p.C = C; p.phase = phase;
-  p.seed_lo = (uint32_t)(seed & 0xFFFFFFFFull); p.seed_hi = (uint32_t)(seed >> 32);
-  p.row_words = row_words; p.reversed = reversed ? 1u : 0u;
-  p.held = d_held.as<unsigned long long>();
-  p.in_ptr = d_in_ptr.as<uint32_t>(); p.in_link = d_in_link.as<uint32_t>();
-  p.in_src = d_in_src.as<uint32_t>(); p.link_dst = d_link_dst.as<uint32_t>();
-  p.in_rec = d_in_rec.as<uint4>();
-  p.order = d_order.as<uint32_t>();
-  p.cost = d_cost.as<unsigned long long>();
-  p.carry = d_carry.as<uint32_t>(); p.free_at = d_free_at.as<unsigned long long>();
-  p.ctl = d_ctl.as<Ctl>();
+  const PassDev p = make_pass_dev(g, d_cost, cpn, seed, phase, reversed, d_held.as<unsigned long long>(),
+                                  d_carry.as<uint32_t>(), d_free_at.as<unsigned long long>(), d_ctl.as<Ctl>());
   tacos::launch_init_pass(p, stream);
   HIP_TRY(hipGetLastError());
 
@@ -279,13 +335,8 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   // Small topologies: one workgroup sweeps many spans with the link state in LDS.  Chosen
   // automatically when the shape fits (launch_mode 0), forced by launch_mode 2.
   bool small = false;
-  DevBuf d_out_ptr, d_out_dst;
-  if (launch_mode != 1 && match_mode == 0) {
-    int dev = 0, lds_max = 0;
-    HIP_TRY(hipGetDevice(&dev));
-    HIP_TRY(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
-    const size_t need = tacos::small_sweep_lds_bytes(N, L, NP);
-    small = need != (size_t)-1 && need <= (size_t)lds_max;
+  if (launch_mode != 1) {
+    small = fits_small_kernel(N, L, NP);
     if (!small && launch_mode == 2) {
       g_last_error = "launch_mode 2: links, NPUs and need rows do not fit the LDS of one workgroup";
       return TACOS_E_INVAL;
@@ -293,8 +344,6 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   }
   pass.prefill = small;  // the small-topology kernel writes matches only
   if (small) {
-    upload(d_out_ptr, out_ptr.data(), out_ptr.size(), stream);
-    upload(d_out_dst, out_dst.data(), out_dst.size(), stream);
     for (;;) {
       if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
       uint32_t *row = nullptr;
@@ -311,8 +360,8 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
         ev0 = pool.ev[0]; ev1 = pool.ev[1];
         HIP_TRY(hipEventRecord(ev0, stream));
       }
-      HIP_TRY(tacos::launch_small_sweep(p, d_out_ptr.as<uint32_t>(), d_out_dst.as<uint32_t>(), (uint32_t)e,
-                                        (uint32_t)n, stop_event, row, tslot, stream));
+      HIP_TRY(tacos::launch_small_sweep(p, g.out_ptr.as<uint32_t>(), g.out_dst.as<uint32_t>(), (uint32_t)e,
+                                        (uint32_t)n, stop_event, row, tslot, match_mode, stream));
       if (time_kernels) HIP_TRY(hipEventRecord(ev1, stream));
       HIP_TRY(hipMemcpyAsync(host_ctl.p, p.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, stream));
       HIP_TRY(hipStreamSynchronize(stream));
@@ -479,6 +528,27 @@ int device_costs(const tacos_topology_t *topo, uint64_t chunk_bytes, hipStream_t
   return ovf ? TACOS_E_OVERFLOW : TACOS_OK;
 }
 
+// Kernel matching mode from the options: 0 link-centric; 1 postcondition-centric, random
+// holder; 2 postcondition-centric, first holder of the cheapest-first list.
+int resolve_match_mode(const tacos_topology_t *topo, int coll, const tacos_options_t *opts, uint32_t *mode)
+{
+  *mode = 0;
+  if (!opts || opts->matching == TACOS_MATCH_LINK_CENTRIC) return TACOS_OK;
+  if (opts->matching != TACOS_MATCH_POSTCONDITION) return TACOS_E_INVAL;
+  std::vector<uint32_t> deg_in(topo->n_npus, 0), deg_out(topo->n_npus, 0);
+  for (uint32_t i = 0; i < topo->n_npus; ++i) {
+    deg_out[i] = topo->row_ptr[i + 1] - topo->row_ptr[i];
+    for (uint32_t l = topo->row_ptr[i]; l < topo->row_ptr[i + 1]; ++l) deg_in[topo->col_idx[l]]++;
+  }
+  for (uint32_t i = 0; i < topo->n_npus; ++i) {
+    // the reversed pass of a Reduce-Scatter walks the out-links as incoming links
+    const bool fwd = coll != TACOS_REDUCE_SCATTER, rev = coll != TACOS_ALL_GATHER;
+    if ((fwd && deg_in[i] > 64) || (rev && deg_out[i] > 64)) return TACOS_E_INVAL;
+  }
+  *mode = opts->link_order == TACOS_LINK_ORDER_COST ? 2u : 1u;
+  return TACOS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -498,20 +568,8 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
     return TACOS_E_INVAL;
   // kernel variant: 0 link-centric; 1 postcondition-centric, random holder; 2 first holder
   uint32_t match_mode = 0;
-  if (opts && opts->matching == TACOS_MATCH_POSTCONDITION) {
-    if (opts->launch_mode == 2) return TACOS_E_INVAL;
-    std::vector<uint32_t> deg_in(topo->n_npus, 0), deg_out(topo->n_npus, 0);
-    for (uint32_t i = 0; i < topo->n_npus; ++i) {
-      deg_out[i] = topo->row_ptr[i + 1] - topo->row_ptr[i];
-      for (uint32_t l = topo->row_ptr[i]; l < topo->row_ptr[i + 1]; ++l) deg_in[topo->col_idx[l]]++;
-    }
-    for (uint32_t i = 0; i < topo->n_npus; ++i) {
-      // the reversed pass of a Reduce-Scatter walks the out-links as incoming links
-      const bool fwd = coll != TACOS_REDUCE_SCATTER, rev = coll != TACOS_ALL_GATHER;
-      if ((fwd && deg_in[i] > 64) || (rev && deg_out[i] > 64)) return TACOS_E_INVAL;
-    }
-    match_mode = opts->link_order == TACOS_LINK_ORDER_COST ? 2u : 1u;
-  }
+  rc = resolve_match_mode(topo, (int)coll, opts, &match_mode);
+  if (rc != TACOS_OK) return rc;
   const bool time_kernels = opts && opts->time_kernels;
   const uint32_t launch_mode = opts ? opts->launch_mode : 0;
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
@@ -579,6 +637,145 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
   }
   res->wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - wall0).count();
   *out = res.release();
+  return TACOS_OK;
+}
+
+int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint64_t chunk_bytes,
+                      tacos_collective_t coll, const uint64_t *seeds, uint32_t n_seeds,
+                      const tacos_options_t *opts, uint64_t *time_ps, uint64_t *num_events, uint32_t *best)
+{
+  g_last_error.clear();
+  if (!seeds || n_seeds == 0 || !time_ps) return TACOS_E_INVAL;
+  int rc = validate(topo, chunks_per_npu, chunk_bytes, (int)coll);
+  if (rc != TACOS_OK) return rc;
+  if (opts && (opts->max_events != 0 || opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 2 ||
+               opts->matching > TACOS_MATCH_POSTCONDITION))
+    return TACOS_E_INVAL;
+  uint32_t match_mode = 0;
+  rc = resolve_match_mode(topo, (int)coll, opts, &match_mode);
+  if (rc != TACOS_OK) return rc;
+  const uint32_t launch_mode = opts ? opts->launch_mode : 0;
+  hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
+  int device = 0;
+  rc = require_device(&device);
+  if (rc != TACOS_OK) return rc;
+
+  const uint32_t N = topo->n_npus, L = topo->n_links;
+  auto pick_best = [&]() {
+    uint32_t b = 0;
+    for (uint32_t i = 1; i < n_seeds; ++i)
+      if (time_ps[i] < time_ps[b]) b = i;
+    if (best) *best = b;
+  };
+  if (N == 1) {
+    for (uint32_t i = 0; i < n_seeds; ++i) { time_ps[i] = 0; if (num_events) num_events[i] = 0; }
+    pick_best();
+    return TACOS_OK;
+  }
+  if (L == 0) return TACOS_E_UNREACHABLE;
+
+  try {
+    const uint32_t C = N * chunks_per_npu;
+    const uint32_t NP = (C + 8191u) / 8192u;
+    const bool concurrent = launch_mode != 1 && fits_small_kernel(N, L, NP);
+    if (!concurrent && launch_mode == 2) {
+      g_last_error = "launch_mode 2: links, NPUs and need rows do not fit the LDS of one workgroup";
+      return TACOS_E_INVAL;
+    }
+    if (!concurrent) {
+      // a topology this large fills the GPU by itself: one seed after the other
+      for (uint32_t i = 0; i < n_seeds; ++i) {
+        tacos_result_t *r = nullptr;
+        rc = tacos_synthesize(topo, chunks_per_npu, chunk_bytes, coll, seeds[i], opts, &r);
+        if (rc != TACOS_OK) return rc;
+        time_ps[i] = r->collective_time;
+        if (num_events) num_events[i] = r->n_events;
+        tacos_result_free(r);
+      }
+      pick_best();
+      return TACOS_OK;
+    }
+
+    std::vector<uint32_t> link_src(L), link_dst(topo->col_idx, topo->col_idx + L);
+    for (uint32_t i = 0; i < N; ++i)
+      for (uint32_t l = topo->row_ptr[i]; l < topo->row_ptr[i + 1]; ++l) link_src[l] = i;
+    DevBuf d_cost;
+    std::vector<uint64_t> host_cost;
+    const bool by_cost = opts && opts->link_order == TACOS_LINK_ORDER_COST;
+    rc = device_costs(topo, chunk_bytes, stream, d_cost, by_cost ? &host_cost : nullptr);
+    if (rc != TACOS_OK) return rc;
+    const std::vector<uint64_t> *order_cost = by_cost ? &host_cost : nullptr;
+    const bool want_rev = coll != TACOS_ALL_GATHER, want_fwd = coll != TACOS_REDUCE_SCATTER;
+    PassGraph g_rev, g_fwd;
+    if (want_rev) build_pass_graph(N, L, link_dst, link_src, order_cost, stream, g_rev);
+    if (want_fwd) build_pass_graph(N, L, link_src, link_dst, order_cost, stream, g_fwd);
+    const uint32_t per_seed = (want_rev ? 1u : 0u) + (want_fwd ? 1u : 0u);
+
+    // groups of seeds whose passes (one workgroup each) run in one launch
+    const size_t row_bytes = (size_t)NP * 128u * 8u;
+    const size_t job_bytes = (size_t)N * row_bytes + (size_t)L * 12 + sizeof(Ctl);
+    const uint32_t group_seeds = (uint32_t)std::max<size_t>(1, std::min<size_t>(kSearchJobs / per_seed,
+                                                                            kSearchBytes / (job_bytes * per_seed)));
+    for (uint32_t s0 = 0; s0 < n_seeds; s0 += group_seeds) {
+      const uint32_t ns = std::min(group_seeds, n_seeds - s0);
+      const uint32_t n_jobs = ns * per_seed;
+      DevBuf d_held((size_t)n_jobs * N * row_bytes), d_carry((size_t)n_jobs * L * 4),
+          d_free((size_t)n_jobs * L * 8), d_ctl((size_t)n_jobs * sizeof(Ctl)), d_jobs;
+      std::vector<tacos::SmallJob> jobs(n_jobs);
+      for (uint32_t i = 0; i < ns; ++i) {
+        for (uint32_t k = 0; k < per_seed; ++k) {
+          const uint32_t j = i * per_seed + k;
+          const bool rev = want_rev && k == 0;
+          const PassGraph &g = rev ? g_rev : g_fwd;
+          jobs[j].p = make_pass_dev(g, d_cost, chunks_per_npu, seeds[s0 + i], rev ? 1u : 0u, rev,
+                                    d_held.as<unsigned long long>() + (size_t)j * N * (row_bytes / 8),
+                                    d_carry.as<uint32_t>() + (size_t)j * L,
+                                    d_free.as<unsigned long long>() + (size_t)j * L, d_ctl.as<Ctl>() + j);
+          jobs[j].out_ptr = g.out_ptr.as<uint32_t>();
+          jobs[j].out_dst = g.out_dst.as<uint32_t>();
+          tacos::launch_init_pass(jobs[j].p, stream);
+        }
+      }
+      HIP_TRY(hipGetLastError());
+      upload(d_jobs, jobs.data(), jobs.size(), stream);
+      HIP_TRY(hipStreamSynchronize(stream));
+      PinnedBuf host_ctl((size_t)n_jobs * sizeof(Ctl));
+      const Ctl *hc = static_cast<const Ctl *>(host_ctl.p);
+      uint64_t e = 0;
+      for (;;) {
+        if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
+        const uint32_t n = (uint32_t)std::min<uint64_t>(kSearchSpansPerLaunch, 0xFFFFFFFEull - e);
+        HIP_TRY(tacos::launch_small_sweep_batch(d_jobs.as<tacos::SmallJob>(), n_jobs, jobs[0].p, (uint32_t)e, n,
+                                                match_mode, stream));
+        HIP_TRY(hipMemcpyAsync(host_ctl.p, d_ctl.p, (size_t)n_jobs * sizeof(Ctl), hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        e += n;
+        bool all_done = true;
+        for (uint32_t j = 0; j < n_jobs; ++j) all_done = all_done && hc[j].done != 0;
+        if (all_done) break;
+      }
+      for (uint32_t j = 0; j < n_jobs; ++j) {
+        if (hc[j].status == tacos::kStUnreachable) return TACOS_E_UNREACHABLE;
+        if (hc[j].status == tacos::kStOverflow) return TACOS_E_OVERFLOW;
+        if (hc[j].status == tacos::kStInternal) {
+          g_last_error = "internal: matching produced a chunk id out of range";
+          return TACOS_E_DEVICE;
+        }
+      }
+      for (uint32_t i = 0; i < ns; ++i) {
+        uint64_t T = 0, ev = 0;
+        for (uint32_t k = 0; k < per_seed; ++k) { T += hc[i * per_seed + k].T; ev += hc[i * per_seed + k].n_events; }
+        time_ps[s0 + i] = T;
+        if (num_events) num_events[s0 + i] = ev;
+      }
+    }
+  } catch (const HipFail &f) {
+    return f.code;
+  } catch (const std::bad_alloc &) {
+    g_last_error = "host allocation failed";
+    return TACOS_E_NOMEM;
+  }
+  pick_best();
   return TACOS_OK;
 }
 

@@ -81,13 +81,24 @@ void launch_match(const PassDev &p, uint32_t event, uint32_t *sched_row, uint32_
 // a3-a8 fused for small topologies: ONE workgroup sweeps spans [first_event,
 // first_event+n_events) with the per-link state in LDS (arrivals, termination test,
 // matching of the destinations something changed for, next-event min-reduction) and
-// returns early when the pass ends.  stop_event: the span at which only the arrivals are
+// returns early when the pass ends.  mode: as launch_match.  stop_event: the span at which only the arrivals are
 // applied (prefix runs), or 0xFFFFFFFF.  sched_rows / event_times point at the slots of
 // first_event; the rows must be pre-filled with kNone.  out_ptr/out_dst: out-neighbour
 // lists of the pass orientation.  Needs small_sweep_lds_bytes(...) of dynamic LDS.
 hipError_t launch_small_sweep(const PassDev &p, const uint32_t *out_ptr, const uint32_t *out_dst,
                               uint32_t first_event, uint32_t n_events, uint32_t stop_event,
-                              uint32_t *sched_rows, unsigned long long *event_times, hipStream_t s);
+                              uint32_t *sched_rows, unsigned long long *event_times, uint32_t mode,
+                              hipStream_t s);
+// The same sweep for n_jobs independent passes of one shape at once, one workgroup each
+// (jobs: device array); collective times only, no schedule rows.  p0: any of the jobs'
+// PassDev (shape).  Every unfinished job advances by n_events spans from first_event.
+struct SmallJob {
+  PassDev p;
+  const uint32_t *out_ptr;
+  const uint32_t *out_dst;
+};
+hipError_t launch_small_sweep_batch(const SmallJob *jobs, uint32_t n_jobs, const PassDev &p0,
+                                    uint32_t first_event, uint32_t n_events, uint32_t mode, hipStream_t s);
 // LDS the small-topology kernel needs, (size_t)-1 if the shape is not supported
 size_t small_sweep_lds_bytes(uint32_t N, uint32_t L, uint32_t NP);
 // epilogue: per-row match counts and the schedule digest of a block of rows

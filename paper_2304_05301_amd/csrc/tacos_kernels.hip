@@ -717,12 +717,11 @@ constexpr size_t kLdsPerWorkgroup = 160 * 1024;  // gfx950
 // stores and atomics are not waited for.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int NP>
-__global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 *__restrict__ out_ptr,
-                                                           const u32 *__restrict__ out_dst, u32 first_event,
-                                                           u32 n_events, u32 stop_event,
-                                                           u32 *__restrict__ sched_rows,
-                                                           u64 *__restrict__ event_times, u32 dst_in_lds)
+template <int NP, int MODE>
+__device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__restrict__ out_ptr,
+                                                 const u32 *__restrict__ out_dst, u32 first_event,
+                                                 u32 n_events, u32 stop_event, u32 *__restrict__ sched_rows,
+                                                 u64 *__restrict__ event_times, u32 dst_in_lds)
 {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const u32 Lp = (p.L + 1u) & ~1u;
@@ -782,8 +781,8 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
   u64 lm = own_min();
 
   for (; e < first_event + n_events; ++e) {
-    u32 *row = sched_rows + (u64)(e - first_event) * p.L;
-    if (tid == 0) event_times[e - first_event] = t;
+    u32 *row = sched_rows ? sched_rows + (u64)(e - first_event) * p.L : nullptr;  // null: times only
+    if (tid == 0 && event_times) event_times[e - first_event] = t;
     // ---- arrivals at t (a3): the NPUs a chunk arrived at start the work list
     if (lm == t) {
       for (u32 l2 = tid * 2u; l2 < Lp; l2 += 2048u) {
@@ -797,7 +796,7 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
           s_carry[l] = kNone;
           s_free[l] = kInf;
           atomicAdd(&s_cnt[1], 1u);
-          if (p.reversed) row[l] = c;
+          if (p.reversed && row) row[l] = c;
           if (atomicExch(&s_stamp[d], e) != e) s_work[atomicAdd(&s_cnt[3], 1u)] = d;
         }
       }
@@ -827,7 +826,11 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
     const u32 n_work = (e == 0u) ? p.N : n_arr + s_cnt[0];
     for (u32 i = wave; i < n_work; i += 16u) {
       const u32 d = uniform((e == 0u) ? i : s_work[i]);
-      (void)match_destination<NP>(q, d, e, t, p.reversed ? nullptr : row, lane, s_need + wave * NP * 64);
+      if constexpr (MODE == 0)
+        (void)match_destination<NP>(q, d, e, t, p.reversed ? nullptr : row, lane, s_need + wave * NP * 64);
+      else
+        (void)match_destination_pairs<NP>(q, d, e, t, p.reversed ? nullptr : row, lane, s_need + wave * NP * 64,
+                                          MODE == 2);
     }
     lds_barrier();
     // ---- next span = earliest end of a transfer in flight (a8), reduced in LDS
@@ -855,6 +858,28 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
   if (tid < 64) ctl->arrived[tid] = 0ull;  // folded into `remaining` above
   if (tid == 0 && !finished) ctl->next_t[e & 1u] = t;
   if (tid == 0) ctl->remaining = remaining;
+}
+
+template <int NP, int MODE>
+__global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 *__restrict__ out_ptr,
+                                                           const u32 *__restrict__ out_dst, u32 first_event,
+                                                           u32 n_events, u32 stop_event,
+                                                           u32 *__restrict__ sched_rows,
+                                                           u64 *__restrict__ event_times, u32 dst_in_lds)
+{
+  small_sweep_body<NP, MODE>(p, out_ptr, out_dst, first_event, n_events, stop_event, sched_rows, event_times,
+                             dst_in_lds);
+}
+
+// Many independent passes at once (one per workgroup, each with its own seed, rows, link
+// state and control block): only the collective times are wanted, no schedule is kept.
+template <int NP, int MODE>
+__global__ __launch_bounds__(1024) void small_sweep_batch_kernel(const SmallJob *__restrict__ jobs, u32 first_event,
+                                                                 u32 n_events, u32 dst_in_lds)
+{
+  const SmallJob &j = jobs[blockIdx.x];
+  small_sweep_body<NP, MODE>(j.p, j.out_ptr, j.out_dst, first_event, n_events, 0xFFFFFFFFu, nullptr, nullptr,
+                             dst_in_lds);
 }
 
 // ---------------------------------------------------------------- epilogue
@@ -965,30 +990,77 @@ void launch_match(const PassDev &p, u32 event, u32 *sched_row, u32 mode, hipStre
   else launch_match_mode<2>(p, event, sched_row, s);
 }
 
-template <int NP> static hipError_t launch_small_np(const PassDev &p, const u32 *out_ptr, const u32 *out_dst,
-                                                    u32 first_event, u32 n_events, u32 stop_event,
-                                                    u32 *sched_rows, u64 *event_times, hipStream_t s)
+static size_t small_launch_lds(const PassDev &p, u32 *dst_in_lds)
 {
-  size_t lds = small_lds_bytes(p.N, p.L, NP);
+  size_t lds = small_lds_bytes(p.N, p.L, p.NP);
   const size_t dst_bytes = ((size_t)p.L * 4 + 15) & ~(size_t)15;
-  const u32 dst_in_lds = lds + dst_bytes <= kLdsPerWorkgroup ? 1u : 0u;
-  if (dst_in_lds) lds += dst_bytes;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&small_sweep_kernel<NP>),
+  *dst_in_lds = lds + dst_bytes <= kLdsPerWorkgroup ? 1u : 0u;
+  if (*dst_in_lds) lds += dst_bytes;
+  return lds;
+}
+
+template <int NP, int MODE>
+static hipError_t launch_small_np(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
+                                  u32 n_events, u32 stop_event, u32 *sched_rows, u64 *event_times, hipStream_t s)
+{
+  u32 dst_in_lds = 0;
+  const size_t lds = small_launch_lds(p, &dst_in_lds);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&small_sweep_kernel<NP, MODE>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(small_sweep_kernel<NP>, dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst, first_event,
+  hipLaunchKernelGGL((small_sweep_kernel<NP, MODE>), dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst, first_event,
                      n_events, stop_event, sched_rows, event_times, dst_in_lds);
   return hipGetLastError();
 }
 
-hipError_t launch_small_sweep(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
-                              u32 n_events, u32 stop_event, u32 *sched_rows, u64 *event_times, hipStream_t s)
+template <int NP, int MODE>
+static hipError_t launch_batch_np(const SmallJob *jobs, u32 n_jobs, const PassDev &p0, u32 first_event,
+                                  u32 n_events, hipStream_t s)
 {
-  switch (p.NP) {
-    case 1: return launch_small_np<1>(p, out_ptr, out_dst, first_event, n_events, stop_event, sched_rows, event_times, s);
-    case 2: return launch_small_np<2>(p, out_ptr, out_dst, first_event, n_events, stop_event, sched_rows, event_times, s);
+  u32 dst_in_lds = 0;
+  const size_t lds = small_launch_lds(p0, &dst_in_lds);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&small_sweep_batch_kernel<NP, MODE>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((small_sweep_batch_kernel<NP, MODE>), dim3(n_jobs), dim3(1024), lds, s, jobs, first_event,
+                     n_events, dst_in_lds);
+  return hipGetLastError();
+}
+
+hipError_t launch_small_sweep(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
+                              u32 n_events, u32 stop_event, u32 *sched_rows, u64 *event_times, u32 mode,
+                              hipStream_t s)
+{
+#define TACOS_SMALL(NP_, M_) \
+  return launch_small_np<NP_, M_>(p, out_ptr, out_dst, first_event, n_events, stop_event, sched_rows, event_times, s)
+  if (mode > 2) return hipErrorInvalidValue;
+  switch (p.NP * 4 + mode) {
+    case 4: TACOS_SMALL(1, 0);
+    case 5: TACOS_SMALL(1, 1);
+    case 6: TACOS_SMALL(1, 2);
+    case 8: TACOS_SMALL(2, 0);
+    case 9: TACOS_SMALL(2, 1);
+    case 10: TACOS_SMALL(2, 2);
     default: return hipErrorInvalidValue;
   }
+#undef TACOS_SMALL
+}
+
+hipError_t launch_small_sweep_batch(const SmallJob *jobs, u32 n_jobs, const PassDev &p0, u32 first_event,
+                                    u32 n_events, u32 mode, hipStream_t s)
+{
+#define TACOS_BATCH(NP_, M_) return launch_batch_np<NP_, M_>(jobs, n_jobs, p0, first_event, n_events, s)
+  if (mode > 2 || n_jobs == 0) return hipErrorInvalidValue;
+  switch (p0.NP * 4 + mode) {
+    case 4: TACOS_BATCH(1, 0);
+    case 5: TACOS_BATCH(1, 1);
+    case 6: TACOS_BATCH(1, 2);
+    case 8: TACOS_BATCH(2, 0);
+    case 9: TACOS_BATCH(2, 1);
+    case 10: TACOS_BATCH(2, 2);
+    default: return hipErrorInvalidValue;
+  }
+#undef TACOS_BATCH
 }
 
 size_t small_sweep_lds_bytes(u32 N, u32 L, u32 NP) { return NP <= 2 ? small_lds_bytes(N, L, NP) : (size_t)-1; }

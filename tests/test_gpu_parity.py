@@ -367,14 +367,17 @@ PAIR_CASES = [
 
 @pytest.mark.parametrize("name,mk,cpn,coll", PAIR_CASES, ids=[c[0] for c in PAIR_CASES])
 @pytest.mark.parametrize("link_order", [0, 1])
-def test_postcondition_centric_matching_bit_exact(name, mk, cpn, coll, link_order, stream):
+@pytest.mark.parametrize("launch_mode", [1, 2])
+def test_postcondition_centric_matching_bit_exact(name, mk, cpn, coll, link_order, launch_mode, stream):
     """matching = 1 (Algorithm 1 in the order the paper prints it) against the oracle's
-    same mode, with random and with cheapest-first holder links."""
+    same mode, with random and with cheapest-first holder links, through the per-span
+    launches and through the single-workgroup kernel."""
     topo = mk()
     cb = 96 << 10
     kw = dict(max_events=60) if cpn == 65 else {}
     ref = cpu(topo, cpn, cb, coll, 23, matching=1, link_order=link_order, **kw)
-    with gpu(topo, cpn, cb, coll, 23, stream, matching=1, link_order=link_order, **kw) as r:
+    with gpu(topo, cpn, cb, coll, 23, stream, matching=1, link_order=link_order, launch_mode=launch_mode,
+             **kw) as r:
         assert_same(r, ref, name)
 
 
@@ -382,9 +385,6 @@ def test_postcondition_centric_limits(stream):
     fc70 = T.fully_connected(70)  # in-degree 69 > 64
     with pytest.raises(binding.TacosError) as e:
         gpu(fc70, 1, MiB, T.ALL_GATHER, 0, stream, matching=1)
-    assert e.value.code == binding.TACOS_E_INVAL
-    with pytest.raises(binding.TacosError) as e:
-        gpu(T.ring(4), 1, MiB, T.ALL_GATHER, 0, stream, matching=1, launch_mode=2)
     assert e.value.code == binding.TACOS_E_INVAL
 
 
@@ -397,3 +397,93 @@ def test_postcondition_centric_workload_5_prefix(stream):
         assert r.num_xfers == ref.n_xfers and r.digest == ref.digest
         assert np.array_equal(r.read(0, 1 << 20), ref.xfers[:1 << 20])
         assert np.array_equal(r.read(r.num_xfers - (1 << 20), 1 << 20), ref.xfers[-(1 << 20):])
+
+
+# ---------------------------------------------------------------- best of several seeds
+
+def search(topo, cpn, cb, coll, seeds, stream, **kw):
+    return binding.tacos_seed_search(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps,
+                                     topo.beta_fs_per_B, cpn, cb, coll, seeds, stream=stream, **kw)
+
+
+def oracle_times(topo, cpn, cb, coll, seeds, **kw):
+    out = [cpu(topo, cpn, cb, coll, int(s), keep_xfers=0, **kw) for s in seeds]
+    return (np.array([o.collective_time_ps for o in out], dtype=np.uint64),
+            np.array([o.n_events for o in out], dtype=np.uint64))
+
+
+SEARCH_CASES = [
+    ("ring8_ag", lambda: T.ring(8), 1, T.ALL_GATHER),
+    ("mesh5x4_ar", lambda: T.mesh2d(5, 4), 3, T.ALL_REDUCE),
+    ("hetero_torus_ar", lambda: T.grid([3, 3, 4], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000]), 3, T.ALL_REDUCE),
+    ("random40_rs", lambda: T.random_regular_out(40, 3, seed=7)[0], 2, T.REDUCE_SCATTER),
+    ("torus4x4x8_c8320_ag", lambda: T.torus3d(4, 4, 8), 65, T.ALL_GATHER),
+]
+
+
+@pytest.mark.parametrize("name,mk,cpn,coll", SEARCH_CASES, ids=[c[0] for c in SEARCH_CASES])
+@pytest.mark.parametrize("matching,link_order", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_seed_search_equals_one_oracle_run_per_seed(name, mk, cpn, coll, matching, link_order, stream):
+    """Every seed's collective time and span count from the concurrent search are the
+    oracle's for that seed; the best index is the first minimum."""
+    topo = mk()
+    cb = 200 << 10
+    seeds = np.arange(100, 100 + (5 if cpn == 65 else 19), dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15)
+    want_t, want_e = oracle_times(topo, cpn, cb, coll, seeds, matching=matching, link_order=link_order)
+    times, events, best = search(topo, cpn, cb, coll, seeds, stream, matching=matching, link_order=link_order)
+    assert np.array_equal(times, want_t), name
+    assert np.array_equal(events, want_e), name
+    assert best == int(np.argmin(want_t))
+
+
+def test_seed_search_more_passes_than_compute_units(stream):
+    """600 seeds of an All-Reduce = 1200 single-workgroup passes in one launch (256 CUs)."""
+    topo = T.grid([3, 3], True, [300_000, 700_000], [5_000, 20_000])
+    seeds = np.arange(600, dtype=np.uint64)
+    want_t, want_e = oracle_times(topo, 2, MiB, T.ALL_REDUCE, seeds)
+    times, events, best = search(topo, 2, MiB, T.ALL_REDUCE, seeds, stream)
+    assert np.array_equal(times, want_t) and np.array_equal(events, want_e)
+    assert best == int(np.argmin(want_t))
+    assert len(set(times.tolist())) > 1  # the seeds do differ in quality
+
+
+def test_seed_search_sequential_path_and_single_run_agree(stream):
+    topo = T.random_regular_out(24, 3, seed=5)[0]
+    seeds = np.array([7, 7, 1 << 63, 0], dtype=np.uint64)
+    a = search(topo, 2, MiB, T.ALL_REDUCE, seeds, stream, launch_mode=1)
+    b = search(topo, 2, MiB, T.ALL_REDUCE, seeds, stream, launch_mode=2)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and a[2] == b[2]
+    assert a[0][0] == a[0][1]
+    with gpu(topo, 2, MiB, T.ALL_REDUCE, int(seeds[a[2]]), stream) as r:
+        assert r.collective_time_ps == int(a[0][a[2]]) and r.num_events == int(a[1][a[2]])
+
+
+def test_seed_search_workload_4_against_stored_oracle_values(stream):
+    """Three seeds of the 1024-NPU heterogeneous workload (about a million spans each),
+    against values written by tests/golden/make_golden.py from the oracle."""
+    with open(os.path.join(os.path.dirname(GOLDEN), "seed_search_oracle.json")) as f:
+        g = json.load(f)
+    w = T.workload(4)
+    seeds = np.array(g["seeds"], dtype=np.uint64)
+    times, events, best = binding.seed_search_workload(w, seeds, stream=stream)
+    assert times.tolist() == g["collective_time_ps"]
+    assert events.tolist() == g["n_events"]
+    assert best == int(np.argmin(np.array(g["collective_time_ps"], dtype=np.uint64)))
+
+
+def test_seed_search_errors_and_degenerate_inputs(stream):
+    ring = T.ring(6)
+    with pytest.raises(binding.TacosError) as e:
+        search(ring, 1, MiB, T.ALL_GATHER, [], stream)
+    assert e.value.code == binding.TACOS_E_INVAL
+    big = T.torus3d(16, 16, 16)  # 24,576 links do not fit the LDS of one workgroup
+    with pytest.raises(binding.TacosError) as e:
+        search(big, 1, MiB, T.ALL_GATHER, [1, 2], stream, launch_mode=2)
+    assert e.value.code == binding.TACOS_E_INVAL
+    one = T.from_edge_list(1, [])
+    times, events, best = search(one, 4, MiB, T.ALL_REDUCE, [3, 4, 5], stream)
+    assert times.tolist() == [0, 0, 0] and events.tolist() == [0, 0, 0] and best == 0
+    broken = T.from_edge_list(3, [(0, 1, 1000, 10), (1, 0, 1000, 10), (0, 2, 1000, 10)])  # 2 cannot send
+    with pytest.raises(binding.TacosError) as e:
+        search(broken, 1, MiB, T.ALL_GATHER, [1, 2, 3], stream)
+    assert e.value.code == binding.TACOS_E_UNREACHABLE
