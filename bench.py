@@ -131,6 +131,31 @@ def report_all(binding, T, stream, with_cpu):
               f"{r['alg_GBps'] / HBM_PEAK_GBS:.4f} | {cpu} |")
 
 
+def report_seed_search(binding, T, stream):
+    """Best-of-K seeds on the workloads that fit the single-workgroup kernel: K single
+    syntheses' worth of spans in about the time of one."""
+    import numpy as np
+    print()
+    print("| workload | matching | seeds | search (s) | spans swept | spans/s | one synthesis (s) | best T (ps) | "
+          "median T (ps) | worst T (ps) |")
+    print("|---|---|---|---|---|---|---|---|---|---|")
+    for idx, k, matching in ((2, 1024, 0), (3, 1024, 0), (3, 1024, 1), (4, 256, 0)):
+        w = T.workload(idx)
+        seeds = np.arange(k, dtype=np.uint64)
+        binding.seed_search_workload(w, seeds[:2], stream=stream, matching=matching)
+        t0 = time.perf_counter()
+        times, events, best = binding.seed_search_workload(w, seeds, stream=stream, matching=matching)
+        dt = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        binding.tacos_seed_search(w.topo.n_npus, w.topo.row_ptr, w.topo.col_idx, w.topo.alpha_ps,
+                                  w.topo.beta_fs_per_B, w.chunks_per_npu, w.chunk_bytes, w.collective,
+                                  seeds[best:best + 1], stream=stream, matching=matching)
+        one = time.perf_counter() - t0
+        print(f"| {w.name} | {matching} | {k} | {dt:.3f} | {int(events.sum())} | {events.sum() / dt:.3g} | {one:.3f} | "
+              f"{int(times.min())} | {int(np.median(times))} | {int(times.max())} |")
+        print(f"[report] seed search on workload {idx} done", file=sys.stderr, flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -159,6 +184,7 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     if args.report_all:
         report_all(binding, T, stream, not args.no_cpu_baseline)
+        report_seed_search(binding, T, stream)
         return
     w = T.workload(args.workload)
     topo = w.topo

@@ -202,7 +202,7 @@ std::vector<uint32_t> cluster_order(uint32_t N, uint32_t L, const std::vector<ui
 // cheapest first), out-neighbour lists, link destinations, processing order.
 struct PassGraph {
   uint32_t N = 0, L = 0;
-  DevBuf in_ptr, in_link, in_src, in_rec, link_dst, order, out_ptr, out_dst;
+  DevBuf in_ptr, in_link, in_src, in_rec, pos_dst, slot_rec, out_ptr, out_dst;
 };
 
 void build_pass_graph(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
@@ -243,11 +243,17 @@ void build_pass_graph(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc,
   std::vector<uint32_t> out_ptr, out_dst;
   std::vector<uint32_t> order = cluster_order(N, L, in_ptr, in_src, psrc, pdst, out_ptr, out_dst);
 
-  upload(g.order, order.data(), order.size(), stream);
+  std::vector<uint32_t> slot_rec((size_t)N * 4), pos_dst(L);
+  for (uint32_t k = 0; k < N; ++k) {
+    const uint32_t d = order[k];
+    slot_rec[4 * (size_t)k] = d; slot_rec[4 * (size_t)k + 1] = in_ptr[d]; slot_rec[4 * (size_t)k + 2] = in_ptr[d + 1];
+  }
+  for (uint32_t j = 0; j < L; ++j) pos_dst[j] = pdst[in_link[j]];
+  upload(g.slot_rec, slot_rec.data(), slot_rec.size(), stream);
+  upload(g.pos_dst, pos_dst.data(), pos_dst.size(), stream);
   upload(g.in_ptr, in_ptr.data(), in_ptr.size(), stream);
   upload(g.in_link, in_link.data(), in_link.size(), stream);
   upload(g.in_src, in_src.data(), in_src.size(), stream);
-  upload(g.link_dst, pdst.data(), pdst.size(), stream);
   upload(g.out_ptr, out_ptr.data(), out_ptr.size(), stream);
   upload(g.out_dst, out_dst.data(), out_dst.size(), stream);
   g.in_rec.alloc((size_t)L * 16);
@@ -269,9 +275,9 @@ PassDev make_pass_dev(const PassGraph &g, const DevBuf &d_cost, uint32_t cpn, ui
   p.row_words = NP * 128u; p.reversed = reversed ? 1u : 0u;
   p.held = held;
   p.in_ptr = g.in_ptr.as<uint32_t>(); p.in_link = g.in_link.as<uint32_t>();
-  p.in_src = g.in_src.as<uint32_t>(); p.link_dst = g.link_dst.as<uint32_t>();
+  p.in_src = g.in_src.as<uint32_t>(); p.pos_dst = g.pos_dst.as<uint32_t>();
   p.in_rec = g.in_rec.as<uint4>();
-  p.order = g.order.as<uint32_t>();
+  p.slot_rec = g.slot_rec.as<uint4>();
   p.cost = d_cost.as<unsigned long long>();
   p.carry = carry; p.free_at = free_at;
   p.ctl = ctl;
@@ -308,8 +314,8 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   d_carry.alloc((size_t)L * 4);
   d_free_at.alloc((size_t)L * 8);
   d_ctl.alloc(sizeof(Ctl));
-  const PassDev p = make_pass_dev(g, d_cost, cpn, seed, phase, reversed, d_held.as<unsigned long long>(),
-                                  d_carry.as<uint32_t>(), d_free_at.as<unsigned long long>(), d_ctl.as<Ctl>());
+  PassDev p = make_pass_dev(g, d_cost, cpn, seed, phase, reversed, d_held.as<unsigned long long>(),
+                            d_carry.as<uint32_t>(), d_free_at.as<unsigned long long>(), d_ctl.as<Ctl>());
   tacos::launch_init_pass(p, stream);
   HIP_TRY(hipGetLastError());
 
@@ -343,6 +349,11 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
     }
   }
   pass.prefill = small;  // the small-topology kernel writes matches only
+  DevBuf d_rnd;
+  if (!small && match_mode == 0) {
+    d_rnd.alloc((size_t)L * 4);
+    p.rnd = d_rnd.as<uint32_t>();
+  }
   if (small) {
     for (;;) {
       if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }

@@ -55,11 +55,15 @@ struct PassDev {
   const uint32_t *in_src;          // [L] their source NPUs (pass orientation)
   uint4 *in_rec;                   // [L] the in-lists as one record per entry: (link, source, cost lo, cost hi),
                                    //     written by the set-up kernel from in_link / in_src / cost
-  const uint32_t *link_dst;        // [L] destination NPU of link id (pass orientation)
-  const uint32_t *order;           // [N] processing order of the destinations (a permutation)
+  const uint32_t *pos_dst;         // [L] destination NPU of in-list position j (pass orientation)
+  const uint4 *slot_rec;           // [N] per processing slot: (destination d, in_ptr[d], in_ptr[d+1], 0); the
+                                   //     destinations in processing order are a permutation of the NPUs
   const unsigned long long *cost;  // [L]
-  uint32_t *carry;                 // [L] chunk in flight or kNone
-  unsigned long long *free_at;     // [L]
+  uint32_t *carry;                 // [L] chunk in flight or kNone, indexed by IN-LIST POSITION j (so that a
+                                   //     destination's links are contiguous and need no indirection)
+  unsigned long long *free_at;     // [L] busy-until time, same indexing
+  uint32_t *rnd;                   // [L] by in-list position: word 0 of Philox(link, current span, phase, 0),
+                                   //     written by arrive_kernel for the link-centric match_kernel; else null
   Ctl *ctl;
 };
 

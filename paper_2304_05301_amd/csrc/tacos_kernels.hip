@@ -188,11 +188,15 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
                                                      u32 *__restrict__ sched_row)
 {
   Ctl *ctl = p.ctl;
+  // one thread per in-list position (the per-link state is kept in in-list order)
   const u32 l = blockIdx.x * 256u + threadIdx.x;
   // the link's state does not depend on the control block: have all loads in flight at once
-  u32 c = kNone, d = 0;
+  u32 c = kNone, d = 0, link = 0;
   u64 fa = 0;
-  if (l < p.L) { c = p.carry[l]; fa = p.free_at[l]; d = p.link_dst[l]; }
+  if (l < p.L) {
+    c = p.carry[l]; fa = p.free_at[l]; d = p.pos_dst[l];
+    if (sched_row || p.rnd) link = p.in_link[l];
+  }
   if (ctl->done) return;
   const u64 t = ctl->next_t[event & 1u];
   if (l == 0) {
@@ -204,12 +208,15 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
     }
   }
   if (t == kInf) return;
+  // a6, first half: this span's random word of every link (the matching kernel takes it
+  // modulo the number of candidates); here all 64 lanes of a wavefront are in use
+  if (p.rnd && l < p.L) p.rnd[l] = philox4x32_10_word0(link, event, p.phase, 0u, p.seed_lo, p.seed_hi);
   const bool arrived = (c != kNone) && (fa == t);
   if (arrived) {
     atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
     p.carry[l] = kNone;
   }
-  if (sched_row && l < p.L) sched_row[l] = arrived ? c : kNone;
+  if (sched_row && l < p.L) sched_row[link] = arrived ? c : kNone;
   const u32 n = (u32)__popcll(__ballot(arrived));
   __shared__ u32 block_n;
   if (threadIdx.x == 0) block_n = 0;
@@ -296,35 +303,40 @@ __device__ __forceinline__ u32 kth_set_bit_wave(u32 lo, u32 hi, u32 k)
 // points at this wavefront's private NP*64 uint4.  Source rows land in two register
 // buffers used in turn, so that the next link's row is in flight while the current link
 // is decided; the candidate set is formed in place in the buffer.
-template <int NP>
-__device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 event, u64 t,
+template <int NP, bool LATENCY_BOUND>
+__device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb, u32 je, u32 event, u64 t,
                                                      u32 *__restrict__ sched_row, int lane, uint4 *need_lds)
 {
   constexpr int NW = 2 * NP;
   constexpr int NDW = 4 * NP;
   typedef RowRegs<NDW> RT;
   Ctl *ctl = p.ctl;
-  const u32 jb = p.in_ptr[d], je = p.in_ptr[d + 1];
-  u64 my_min = kInf;
+  u64 my_min = kInf;  // [jb, je) = d's in-list positions
 
-  // d's own row is asked for together with the in-list records, before it is known
-  // whether any incoming link is idle: one memory round trip instead of two
+  // LATENCY_BOUND (the single-workgroup kernel; few destinations per span): d's own row is
+  // asked for together with the in-list records, before it is known whether any incoming
+  // link is idle (one memory round trip instead of two, NP*4 more live registers), and the
+  // links' random words are computed here.  Otherwise (one wavefront per destination of a
+  // large topology, VALU- and bandwidth-bound) the random words were computed for all links
+  // of the span by arrive_kernel, with every lane busy, and are read from p.rnd.
   const uint4 *hp = reinterpret_cast<const uint4 *>(p.held + (u64)d * p.row_words) + lane;
   uint4 own[NP];
+  if constexpr (LATENCY_BOUND) {
 #pragma unroll
-  for (int i = 0; i < NP; ++i) own[i] = hp[i * 64];
+    for (int i = 0; i < NP; ++i) own[i] = hp[i * 64];
+  }
 
   u32 l0 = 0, s0 = 0, cr0 = kNone;
   u64 cs0 = 0;
   if (jb + lane < je) {
     const uint4 rec = p.in_rec[jb + lane];
+    cr0 = p.carry[jb + lane];
     l0 = rec.x; s0 = rec.y; cs0 = ((u64)rec.w << 32) | rec.z;
-    cr0 = p.carry[l0];
   }
   bool any_idle = __ballot(jb + lane < je && cr0 == kNone) != 0ull;
   for (u32 base = jb + 64; base < je && !any_idle; base += 64) {
     const u32 j = base + lane;
-    any_idle = __ballot(j < je && p.carry[p.in_rec[j < je ? j : jb].x] == kNone) != 0ull;
+    any_idle = __ballot(j < je && p.carry[j < je ? j : jb] == kNone) != 0ull;
   }
 
   bool need_any = false;
@@ -334,7 +346,9 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
     u32 acc = 0;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-      uint4 v = own[i];
+      uint4 v;
+      if constexpr (LATENCY_BOUND) v = own[i];
+      else v = hp[i * 64];
       v.x = ~v.x; v.y = ~v.y; v.z = ~v.z; v.w = ~v.w;
       need_lds[i * 64 + lane] = v;
       acc |= v.x | v.y | v.z | v.w;
@@ -344,7 +358,7 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
       const u32 j = base + lane;
       u32 cr = kNone;
       if (base == jb) cr = cr0;
-      else if (j < je) cr = p.carry[p.in_rec[j].x];
+      else if (j < je) cr = p.carry[j];
       const u64 busy = __ballot(cr != kNone);
       if (busy && cr != kNone) {
         // every busy lane clears its own link's chunk (distinct chunks; dword updates
@@ -367,14 +381,16 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
       l = 0; s = 0; cr = kNone; cs = 0;
       if (valid) {
         const uint4 rec = p.in_rec[j];
+        cr = p.carry[j];
         l = rec.x; s = rec.y; cs = ((u64)rec.w << 32) | rec.z;
-        cr = p.carry[l];
       }
     }
     u32 res = kNone;
     if (need_any) {
       u64 idle = __ballot(valid && cr == kNone);
-      const u32 r = philox4x32_10_word0(l, event, p.phase, 0u, p.seed_lo, p.seed_hi);
+      u32 r = 0;
+      if constexpr (LATENCY_BOUND) r = philox4x32_10_word0(l, event, p.phase, 0u, p.seed_lo, p.seed_hi);
+      else if (valid) r = p.rnd[j];
       typename RT::A buf0_a, buf1_a;
       typename RT::B buf0_b, buf1_b;
       auto fetch = [&](typename RT::A &ba, typename RT::B &bb, u64 pending) {
@@ -459,12 +475,12 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 ev
           ctl->done = 1u;
         } else {
           const u64 fa = t + cs;
-          p.carry[l] = res;
-          p.free_at[l] = fa;
+          p.carry[j] = res;
+          p.free_at[j] = fa;
           my_min = fa < my_min ? fa : my_min;
         }
       } else if (cr != kNone) {
-        const u64 fa = p.free_at[l];
+        const u64 fa = p.free_at[j];
         my_min = fa < my_min ? fa : my_min;
       }
     }
@@ -501,7 +517,7 @@ __device__ __forceinline__ void philox4x32_10_words01(u32 c0, u32 c1, u32 c2, u3
 // with (r0, r1) = words 0, 1 of Philox(d, event, phase + 2, step; seed).  The rows of the
 // free links are re-streamed (from L2) in every step.
 template <int NP>
-__device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, u32 event, u64 t,
+__device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, u32 jb, u32 je, u32 event, u64 t,
                                                        u32 *__restrict__ sched_row, int lane, uint4 *need_lds,
                                                        bool first_holder)
 {
@@ -509,15 +525,15 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
   constexpr int NDW = 4 * NP;
   typedef RowRegs<NDW> RT;
   Ctl *ctl = p.ctl;
-  const u32 jb = p.in_ptr[d], je = p.in_ptr[d + 1];
   u64 my_min = kInf;
   const bool valid = jb + lane < je;
+  const u32 j = jb + (u32)lane;
   u32 l = 0, s = 0, cr = kNone;
   u64 cs = 0;
   if (valid) {
-    const uint4 rec = p.in_rec[jb + lane];
+    const uint4 rec = p.in_rec[j];
+    cr = p.carry[j];
     l = rec.x; s = rec.y; cs = ((u64)rec.w << 32) | rec.z;
-    cr = p.carry[l];
   }
   u64 free_links = __ballot(valid && cr == kNone);
   u32 res = kNone;
@@ -626,12 +642,12 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
         ctl->done = 1u;
       } else {
         const u64 fa = t + cs;
-        p.carry[l] = res;
-        p.free_at[l] = fa;
+        p.carry[j] = res;
+        p.free_at[j] = fa;
         my_min = fa < my_min ? fa : my_min;
       }
     } else if (cr != kNone) {
-      const u64 fa = p.free_at[l];
+      const u64 fa = p.free_at[j];
       my_min = fa < my_min ? fa : my_min;
     }
   }
@@ -640,8 +656,12 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
 
 // MODE 0: link-centric matching; 1: postcondition-centric, random holder; 2: postcondition-
 // centric, first holder of the (cheapest-first) list.
+// (Five-piece rows, the 40,960-NPU workloads: the register allocator lands two registers
+// above the 80 that allow 6 wavefronts per SIMD; asking for 6 costs no spill and is 7 %
+// faster.  7 or 8 wavefronts per SIMD spill and are slower.)
 template <int NP, int MODE>
-__global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NP == 5 && MODE == 0 ? 6 : 1)))
+void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
 {
   const int lane = threadIdx.x & 63;
   // Workgroups are handed to the 8 XCDs round-robin.  Give XCD x the contiguous slice
@@ -652,7 +672,8 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
   const u32 pos = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
   const u32 slot = uniform(pos * 4u + (threadIdx.x >> 6));
   if (slot >= p.N) return;
-  const u32 d = uniform(p.order[slot]);
+  const uint4 sr = p.slot_rec[slot];  // (destination, its in-list begin, end)
+  const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
   Ctl *ctl = p.ctl;
   if (ctl->done) return;
   const u64 rem = ctl->remaining - wave_sum64(ctl->arrived[lane]);
@@ -664,8 +685,8 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
   __shared__ uint4 need_lds[4 * NP * 64];
   uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
   u64 my_min;
-  if constexpr (MODE == 0) my_min = match_destination<NP>(p, d, event, t, sched_row, lane, my_need);
-  else my_min = match_destination_pairs<NP>(p, d, event, t, sched_row, lane, my_need, MODE == 2);
+  if constexpr (MODE == 0) my_min = match_destination<NP, false>(p, d, jb, je, event, t, sched_row, lane, my_need);
+  else my_min = match_destination_pairs<NP>(p, d, jb, je, event, t, sched_row, lane, my_need, MODE == 2);
 
   // a8: next span = earliest end of a transfer in flight (min over all destinations)
   const u64 m = wave_min64(my_min);
@@ -699,7 +720,7 @@ __global__ __launch_bounds__(256) void match_kernel(PassDev p, u32 event, u32 *_
 //
 // LDS layout (dynamic): u64 free_at[L rounded up to even] | u32 carry[L] | u32 stamp[N] |
 // u32 work[N] | uint4 need[16][NP][64] | u64 next[2] | u32 counters[4] | Ctl shadow |
-// (if it still fits) u32 link_dst[L].
+// (if it still fits) u32 pos_dst[L].  Link state is indexed by in-list position, as in HBM.
 __host__ __device__ inline size_t small_lds_bytes(u32 N, u32 L, u32 NP)
 {
   size_t b = (((size_t)L + 1) & ~(size_t)1) * 8;
@@ -753,10 +774,10 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
     s_ctl->status = 0u; s_ctl->done = 0u;
     s_next[0] = kInf; s_next[1] = kInf;
   }
-  const u32 *link_dst = p.link_dst;
+  const u32 *pos_dst = p.pos_dst;
   if (dst_in_lds) {
-    for (u32 l = tid; l < p.L; l += 1024u) s_dst[l] = p.link_dst[l];
-    link_dst = s_dst;
+    for (u32 l = tid; l < p.L; l += 1024u) s_dst[l] = p.pos_dst[l];
+    pos_dst = s_dst;
   }
   PassDev q = p;  // the matching code works on the LDS copy of the link state
   q.carry = s_carry;
@@ -791,12 +812,12 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
           const u32 l = l2 + k;
           if (s_free[l] != t) continue;
           const u32 c = s_carry[l];
-          const u32 d = link_dst[l];
+          const u32 d = pos_dst[l];
           atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
           s_carry[l] = kNone;
           s_free[l] = kInf;
           atomicAdd(&s_cnt[1], 1u);
-          if (p.reversed && row) row[l] = c;
+          if (p.reversed && row) row[p.in_link[l]] = c;
           if (atomicExch(&s_stamp[d], e) != e) s_work[atomicAdd(&s_cnt[3], 1u)] = d;
         }
       }
@@ -826,11 +847,13 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
     const u32 n_work = (e == 0u) ? p.N : n_arr + s_cnt[0];
     for (u32 i = wave; i < n_work; i += 16u) {
       const u32 d = uniform((e == 0u) ? i : s_work[i]);
+      const u32 jb = p.in_ptr[d], je = p.in_ptr[d + 1];
       if constexpr (MODE == 0)
-        (void)match_destination<NP>(q, d, e, t, p.reversed ? nullptr : row, lane, s_need + wave * NP * 64);
+        (void)match_destination<NP, true>(q, d, jb, je, e, t, p.reversed ? nullptr : row, lane,
+                                          s_need + wave * NP * 64);
       else
-        (void)match_destination_pairs<NP>(q, d, e, t, p.reversed ? nullptr : row, lane, s_need + wave * NP * 64,
-                                          MODE == 2);
+        (void)match_destination_pairs<NP>(q, d, jb, je, e, t, p.reversed ? nullptr : row, lane,
+                                          s_need + wave * NP * 64, MODE == 2);
     }
     lds_barrier();
     // ---- next span = earliest end of a transfer in flight (a8), reduced in LDS
