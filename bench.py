@@ -35,10 +35,10 @@ def algorithmic_bytes(n_matches, n_npus, n_links, n_chunks):
     return n_matches * wb * (1.0 + 2.0 / deg)
 
 
-def measured_traffic(workload_name):
+def measured_traffic(kernel, workload_name):
     """HBM-side bytes per launch of the matching kernel from the committed rocprofv3 --pmc
     summary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size), or None."""
-    path = os.path.join(PROFILES, f"match_kernel_{workload_name}_traffic.txt")
+    path = os.path.join(PROFILES, f"{kernel}_{workload_name}_traffic.txt")
     if not os.path.exists(path):
         return None
     vals = {}
@@ -161,7 +161,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", type=int, default=5, help="1..5 (default 5: 40,960-NPU torus)")
+    ap.add_argument("--workload", type=int, default=5, help="1..7 (default 5: 40,960-NPU torus)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report-all", action="store_true",
                     help="instead of the one JSON line: a table over workloads 1..7 (GPU time, spans, "
@@ -220,7 +220,9 @@ def main():
     alg_bytes = algorithmic_bytes(n_xfers, topo.n_npus, topo.n_links, n_chunks)
     mean_launch_s = kernel_ms * 1e-3 / launches
     achieved = alg_bytes / launches / mean_launch_s / 1e9 if mean_launch_s > 0 else 0.0
-    traffic = measured_traffic(w.name)
+    # small topologies run in the single-workgroup kernel: a few launches, each many spans
+    kernel = "small_sweep_kernel" if launches < n_events else "match_kernel"
+    traffic = measured_traffic(kernel, w.name)
 
     line = {
         "metric": "ten_link_chunk_matches_per_sec",
@@ -249,7 +251,7 @@ def main():
         "match_kernel_matches_per_s": n_xfers / (kernel_ms * 1e-3) if kernel_ms > 0 else None,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "match_kernel",
+                     "kernel": kernel,
                      "algorithmic_bytes_per_launch": alg_bytes / launches,
                      "mean_launch_us": mean_launch_s * 1e6},
         "paper_context": "paper reports wall-clock only: 128-NPU All-Reduce synthesized in 1.08 s, "
