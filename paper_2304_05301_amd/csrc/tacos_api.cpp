@@ -203,6 +203,7 @@ std::vector<uint32_t> cluster_order(uint32_t N, uint32_t L, const std::vector<ui
 struct PassGraph {
   uint32_t N = 0, L = 0;
   DevBuf in_ptr, in_link, in_src, in_rec, pos_dst, slot_rec, out_ptr, out_dst;
+  std::vector<uint32_t> h_order, h_in_ptr;  // host copies, for dropping complete destinations
 };
 
 void build_pass_graph(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
@@ -249,6 +250,8 @@ void build_pass_graph(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc,
     slot_rec[4 * (size_t)k] = d; slot_rec[4 * (size_t)k + 1] = in_ptr[d]; slot_rec[4 * (size_t)k + 2] = in_ptr[d + 1];
   }
   for (uint32_t j = 0; j < L; ++j) pos_dst[j] = pdst[in_link[j]];
+  g.h_order = order;
+  g.h_in_ptr = in_ptr;
   upload(g.slot_rec, slot_rec.data(), slot_rec.size(), stream);
   upload(g.pos_dst, pos_dst.data(), pos_dst.size(), stream);
   upload(g.in_ptr, in_ptr.data(), in_ptr.size(), stream);
@@ -278,6 +281,7 @@ PassDev make_pass_dev(const PassGraph &g, const DevBuf &d_cost, uint32_t cpn, ui
   p.in_src = g.in_src.as<uint32_t>(); p.pos_dst = g.pos_dst.as<uint32_t>();
   p.in_rec = g.in_rec.as<uint4>();
   p.slot_rec = g.slot_rec.as<uint4>();
+  p.n_slots = g.N;
   p.cost = d_cost.as<unsigned long long>();
   p.carry = carry; p.free_at = free_at;
   p.ctl = ctl;
@@ -308,6 +312,16 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
 
   PassGraph g;
   build_pass_graph(N, L, psrc, pdst, order_cost, stream, g);
+  // Small topologies: one workgroup sweeps many spans with the link state in LDS.  Chosen
+  // automatically when the shape fits (launch_mode 0), forced by launch_mode 2.
+  bool small = false;
+  if (launch_mode != 1) {
+    small = fits_small_kernel(N, L, NP);
+    if (!small && launch_mode == 2) {
+      g_last_error = "launch_mode 2: links, NPUs and need rows do not fit the LDS of one workgroup";
+      return TACOS_E_INVAL;
+    }
+  }
   DevBuf d_held, d_carry, d_free_at, d_ctl;
   const uint32_t row_words = NP * 128u;
   d_held.alloc((size_t)N * row_words * 8);
@@ -316,6 +330,16 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   d_ctl.alloc(sizeof(Ctl));
   PassDev p = make_pass_dev(g, d_cost, cpn, seed, phase, reversed, d_held.as<unsigned long long>(),
                             d_carry.as<uint32_t>(), d_free_at.as<unsigned long long>(), d_ctl.as<Ctl>());
+  // per-span launches: destinations that hold every chunk are dropped from the order
+  DevBuf d_done;
+  std::vector<uint32_t> h_done;
+  uint32_t n_active = N;
+  if (!small) {
+    d_done.alloc((size_t)N * 4);
+    HIP_TRY(hipMemsetAsync(d_done.p, 0, (size_t)N * 4, stream));
+    p.dest_done = d_done.as<uint32_t>();
+    h_done.assign(N, 0);
+  }
   tacos::launch_init_pass(p, stream);
   HIP_TRY(hipGetLastError());
 
@@ -338,17 +362,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
 
   uint64_t e = 0;
   bool stopped = false;  // prefix run reached max_events
-  // Small topologies: one workgroup sweeps many spans with the link state in LDS.  Chosen
-  // automatically when the shape fits (launch_mode 0), forced by launch_mode 2.
-  bool small = false;
-  if (launch_mode != 1) {
-    small = fits_small_kernel(N, L, NP);
-    if (!small && launch_mode == 2) {
-      g_last_error = "launch_mode 2: links, NPUs and need rows do not fit the LDS of one workgroup";
-      return TACOS_E_INVAL;
-    }
-  }
-  pass.prefill = small;  // the small-topology kernel writes matches only
+  pass.prefill = true;  // the kernels write matches (a reversed pass: arrivals) only
   DevBuf d_rnd;
   if (!small && match_mode == 0) {
     d_rnd.alloc((size_t)L * 4);
@@ -419,6 +433,26 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
       }
       if (done || stopped) break;
       batch = std::min<uint32_t>(batch * 2, 512);
+      // Drop the destinations that are complete from the processing order once that
+      // shrinks the launch by an eighth (the first slot always stays: it ends the pass).
+      HIP_TRY(hipMemcpyAsync(h_done.data(), d_done.p, (size_t)N * 4, hipMemcpyDeviceToHost, stream));
+      HIP_TRY(hipStreamSynchronize(stream));
+      uint32_t alive = 0;
+      for (uint32_t k = 0; k < N; ++k) alive += (k == 0 || !h_done[g.h_order[k]]) ? 1u : 0u;
+      if (alive + n_active / 8 <= n_active) {
+        std::vector<uint32_t> rec((size_t)alive * 4, 0);
+        size_t w = 0;
+        for (uint32_t k = 0; k < N; ++k) {
+          const uint32_t d = g.h_order[k];
+          if (k != 0 && h_done[d]) continue;
+          rec[w] = d; rec[w + 1] = g.h_in_ptr[d]; rec[w + 2] = g.h_in_ptr[d + 1];
+          w += 4;
+        }
+        HIP_TRY(hipMemcpyAsync(g.slot_rec.p, rec.data(), rec.size() * 4, hipMemcpyHostToDevice, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        n_active = alive;
+        p.n_slots = alive;
+      }
     }
   }
 

@@ -56,6 +56,8 @@ struct PassDev {
   uint4 *in_rec;                   // [L] the in-lists as one record per entry: (link, source, cost lo, cost hi),
                                    //     written by the set-up kernel from in_link / in_src / cost
   const uint32_t *pos_dst;         // [L] destination NPU of in-list position j (pass orientation)
+  uint32_t n_slots;                // processing slots in use (N, less the complete destinations the host dropped)
+  uint32_t *dest_done;             // [N] set to 1 by the matching once the NPU holds every chunk; may be null
   const uint4 *slot_rec;           // [N] per processing slot: (destination d, in_ptr[d], in_ptr[d+1], 0); the
                                    //     destinations in processing order are a permutation of the NPUs
   const unsigned long long *cost;  // [L]

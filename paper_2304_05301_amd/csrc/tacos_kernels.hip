@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
     atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
     p.carry[l] = kNone;
   }
-  if (sched_row && l < p.L) sched_row[link] = arrived ? c : kNone;
+  if (sched_row && arrived) sched_row[link] = c;  // rows are pre-filled with kNone
   const u32 n = (u32)__popcll(__ballot(arrived));
   __shared__ u32 block_n;
   if (threadIdx.x == 0) block_n = 0;
@@ -354,6 +354,9 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb
       acc |= v.x | v.y | v.z | v.w;
     }
     need_any = __ballot(acc != 0u) != 0ull;  // before the in-flight bits are removed: a superset
+    // d holds every chunk: nothing is or will be in flight to it, its links stay idle for
+    // good, and the host may drop it from the processing order
+    if (!need_any && p.dest_done && lane == 0) p.dest_done[d] = 1u;
     for (u32 base = jb; base < je; base += 64) {
       const u32 j = base + lane;
       u32 cr = kNone;
@@ -465,7 +468,7 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb
       }
     }
     if (valid) {
-      if (sched_row) sched_row[l] = res;
+      if (sched_row && res != kNone) sched_row[l] = res;  // rows are pre-filled with kNone
       if (res != kNone) {
         if (res >= p.C) {
           ctl->status = kStInternal;
@@ -540,12 +543,15 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
 
   if (free_links) {
     const uint4 *hp = reinterpret_cast<const uint4 *>(p.held + (u64)d * p.row_words) + lane;
+    u32 acc = 0;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       uint4 v = hp[i * 64];
       v.x = ~v.x; v.y = ~v.y; v.z = ~v.z; v.w = ~v.w;
       need_lds[i * 64 + lane] = v;
+      acc |= v.x | v.y | v.z | v.w;
     }
+    if (__ballot(acc != 0u) == 0ull && p.dest_done && lane == 0) p.dest_done[d] = 1u;  // d holds every chunk
     if (cr != kNone) {  // chunks in flight to d are not needed
       const u32 w = cr >> 6;
       const u32 ln = w / (u32)NW;
@@ -632,7 +638,7 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
     }
   }
   if (valid) {
-    if (sched_row) sched_row[l] = res;
+    if (sched_row && res != kNone) sched_row[l] = res;  // rows are pre-filled with kNone
     if (res != kNone) {
       if (res >= p.C) {
         ctl->status = kStInternal;
@@ -671,7 +677,7 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   const u32 per_xcd = gridDim.x >> 3;
   const u32 pos = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
   const u32 slot = uniform(pos * 4u + (threadIdx.x >> 6));
-  if (slot >= p.N) return;
+  if (slot >= p.n_slots) return;
   const uint4 sr = p.slot_rec[slot];  // (destination, its in-list begin, end)
   const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
   Ctl *ctl = p.ctl;
@@ -679,7 +685,7 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   const u64 rem = ctl->remaining - wave_sum64(ctl->arrived[lane]);
   const u64 t = ctl->next_t[event & 1u];
   if (rem == 0) {  // every postcondition satisfied: the collective ends now
-    if (d == 0 && lane == 0) { ctl->T = t; ctl->n_events = event; ctl->done = 1u; }
+    if (slot == 0 && lane == 0) { ctl->T = t; ctl->n_events = event; ctl->done = 1u; }
     return;
   }
   __shared__ uint4 need_lds[4 * NP * 64];
@@ -992,7 +998,8 @@ void launch_arrive(const PassDev &p, u32 event, u64 *event_time_slot, u32 *sched
 
 template <int MODE> static void launch_match_mode(const PassDev &p, u32 event, u32 *sched_row, hipStream_t s)
 {
-  const dim3 grid(8u * ((((p.N + 3u) / 4u) + 7u) / 8u)), block(256);
+  const u32 n_wg = (p.n_slots + 3u) / 4u;
+  const dim3 grid(8u * ((n_wg + 7u) / 8u + (n_wg == 0u)), 1, 1), block(256);
   switch (p.NP) {
     case 1: hipLaunchKernelGGL((match_kernel<1, MODE>), grid, block, 0, s, p, event, sched_row); break;
     case 2: hipLaunchKernelGGL((match_kernel<2, MODE>), grid, block, 0, s, p, event, sched_row); break;
