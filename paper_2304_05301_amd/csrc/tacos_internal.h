@@ -76,11 +76,12 @@ void launch_link_cost(const unsigned long long *alpha, const unsigned long long 
 // a2: precondition rows, idle links, control block
 void launch_init_pass(const PassDev &p, hipStream_t s);
 // a3 + a8 (consume): arrivals at the event's time; writes event_time_slot and, for a
-// reversed pass, the schedule row of the event
+// reversed pass, the arrivals into the schedule row of the event (rows are pre-filled with kNone)
 void launch_arrive(const PassDev &p, uint32_t event, unsigned long long *event_time_slot,
                    uint32_t *sched_row, hipStream_t s);
 // a4-a8 (produce): termination test, matching for all destinations, min-reduction of
-// the next event time; a forward pass writes the schedule row of the event
+// the next event time; a forward pass writes its matches into the schedule row of the event
+// (pre-filled with kNone).  Only the first p.n_slots processing slots are launched.
 // mode 0: link-centric; 1: postcondition-centric with a random holder link; 2: postcondition-
 // centric with the first holder of the incoming list (in-degree <= 64 for modes 1, 2)
 void launch_match(const PassDev &p, uint32_t event, uint32_t *sched_row, uint32_t mode, hipStream_t s);

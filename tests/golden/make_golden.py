@@ -12,6 +12,12 @@ additionally runs the 40,960-NPU workload 5 to completion (OpenMP over destinati
 minutes) and stores its time, sweeps, records, digest and the SHA-256 of the per-sweep
 (time, match count) trace in workload5_oracle.json.  Its 1.68e9 records are not kept.
 
+    python tests/golden/make_golden.py --scalability 6 [--threads 8]      (or 7)
+
+runs the paper's scalability workload (6: All-Reduce on the 200x200 mesh, 7: on the
+35x35x35 3-D mesh) to completion, digest only (tens of minutes on 8 threads), and stores
+collective time, per-pass times and sweeps, records and digest in workload<N>_oracle.json.
+
     python tests/golden/make_golden.py --seed-search
 
 runs workload 4's topology with three other seeds, one after the other (a minute), and
@@ -69,7 +75,31 @@ def seed_search():
         f.write("\n")
 
 
+def scalability(idx, threads):
+    w = T.workload(idx)
+    oracle.set_progress(2000)
+    r = oracle.synthesize_workload(w, keep_xfers=0, n_threads=threads)
+    out = {
+        "name": w.name,
+        "topology": w.topo.name,
+        "collective_time_ps": r.collective_time_ps,
+        "n_events": r.n_events,
+        "n_xfers": r.n_xfers,
+        "pass_time_ps": list(r.pass_time_ps)[:2],
+        "pass_events": list(r.pass_events)[:2],
+        "digest": r.digest,
+    }
+    print(idx, out, flush=True)
+    with open(os.path.join(HERE, f"workload{idx}_oracle.json"), "w") as f:
+        json.dump(out, f, indent=1, sort_keys=True)
+        f.write("\n")
+
+
 def main():
+    if "--scalability" in sys.argv:
+        threads = int(sys.argv[sys.argv.index("--threads") + 1]) if "--threads" in sys.argv else 8
+        scalability(int(sys.argv[sys.argv.index("--scalability") + 1]), threads)
+        return
     if "--seed-search" in sys.argv:
         seed_search()
         return

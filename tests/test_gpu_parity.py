@@ -289,6 +289,26 @@ def test_workload_5_full_run_against_stored_oracle_result(stream):
         assert int(last["t_ps"]) + 10_985_760 == g["collective_time_ps"]
 
 
+@pytest.mark.parametrize("idx", [6, 7])
+def test_scalability_workloads_full_run_against_stored_oracle_result(idx, stream):
+    """The paper's scalability workloads at full size (All-Reduce on the 200x200 mesh and
+    on the 35x35x35 3-D mesh: 3.2e9 / 3.7e9 transfers, a Reduce-Scatter and an All-Gather
+    pass) against what the oracle stored in tests/golden/workload<N>_oracle.json
+    (make_golden.py --scalability N): collective time, per-pass times and spans, transfers
+    and the digest over every transfer.  Also the launches that drop complete destinations
+    at full size (most NPUs are complete for the second half of each pass)."""
+    with open(os.path.join(os.path.dirname(GOLDEN), f"workload{idx}_oracle.json")) as f:
+        g = json.load(f)
+    w = T.workload(idx)
+    assert w.name == g["name"]
+    with binding.synthesize_workload(w, stream=stream) as r:
+        assert r.collective_time_ps == g["collective_time_ps"]
+        assert r.num_events == g["n_events"] and r.num_xfers == g["n_xfers"]
+        assert [r.pass_time_ps(i) for i in range(2)] == g["pass_time_ps"]
+        assert [r.pass_events(i) for i in range(2)] == g["pass_events"]
+        assert r.digest == g["digest"]
+
+
 @pytest.mark.parametrize("coll", [T.ALL_GATHER, T.ALL_REDUCE])
 def test_lower_cost_link_priority_bit_exact(coll, stream):
     """link_order = cheapest first ('Prioritizing Lower-cost Links') against the oracle
