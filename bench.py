@@ -159,7 +159,7 @@ def report_seed_search(binding, T, stream):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", type=int, default=5, help="1..7 (default 5: 40,960-NPU torus)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -242,6 +242,7 @@ def main():
                    "collective": ["all_gather", "reduce_scatter", "all_reduce"][w.collective],
                    "seed": w.seed},
         "synthesis_wall_s": ms_per_step * 1e-3,
+        "synthesis_wall_s_median": sorted(r[6] for r in results)[len(results) // 2] * 1e-3,
         "matches": n_xfers,
         "ten_spans": n_events,
         "collective_time_ps": T_ps,

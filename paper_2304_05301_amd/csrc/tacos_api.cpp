@@ -439,7 +439,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
       HIP_TRY(hipStreamSynchronize(stream));
       uint32_t alive = 0;
       for (uint32_t k = 0; k < N; ++k) alive += (k == 0 || !h_done[g.h_order[k]]) ? 1u : 0u;
-      if (alive + n_active / 8 <= n_active) {
+      if (alive < n_active && alive + n_active / 8 <= n_active) {
         std::vector<uint32_t> rec((size_t)alive * 4, 0);
         size_t w = 0;
         for (uint32_t k = 0; k < N; ++k) {
