@@ -2,12 +2,15 @@
 //
 // Paper: TACOS, arXiv 2304.05301.  One TEN span ("event") is processed by two launches:
 //   arrive_kernel : the precondition update for the span (chunks whose transfer ends now
-//                   become held), one thread per link;
+//                   become held), one thread per link; also the span's random words;
 //   match_kernel  : Algorithm 1 (utilization-maximizing matching) in its link-centric
-//                   deterministic form, one wavefront per destination NPU, plus the
+//                   deterministic form (or, MODE 1/2, in the postcondition-centric order
+//                   the paper prints), one wavefront per destination NPU, plus the
 //                   min-reduction that finds the next span of Algorithm 2.
 // The host never sees the per-event state; it only queues launches and polls the
 // control block once per batch of events.
+// Small topologies: small_sweep_kernel, ONE workgroup that sweeps many spans with the
+// link state in LDS; small_sweep_batch_kernel runs many such passes (seeds) at once.
 //
 // All arithmetic is integer.  Bitset layout: see PassDev in tacos_internal.h.
 
