@@ -52,6 +52,26 @@ def measured_traffic(kernel, workload_name):
     return float(vals["hbm_bytes_per_launch"])
 
 
+def measured_read_peak_gbs(torch):
+    """Streaming-read rate of this device, measured live: a read-only reduction over 2 GiB
+    (torch's sum kernel), mean of 10 runs after 2 warm-up runs, in GB/s."""
+    a = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+    a.fill_(1)
+    v = a.view(torch.int64)
+    for _ in range(2):
+        v.sum()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        v.sum()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 10
+    del v, a
+    return (2 << 30) / ms / 1e6
+
+
 def cpu_baseline(w, target_s=15.0):
     """The CPU oracle on a bounded sample of the workload: the whole workload if that takes
     about target_s or less, else the first spans of its All-Gather pass (the reversed pass
@@ -223,6 +243,7 @@ def main():
     # small topologies run in the single-workgroup kernel: a few launches, each many spans
     kernel = "small_sweep_kernel" if launches < n_events else "match_kernel"
     traffic = measured_traffic(kernel, w.name)
+    read_peak = measured_read_peak_gbs(torch)
 
     line = {
         "metric": "ten_link_chunk_matches_per_sec",
@@ -254,7 +275,14 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": kernel,
                      "algorithmic_bytes_per_launch": alg_bytes / launches,
-                     "mean_launch_us": mean_launch_s * 1e6},
+                     "mean_launch_us": mean_launch_s * 1e6,
+                     # HBM-side bytes per launch (rocprofv3 counters, committed summary) over the
+                     # launch duration measured now, and the same against a streaming read
+                     # measured now on this device
+                     "traffic_GBps": (traffic / mean_launch_s / 1e9) if traffic and mean_launch_s > 0 else None,
+                     "measured_read_peak_GBps": read_peak,
+                     "traffic_frac_of_measured_peak": (traffic / mean_launch_s / 1e9 / read_peak)
+                     if traffic and mean_launch_s > 0 and read_peak else None},
         "paper_context": "paper reports wall-clock only: 128-NPU All-Reduce synthesized in 1.08 s, "
                          "40K-NPU 2D mesh All-Reduce in 2.52 h (Xeon E5-2699v3, 64 threads)",
     }
