@@ -273,6 +273,18 @@ def seed_search_workload(w, seeds, **kw):
                              w.chunks_per_npu, w.chunk_bytes, w.collective, seeds, **kw)
 
 
+def synthesize_best_of(w, seeds, **kw):
+    """Best of several seeds with its schedule: tacos_seed_search over `seeds`, then
+    tacos_synthesize with the winning seed.  Returns (result, best seed, times)."""
+    skw = {k: v for k, v in kw.items() if k in ("stream", "link_order", "matching")}
+    times, _, best = seed_search_workload(w, seeds, **skw)
+    t = w.topo
+    seed = int(np.asarray(seeds, dtype=np.uint64)[best])
+    r = tacos_synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B,
+                         w.chunks_per_npu, w.chunk_bytes, w.collective, seed, **kw)
+    return r, seed, times
+
+
 def synthesize_workload(w, **kw) -> TacosResult:
     """Convenience: run on an object with .topo/.chunks_per_npu/.chunk_bytes/.collective/.seed."""
     t = w.topo

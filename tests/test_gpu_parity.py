@@ -507,3 +507,14 @@ def test_seed_search_errors_and_degenerate_inputs(stream):
     with pytest.raises(binding.TacosError) as e:
         search(broken, 1, MiB, T.ALL_GATHER, [1, 2, 3], stream)
     assert e.value.code == binding.TACOS_E_UNREACHABLE
+
+
+def test_best_of_seeds_returns_the_winning_schedule(stream):
+    w = T.workload(3)
+    seeds = np.arange(50, 90, dtype=np.uint64)
+    r, seed, times = binding.synthesize_best_of(w, seeds, stream=stream)
+    with r:
+        assert r.collective_time_ps == int(times.min()) and seed == int(seeds[int(np.argmin(times))])
+        ref = oracle.synthesize_workload(T.Workload(w.name, w.topo, w.chunks_per_npu, w.chunk_bytes,
+                                                    w.collective, seed))
+        assert_same(r, ref, "best of 40 seeds")
