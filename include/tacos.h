@@ -87,7 +87,8 @@ typedef enum {
 #define TACOS_MATCH_POSTCONDITION 1u
 
 /* Largest supported number of chunks N*chunks_per_npu (one wavefront keeps a
- * destination's whole "still needed" bitset in registers). */
+ * destination's whole "still needed" bitset in its share of the LDS and a source's
+ * whole row in registers). */
 #define TACOS_MAX_CHUNKS 65536u
 
 #define TACOS_NO_CHUNK 0xFFFFFFFFu
