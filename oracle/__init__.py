@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "tacos_oracle.c")
 _LIB = os.path.join(_HERE, "libtacos_oracle.so")
 
-ALL_GATHER, REDUCE_SCATTER, ALL_REDUCE = 0, 1, 2
+ALL_GATHER, REDUCE_SCATTER, ALL_REDUCE, BROADCAST, REDUCE = 0, 1, 2, 3, 4
 OK, E_INVAL, E_UNREACHABLE, E_OVERFLOW, E_NOMEM = 0, -1, -2, -3, -4
 
 XFER_DTYPE = np.dtype([("t_ps", "<u8"), ("src", "<u4"), ("dst", "<u4"),
@@ -68,7 +68,7 @@ def lib() -> ctypes.CDLL:
             ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
             ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-            ctypes.POINTER(ctypes.POINTER(_CResult))]
+            ctypes.c_uint32, ctypes.POINTER(ctypes.POINTER(_CResult))]
         L.orc_result_free.restype = None
         L.orc_result_free.argtypes = [ctypes.POINTER(_CResult)]
         L.orc_philox4x32_10.restype = None
@@ -129,7 +129,7 @@ def max_threads() -> int:
 def synthesize(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_per_npu, chunk_bytes,
                collective, seed, max_events: int = 0, keep_first: int = 0,
                keep_xfers: int = (1 << 64) - 1, n_threads: int = 1,
-               link_order: int = 0, matching: int = 0) -> OracleResult:
+               link_order: int = 0, matching: int = 0, root: int = 0) -> OracleResult:
     rp = np.ascontiguousarray(row_ptr, dtype=np.uint32)
     ci = np.ascontiguousarray(col_idx, dtype=np.uint32)
     al = np.ascontiguousarray(alpha_ps, dtype=np.uint64)
@@ -139,7 +139,7 @@ def synthesize(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_per_npu
                               be.ctypes.data, int(chunks_per_npu), int(chunk_bytes),
                               int(collective), int(seed), int(max_events), int(keep_first),
                               int(keep_xfers), int(n_threads), int(link_order), int(matching),
-                              ctypes.byref(res))
+                              int(root), ctypes.byref(res))
     if rc != OK:
         raise OracleError(rc)
     try:

@@ -48,7 +48,7 @@
 #define ORC_NONE 0xFFFFFFFFu
 #define ORC_INF  0xFFFFFFFFFFFFFFFFull
 
-enum { ORC_ALL_GATHER = 0, ORC_REDUCE_SCATTER = 1, ORC_ALL_REDUCE = 2 };
+enum { ORC_ALL_GATHER = 0, ORC_REDUCE_SCATTER = 1, ORC_ALL_REDUCE = 2, ORC_BROADCAST = 3, ORC_REDUCE = 4 };
 enum { ORC_OK = 0, ORC_E_INVAL = -1, ORC_E_UNREACHABLE = -2, ORC_E_OVERFLOW = -3, ORC_E_NOMEM = -4 };
 
 typedef struct {
@@ -221,9 +221,12 @@ static uint32_t kth_bit(uint64_t w, uint32_t k)
 static int ag_pass(uint32_t N, uint32_t L, const uint32_t *psrc, const uint32_t *pdst,
                    const uint64_t *cost, uint32_t cpn, uint64_t seed, uint32_t phase,
                    uint64_t max_events, int n_threads, int link_order, int matching,
-                   pass_out_t *out, uint64_t *T, uint64_t *n_events, int *complete)
+                   pass_out_t *out, uint64_t *T, uint64_t *n_events, int *complete, uint32_t root)
 {
-  const uint64_t C = (uint64_t)N * cpn;
+  /* root == ORC_NONE: All-Gather, N*cpn chunks, chunk c owned by NPU c / cpn.
+   * Otherwise Broadcast from `root`: cpn chunks, all held by the root at t = 0; the
+   * postcondition is the same (every NPU holds every chunk). */
+  const uint64_t C = (root == ORC_NONE) ? (uint64_t)N * cpn : (uint64_t)cpn;
   const uint64_t W = (C + 63) / 64;
   int rc = ORC_OK;
   const size_t n_words = (size_t)N * W;
@@ -261,11 +264,16 @@ static int ag_pass(uint32_t N, uint32_t L, const uint32_t *psrc, const uint32_t 
       }
   }
   /* precondition of All-Gather: NPU i holds its own cpn chunks */
+  if (root == ORC_NONE) {
   for (uint32_t i = 0; i < N; ++i)
     for (uint32_t j = 0; j < cpn; ++j) {
       uint64_t c = (uint64_t)i * cpn + j;
       held[(size_t)i * W + (c >> 6)] |= 1ull << (c & 63);
     }
+  } else {
+    /* precondition of Broadcast: the root holds all cpn chunks, nobody else any */
+    for (uint32_t j = 0; j < cpn; ++j) held[(size_t)root * W + (j >> 6)] |= 1ull << (j & 63);
+  }
   for (uint32_t l = 0; l < L; ++l) carry[l] = ORC_NONE;
 
   uint64_t remaining = (uint64_t)N * C - C;   /* unsatisfied postconditions */
@@ -441,24 +449,35 @@ static void pass_out_free(pass_out_t *o) { free(o->rec); free(o->ev_time); free(
  *   matching   : 0 = link-centric (every idle link draws a chunk); 1 = Algorithm 1 as
  *                printed, postcondition-centric (every missing chunk draws a source
  *                link); see the comment in ag_pass.
+ *   root       : Broadcast / Reduce only (paragraph "Collectives with Reduction
+ *                Operations": Reduce = the Broadcast synthesized on the reversed links,
+ *                reversed back, exactly as Reduce-Scatter is obtained from All-Gather).
+ *                Broadcast: the root's chunks_per_npu chunks reach every NPU; Reduce: the
+ *                reverse.  Chunk ids are 0 .. chunks_per_npu-1.
  */
 int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col_idx,
                    const uint64_t *alpha_ps, const uint64_t *beta_fs_per_B,
                    uint32_t chunks_per_npu, uint64_t chunk_bytes, int collective,
                    uint64_t seed, uint64_t max_events, uint64_t keep_first,
                    uint64_t keep_xfers, int n_threads, int link_order, int matching,
-                   orc_result_t **result)
+                   uint32_t root, orc_result_t **result)
 {
   if (!row_ptr || !result || n_npus == 0 || chunks_per_npu == 0 || chunk_bytes == 0)
     return ORC_E_INVAL;
-  if (collective != ORC_ALL_GATHER && collective != ORC_REDUCE_SCATTER && collective != ORC_ALL_REDUCE)
-    return ORC_E_INVAL;
+  if (collective < ORC_ALL_GATHER || collective > ORC_REDUCE) return ORC_E_INVAL;
+  const int rooted = collective == ORC_BROADCAST || collective == ORC_REDUCE;
+  if (rooted && root >= n_npus) return ORC_E_INVAL;
+  const uint32_t pass_root = rooted ? root : ORC_NONE;
+  /* which passes: a reversed one (All-Gather / Broadcast on the reversed links, mapped
+   * back in direction and time) and / or a forward one */
+  const int has_rev = collective == ORC_REDUCE_SCATTER || collective == ORC_ALL_REDUCE || collective == ORC_REDUCE;
+  const int has_fwd = collective == ORC_ALL_GATHER || collective == ORC_ALL_REDUCE || collective == ORC_BROADCAST;
   if (row_ptr[0] != 0) return ORC_E_INVAL;
   for (uint32_t i = 0; i < n_npus; ++i)
     if (row_ptr[i + 1] < row_ptr[i]) return ORC_E_INVAL;
   const uint32_t L = row_ptr[n_npus];
   if (L && (!col_idx || !alpha_ps || !beta_fs_per_B)) return ORC_E_INVAL;
-  if ((uint64_t)n_npus * chunks_per_npu >= 0xFFFFFFFFull) return ORC_E_INVAL;
+  if ((rooted ? (uint64_t)chunks_per_npu : (uint64_t)n_npus * chunks_per_npu) >= 0xFFFFFFFFull) return ORC_E_INVAL;
   if (n_threads < 1) n_threads = 1;
   if (link_order != 0 && link_order != 1) return ORC_E_INVAL;
   if (matching != 0 && matching != 1) return ORC_E_INVAL;
@@ -485,25 +504,25 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
   /* Reduce-Scatter (alone or as the first half of All-Reduce): All-Gather on the
    * reversed links, then the schedule reversed in direction AND time, so that the
    * last hop of the reversed All-Gather becomes the first reduction hop. */
-  if (collective == ORC_REDUCE_SCATTER || collective == ORC_ALL_REDUCE) {
+  if (has_rev) {
     pass_out_t *o = &po[n_pass];
     o->keep_limit = ~0ull;
     uint64_t T = 0, ne = 0; int complete = 0;
     rc = ag_pass(n_npus, L, col_idx, src, cost, chunks_per_npu, seed, 1u, max_events,
-                 n_threads, link_order, matching, o, &T, &ne, &complete);
+                 n_threads, link_order, matching, o, &T, &ne, &complete, pass_root);
     if (rc != ORC_OK) goto fail;
     complete_all &= complete;
     res->pass_time_ps[n_pass] = T; res->pass_events[n_pass] = ne;
     n_pass++;
     t_off = T;
   }
-  if (collective == ORC_ALL_GATHER || collective == ORC_ALL_REDUCE) {
+  if (has_fwd) {
     pass_out_t *o = &po[n_pass];
     o->keep_first = keep_first; o->keep_limit = keep_xfers;
     o->fwd = 1; o->t_off = t_off;
     uint64_t T = 0, ne = 0; int complete = 0;
     rc = ag_pass(n_npus, L, src, col_idx, cost, chunks_per_npu, seed, 0u, max_events,
-                 n_threads, link_order, matching, o, &T, &ne, &complete);
+                 n_threads, link_order, matching, o, &T, &ne, &complete, pass_root);
     if (rc != ORC_OK) goto fail;
     complete_all &= complete;
     res->pass_time_ps[n_pass] = T; res->pass_events[n_pass] = ne;
@@ -517,12 +536,12 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
    * from its raw records and not materialised */
   const int digest_only = (keep_xfers == 0);
   for (int p = 0; p < n_pass; ++p)
-    if (!(digest_only && collective != ORC_ALL_GATHER && p == 0)) total_keep += po[p].n;
+    if (!(digest_only && has_rev && p == 0)) total_keep += po[p].n;
   res->xfers = (orc_xfer_t *)malloc((total_keep ? total_keep : 1) * sizeof(orc_xfer_t));
   if (!res->xfers) { rc = ORC_E_NOMEM; goto fail; }
   uint64_t w = 0;
   int p = 0;
-  if (collective != ORC_ALL_GATHER) {
+  if (has_rev) {
     /* reversed pass: a transfer that occupied link l during [t', t'+cost) of the
      * reversed All-Gather occupies the ORIGINAL link l (src -> dst) during
      * [T - t' - cost, T - t') of the Reduce-Scatter */
@@ -548,7 +567,7 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
     res->n_xfers += po[0].n_total;
     p = 1;
   }
-  if (collective != ORC_REDUCE_SCATTER) {
+  if (has_fwd) {
     for (uint64_t i = 0; i < po[p].n; ++i) {
       const pass_rec_t *r = &po[p].rec[i];
       orc_xfer_t x;
@@ -560,7 +579,7 @@ int orc_synthesize(uint32_t n_npus, const uint32_t *row_ptr, const uint32_t *col
     res->n_xfers += po[p].n_total;
   }
   res->n_stored = w;
-  if (collective != ORC_REDUCE_SCATTER) res->digest += po[p].digest;
+  if (has_fwd) res->digest += po[p].digest;
   for (int q = 0; q < n_pass; ++q) {
     res->collective_time_ps += res->pass_time_ps[q];
     res->n_events += res->pass_events[q];

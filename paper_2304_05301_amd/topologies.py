@@ -30,6 +30,8 @@ import numpy as np
 ALL_GATHER = 0
 REDUCE_SCATTER = 1
 ALL_REDUCE = 2
+BROADCAST = 3   # from a root NPU: chunks_per_npu chunks, all held by the root at the start
+REDUCE = 4      # to a root NPU: the reverse of Broadcast
 
 
 def gbps_to_beta_fs_per_B(gb_per_s: float) -> int:

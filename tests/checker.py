@@ -30,11 +30,12 @@ def link_costs_ps(alpha_ps, beta_fs_per_B, chunk_bytes):
 
 
 def check_all_gather(n_npus, link_src, link_dst, cost, cpn, xfers, collective_time,
-                     check_maximal=True, t0=0):
+                     check_maximal=True, t0=0, root=None):
     """xfers: structured array (t_ps, src, dst, chunk, link) of ONE All-Gather pass whose
-    time origin is t0.  Raises AssertionError on the first violated invariant."""
+    time origin is t0.  Raises AssertionError on the first violated invariant.
+    root given: a Broadcast instead (cpn chunks, all held by the root at the start)."""
     N = int(n_npus)
-    C = N * int(cpn)
+    C = N * int(cpn) if root is None else int(cpn)
     L = len(link_src)
     t = xfers["t_ps"].astype(object) - t0 if len(xfers) else np.zeros(0, dtype=object)
     t = [int(x) for x in t]
@@ -55,9 +56,13 @@ def check_all_gather(n_npus, link_src, link_dst, cost, cpn, xfers, collective_ti
     assert np.all(chunk < C) and np.all(chunk >= 0)
 
     arrive = {}  # (npu, chunk) -> arrival time
-    for i in range(N):
+    if root is None:
+        for i in range(N):
+            for j in range(cpn):
+                arrive[(i, i * cpn + j)] = 0
+    else:
         for j in range(cpn):
-            arrive[(i, i * cpn + j)] = 0
+            arrive[(int(root), j)] = 0
     order = sorted(range(n), key=lambda i: (t[i], link[i]))
     last_free = [0] * L
     # delivery uniqueness + interval disjointness
@@ -110,13 +115,18 @@ def check_all_gather(n_npus, link_src, link_dst, cost, cpn, xfers, collective_ti
     return T
 
 
-def check_reduce_scatter(n_npus, link_src, link_dst, cost, cpn, xfers, collective_time):
+def check_reduce_scatter(n_npus, link_src, link_dst, cost, cpn, xfers, collective_time, root=None):
     """Invariants of a Reduce-Scatter schedule obtained by reversal: for every chunk the
     transfers form an in-tree over all NPUs rooted at the owner; an NPU forwards its
     partial sum of chunk c once, and only after everything sent TO it for c has arrived;
-    links carry one chunk at a time; the collective ends at the last arrival."""
+    links carry one chunk at a time; the collective ends at the last arrival.
+    root given: a Reduce instead (cpn chunks, every one of them owned by the root)."""
     N = int(n_npus)
-    C = N * int(cpn)
+    C = N * int(cpn) if root is None else int(cpn)
+
+    def owner(c):
+        return c // cpn if root is None else int(root)
+
     n = len(xfers)
     assert n == C * (N - 1)
     t = [int(x) for x in xfers["t_ps"]]
@@ -132,13 +142,13 @@ def check_reduce_scatter(n_npus, link_src, link_dst, cost, cpn, xfers, collectiv
     for i in range(n):
         key = (int(src[i]), int(chunk[i]))
         assert key not in send_time, f"NPU {key[0]} sends chunk {key[1]} twice"
-        assert key[0] != key[1] // cpn, "the owner never sends its own chunk in Reduce-Scatter"
+        assert key[0] != owner(key[1]), "the owner never sends its own chunk in Reduce-Scatter"
         send_time[key] = t[i]
     assert len(send_time) == C * (N - 1)
     for i in range(n):
         d, c = int(dst[i]), int(chunk[i])
         ta = t[i] + cost[link[i]]
-        if d != c // cpn:
+        if d != owner(c):
             assert ta <= send_time[(d, c)], \
                 f"NPU {d} forwards chunk {c} at {send_time[(d, c)]} before a contribution arrives at {ta}"
     # every chain ends at the owner: follow parents
@@ -146,7 +156,7 @@ def check_reduce_scatter(n_npus, link_src, link_dst, cost, cpn, xfers, collectiv
     for (s, c), d in parent.items():
         hops = 0
         cur = s
-        while cur != c // cpn:
+        while cur != owner(c):
             cur = parent[(cur, c)]
             hops += 1
             assert hops <= N

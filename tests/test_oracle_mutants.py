@@ -47,6 +47,12 @@ MUTANTS = {
     "kth_from_the_top": ("uint32_t k = draw(seed, l, (uint32_t)event, phase) % (uint32_t)p;",
                          "uint32_t k = (uint32_t)p - 1u - draw(seed, l, (uint32_t)event, phase) % (uint32_t)p;"),
     "ar_halves_overlap": ("    t_off = T;\n", "    t_off = 0;\n"),
+    "broadcast_root_ignored": ("held[(size_t)root * W + (j >> 6)] |= 1ull << (j & 63);",
+                               "held[(size_t)0 * W + (j >> 6)] |= 1ull << (j & 63);"),
+    "broadcast_counts_all_gather_chunks": ("(root == ORC_NONE) ? (uint64_t)N * cpn : (uint64_t)cpn;",
+                                           "(uint64_t)N * cpn;"),
+    "reduce_not_reversed": ("const int has_rev = collective == ORC_REDUCE_SCATTER || collective == ORC_ALL_REDUCE || collective == ORC_REDUCE;",
+                            "const int has_rev = collective == ORC_REDUCE_SCATTER || collective == ORC_ALL_REDUCE;"),
 }
 
 
@@ -74,14 +80,14 @@ def _build(name):
     return lib
 
 
-def _run(lib, topo, cpn=1, cb=MiB, coll=0, seed=0, link_order=0, matching=0):
+def _run(lib, topo, cpn=1, cb=MiB, coll=0, seed=0, link_order=0, matching=0, root=0):
     res = ctypes.POINTER(oracle._CResult)()
     rp = np.ascontiguousarray(topo.row_ptr, dtype=np.uint32)
     ci = np.ascontiguousarray(topo.col_idx, dtype=np.uint32)
     al = np.ascontiguousarray(topo.alpha_ps, dtype=np.uint64)
     be = np.ascontiguousarray(topo.beta_fs_per_B, dtype=np.uint64)
     rc = lib.orc_synthesize(topo.n_npus, rp.ctypes.data, ci.ctypes.data, al.ctypes.data, be.ctypes.data,
-                            cpn, cb, coll, seed, 0, 0, (1 << 64) - 1, 1, link_order, matching, ctypes.byref(res))
+                            cpn, cb, coll, seed, 0, 0, (1 << 64) - 1, 1, link_order, matching, root, ctypes.byref(res))
     if rc != 0:
         raise RuntimeError(f"rc={rc}")
     r = res.contents
@@ -155,6 +161,18 @@ def _pins(lib):
         opt = checker.optimal_steps_unit(n, edges)
         Tt, ev, xf = _run(lib, topo, cb=1, seed=1)
         assert opt <= ev <= opt + 1 and Tt == ev
+    # Broadcast from a root: pipelined on a one-way ring (N - 2 + k spans for k chunks), one
+    # span on a complete graph, valid and maximal on a heterogeneous torus; Reduce = its reverse
+    Tt, ev, xf = _run(lib, T.ring(7), cpn=5, coll=3, seed=8, root=3)
+    assert (Tt, ev, len(xf)) == (10 * 21_471_520, 10, 30) and set(xf["chunk"].tolist()) == set(range(5))
+    assert int(xf[0]["src"]) == 3 and int(xf[0]["t_ps"]) == 0
+    Tt, ev, xf = _run(lib, T.fully_connected(6), cpn=1, coll=3, root=4)
+    assert ev == 1 and set(xf["src"].tolist()) == {4} and len(xf) == 5
+    cost = checker.link_costs_ps(het.alpha_ps, het.beta_fs_per_B, 64 << 10)
+    Tt, ev, xf = _run(lib, het, cpn=6, cb=64 << 10, coll=3, seed=3, root=11)
+    checker.check_all_gather(18, het.link_src, het.link_dst, cost, 6, xf, Tt, check_maximal=True, root=11)
+    Tt, ev, xf = _run(lib, het, cpn=4, cb=64 << 10, coll=4, seed=3, root=7)
+    checker.check_reduce_scatter(18, het.link_src, het.link_dst, cost, 4, xf, Tt, root=7)
     # lower-cost-link priority closed form
     par = T.from_edge_list(2, [(0, 1, 10, 0), (0, 1, 1, 0), (1, 0, 1, 0)])
     assert _run(lib, par, cb=1, link_order=1)[0] == 1 and _run(lib, par, cb=1, link_order=0)[0] == 10

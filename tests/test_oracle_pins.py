@@ -463,3 +463,106 @@ def test_postcondition_centric_against_set_based_implementation(lo):
         want_rs = sorted((Tr - t - cost[l], l, c) for (t, l, c) in rev)
         got_rs = [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in rs.xfers]
         assert got_rs == want_rs and rs.collective_time_ps == Tr
+
+
+# ------------------------------------------------------------------ Broadcast / Reduce
+# Paragraph "Collectives with Reduction Operations": Reduce is synthesized as the Broadcast
+# on the reversed links, reversed back (as Reduce-Scatter is from All-Gather).
+
+@pytest.mark.parametrize("n,k,root", [(2, 1, 0), (5, 1, 2), (6, 4, 5), (9, 7, 3), (4, 70, 1)])
+@pytest.mark.parametrize("seed", [0, 11])
+def test_broadcast_is_pipelined_on_a_one_way_ring(n, k, root, seed):
+    """k chunks from the root of a one-way N-ring: the link out of the root is busy for k
+    spans, every later NPU is one span behind its predecessor: N - 2 + k spans, whatever
+    chunks the random choices pick."""
+    topo = T.ring(n)
+    r = run(topo, cpn=k, coll=T.BROADCAST, seed=seed, root=root)
+    c = costs(topo, MiB)[0]
+    assert (r.collective_time_ps, r.n_events, r.n_xfers) == ((n - 2 + k) * c, n - 2 + k, k * (n - 1))
+    checker.check_all_gather(n, topo.link_src, topo.link_dst, costs(topo, MiB), k, r.xfers,
+                             r.collective_time_ps, check_maximal=True, root=root)
+    # hop h of the ring forwards its first chunk exactly h spans after the start
+    first = {}
+    for x in r.xfers:
+        first.setdefault(int(x["src"]), int(x["t_ps"]))
+    assert first == {(root + h) % n: h * c for h in range(n - 1)}
+
+
+def test_broadcast_closed_forms():
+    # complete graph, one chunk: one span, every transfer leaves the root
+    r = run(T.fully_connected(7), coll=T.BROADCAST, root=6)
+    assert r.n_events == 1 and set(r.xfers["src"].tolist()) == {6} and r.n_xfers == 6
+    # two-way ring, one chunk: both directions at once, ceil((N-1)/2) spans
+    for n in (3, 4, 7, 10):
+        r = run(T.ring(n, bidirectional=True), coll=T.BROADCAST, root=n - 1)
+        assert r.n_events == n // 2
+    # 2 NPUs, k chunks over one link: k spans, every chunk exactly once
+    two = T.from_edge_list(2, [(0, 1, 1, 0), (1, 0, 1, 0)])
+    r = run(two, cpn=9, chunk_bytes=1, coll=T.BROADCAST, seed=4, root=1)
+    assert r.n_events == 9 and sorted(r.xfers["chunk"].tolist()) == list(range(9))
+    assert set(r.xfers["link"].tolist()) == {1}
+    # the first choice follows the published Philox vector (counter 0, key 0): link 0, span 0
+    r = run(two, cpn=200, chunk_bytes=1, coll=T.BROADCAST, seed=0, root=0)
+    assert int(r.xfers[0]["chunk"]) == 0x6627E8D5 % 200
+
+
+@pytest.mark.parametrize("name,mk,cpn", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("matching", [0, 1])
+def test_broadcast_valid_maximal_and_bounded(name, mk, cpn, matching):
+    topo = mk()
+    cb = 64 << 10
+    k = 3 * cpn + 1
+    root = topo.n_npus // 2
+    r = run(topo, cpn=k, chunk_bytes=cb, coll=T.BROADCAST, seed=5, root=root, matching=matching)
+    cost = costs(topo, cb)
+    Tend = checker.check_all_gather(topo.n_npus, topo.link_src, topo.link_dst, cost, k, r.xfers,
+                                    r.collective_time_ps, check_maximal=True, root=root)
+    # every NPU but the root receives k chunks over its incoming links; the farthest NPU is a
+    # shortest path away from the root
+    deg = np.bincount(topo.col_idx, minlength=topo.n_npus)
+    slowest_in = [min(cost[l] for l in range(topo.n_links) if topo.col_idx[l] == d) for d in range(topo.n_npus)]
+    for d in range(topo.n_npus):
+        if d != root:
+            assert Tend >= -(-k // int(deg[d])) * slowest_in[d]
+    assert int(r.event_matches.sum()) == r.n_xfers == k * (topo.n_npus - 1)
+
+
+@pytest.mark.parametrize("mk,k,root", [(lambda: T.mesh2d(3, 3), 2, 4),
+                                       (lambda: T.grid([3, 2, 3], True, [300_000, 500_000, 1_000_000],
+                                                       [5_000, 10_000, 20_000]), 3, 17),
+                                       (lambda: T.random_regular_out(14, 2, seed=9)[0], 5, 0)])
+def test_reduce_is_the_reversed_broadcast(mk, k, root):
+    """Reduce: an in-tree to the root for every chunk, an NPU forwards its partial sum once
+    and only after every contribution to it has arrived; and it takes exactly as long as
+    the Broadcast from the same root on the topology with every link reversed would if both
+    drew the same random numbers -- checked through the invariants, and through the time
+    on a topology whose reversal is itself (a mesh with symmetric links and equal costs),
+    where Reduce and Broadcast must meet the same bounds."""
+    topo = mk()
+    cb = 128 << 10
+    cost = costs(topo, cb)
+    r = run(topo, cpn=k, chunk_bytes=cb, coll=T.REDUCE, seed=6, root=root)
+    checker.check_reduce_scatter(topo.n_npus, topo.link_src, topo.link_dst, cost, k, r.xfers,
+                                 r.collective_time_ps, root=root)
+    assert r.n_xfers == k * (topo.n_npus - 1)
+    # every transfer that arrives at the root is the last hop of its chunk's tree; the root never sends
+    assert root not in set(r.xfers["src"].tolist())
+    assert r.pass_time_ps[0] == r.collective_time_ps
+
+
+def test_reduce_on_a_one_way_ring_is_a_pipeline_into_the_root():
+    n, k, root = 6, 3, 2
+    topo = T.ring(n)
+    c = costs(topo, MiB)[0]
+    r = run(topo, cpn=k, coll=T.REDUCE, seed=1, root=root)
+    assert (r.collective_time_ps, r.n_events) == ((n - 2 + k) * c, n - 2 + k)
+    # the NPU right after the root on the ring is the farthest from it: it sends first
+    assert int(r.xfers[0]["src"]) == (root + 1) % n and int(r.xfers[0]["t_ps"]) == 0
+    assert int(r.xfers[-1]["dst"]) == root
+
+
+def test_rooted_collectives_reject_bad_roots():
+    with pytest.raises(oracle.OracleError):
+        run(T.ring(4), coll=T.BROADCAST, root=4)
+    with pytest.raises(oracle.OracleError):
+        run(T.ring(4), coll=5)
