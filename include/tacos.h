@@ -64,7 +64,14 @@ extern "C" {
 typedef enum {
   TACOS_ALL_GATHER = 0,
   TACOS_REDUCE_SCATTER = 1,
-  TACOS_ALL_REDUCE = 2
+  TACOS_ALL_REDUCE = 2,
+  /* Rooted collectives (paragraph "Collectives with Reduction Operations": Reduce is the
+   * Broadcast synthesized on the reversed links, reversed back).  The buffer of the root
+   * (tacos_options_t::root) is split into chunks_per_npu chunks, ids 0 .. chunks_per_npu-1;
+   * Broadcast: all of them start at the root and reach every NPU (one forward pass, phase
+   * 0); Reduce: the reverse (one reversed pass, phase 1).  Same loop, same matching. */
+  TACOS_BROADCAST = 3,
+  TACOS_REDUCE = 4
 } tacos_collective_t;
 
 /* Error codes (every entry point that returns int: 0 = success, negative = error). */
@@ -86,7 +93,7 @@ typedef enum {
 #define TACOS_MATCH_LINK_CENTRIC  0u
 #define TACOS_MATCH_POSTCONDITION 1u
 
-/* Largest supported number of chunks N*chunks_per_npu (one wavefront keeps a
+/* Largest supported number of chunks N*chunks_per_npu (rooted collectives: chunks_per_npu) (one wavefront keeps a
  * destination's whole "still needed" bitset in its share of the LDS and a source's
  * whole row in registers). */
 #define TACOS_MAX_CHUNKS 65536u
@@ -146,6 +153,8 @@ typedef struct {
                              which equals visiting a shuffled list of unsatisfied (d, c)
                              pairs and giving each a random free holder.  Needs in-degree
                              <= 64 (TACOS_E_INVAL otherwise).                                */
+  uint32_t root;          /* TACOS_BROADCAST / TACOS_REDUCE: the root NPU (< n_npus, else
+                             TACOS_E_INVAL); ignored by the other collectives                */
 } tacos_options_t;
 
 typedef struct tacos_result tacos_result_t; /* opaque; owns device and host buffers */

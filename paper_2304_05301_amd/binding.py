@@ -16,7 +16,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtacos_hip.so")
 
-TACOS_ALL_GATHER, TACOS_REDUCE_SCATTER, TACOS_ALL_REDUCE = 0, 1, 2
+TACOS_ALL_GATHER, TACOS_REDUCE_SCATTER, TACOS_ALL_REDUCE, TACOS_BROADCAST, TACOS_REDUCE = 0, 1, 2, 3, 4
 TACOS_OK = 0
 TACOS_E_INVAL, TACOS_E_UNREACHABLE, TACOS_E_OVERFLOW, TACOS_E_NOMEM, TACOS_E_DEVICE = -1, -2, -3, -4, -5
 TACOS_LINK_ORDER_ID, TACOS_LINK_ORDER_COST = 0, 1
@@ -47,7 +47,8 @@ class _Topology(ctypes.Structure):
 class _Options(ctypes.Structure):
     _fields_ = [("stream", ctypes.c_void_p), ("max_events", ctypes.c_uint64),
                 ("time_kernels", ctypes.c_uint32), ("launch_mode", ctypes.c_uint32),
-                ("link_order", ctypes.c_uint32), ("matching", ctypes.c_uint32)]
+                ("link_order", ctypes.c_uint32), ("matching", ctypes.c_uint32),
+                ("root", ctypes.c_uint32)]
 
 
 class TacosError(RuntimeError):
@@ -214,13 +215,13 @@ class TacosResult:
 def tacos_synthesize(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_per_npu,
                      chunk_bytes, collective, seed, stream: int = 0, max_events: int = 0,
                      time_kernels: bool = False, launch_mode: int = 0,
-                     link_order: int = 0, matching: int = 0) -> TacosResult:
+                     link_order: int = 0, matching: int = 0, root: int = 0) -> TacosResult:
     """tacos_synthesize of include/tacos.h.  `stream` is a raw hipStream_t value (for a
     torch stream: torch.cuda.current_stream().cuda_stream); 0 = the null stream."""
     L = load()
     topo, keep = _topology_struct(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B)
     opts = _Options(ctypes.c_void_p(int(stream) or None), int(max_events), 1 if time_kernels else 0,
-                    int(launch_mode), int(link_order), int(matching))
+                    int(launch_mode), int(link_order), int(matching), int(root))
     out = ctypes.c_void_p(None)
     rc = L.tacos_synthesize(ctypes.byref(topo), int(chunks_per_npu), int(chunk_bytes),
                             int(collective), int(seed), ctypes.byref(opts), ctypes.byref(out))
@@ -232,12 +233,12 @@ def tacos_synthesize(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_p
 
 def tacos_seed_search(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_per_npu,
                       chunk_bytes, collective, seeds, stream: int = 0, launch_mode: int = 0,
-                      link_order: int = 0, matching: int = 0):
+                      link_order: int = 0, matching: int = 0, root: int = 0):
     """tacos_seed_search of include/tacos.h: (time_ps[n_seeds], num_events[n_seeds], best index)."""
     L = load()
     topo, keep = _topology_struct(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B)
     opts = _Options(ctypes.c_void_p(int(stream) or None), 0, 0, int(launch_mode), int(link_order),
-                    int(matching))
+                    int(matching), int(root))
     seeds = np.ascontiguousarray(np.asarray(seeds, dtype=np.uint64))
     times = np.zeros(len(seeds), dtype=np.uint64)
     events = np.zeros(len(seeds), dtype=np.uint64)

@@ -264,16 +264,19 @@ void build_pass_graph(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc,
   HIP_TRY(hipStreamSynchronize(stream));
 }
 
+// Chunks of the collective: every NPU contributes cpn, or (rooted) the root's cpn alone.
+uint32_t total_chunks(uint32_t N, uint32_t cpn, uint32_t root) { return root == tacos::kNoRoot ? N * cpn : cpn; }
+
 // Per-pass device state descriptor over a graph; held / carry / free_at / ctl are the
 // pass's own buffers.
-PassDev make_pass_dev(const PassGraph &g, const DevBuf &d_cost, uint32_t cpn, uint64_t seed, uint32_t phase,
-                      bool reversed, unsigned long long *held, uint32_t *carry, unsigned long long *free_at,
-                      Ctl *ctl)
+PassDev make_pass_dev(const PassGraph &g, const DevBuf &d_cost, uint32_t cpn, uint32_t root, uint64_t seed,
+                      uint32_t phase, bool reversed, unsigned long long *held, uint32_t *carry,
+                      unsigned long long *free_at, Ctl *ctl)
 {
-  const uint32_t C = g.N * cpn;
+  const uint32_t C = total_chunks(g.N, cpn, root);
   const uint32_t NP = (C + 8191u) / 8192u;
   PassDev p{};
-  p.N = g.N; p.L = g.L; p.cpn = cpn; p.NP = NP; p.C = C; p.phase = phase;
+  p.N = g.N; p.L = g.L; p.cpn = cpn; p.NP = NP; p.C = C; p.root = root; p.phase = phase;
   p.seed_lo = (uint32_t)(seed & 0xFFFFFFFFull); p.seed_hi = (uint32_t)(seed >> 32);
   p.row_words = NP * 128u; p.reversed = reversed ? 1u : 0u;
   p.held = held;
@@ -300,11 +303,11 @@ bool fits_small_kernel(uint32_t N, uint32_t L, uint32_t NP)
 
 // Runs one All-Gather pass over links psrc[l] -> pdst[l] and stores its schedule rows.
 int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
-             const DevBuf &d_cost, uint32_t cpn, uint64_t seed, uint32_t phase, bool reversed,
+             const DevBuf &d_cost, uint32_t cpn, uint32_t root, uint64_t seed, uint32_t phase, bool reversed,
              uint64_t max_events, bool time_kernels, uint32_t launch_mode, const std::vector<uint64_t> *order_cost,
              uint32_t match_mode, hipStream_t stream, tacos_result &res, Pass &pass)
 {
-  const uint32_t C = N * cpn;
+  const uint32_t C = total_chunks(N, cpn, root);
   const uint32_t NP = (C + 8191u) / 8192u;
   pass.reversed = reversed;
   pass.L = L;
@@ -328,7 +331,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   d_carry.alloc((size_t)L * 4);
   d_free_at.alloc((size_t)L * 8);
   d_ctl.alloc(sizeof(Ctl));
-  PassDev p = make_pass_dev(g, d_cost, cpn, seed, phase, reversed, d_held.as<unsigned long long>(),
+  PassDev p = make_pass_dev(g, d_cost, cpn, root, seed, phase, reversed, d_held.as<unsigned long long>(),
                             d_carry.as<uint32_t>(), d_free_at.as<unsigned long long>(), d_ctl.as<Ctl>());
   // per-span launches: destinations that hold every chunk are dropped from the order
   DevBuf d_done;
@@ -515,10 +518,16 @@ void finish_pass(Pass &pass, uint64_t t_off, uint64_t *digest, hipStream_t strea
   pass.n_xfers = pass.canon_base[pass.n_rows];
 }
 
-int validate(const tacos_topology_t *topo, uint32_t cpn, uint64_t chunk_bytes, int coll)
+bool is_rooted(int coll) { return coll == TACOS_BROADCAST || coll == TACOS_REDUCE; }
+// a reversed pass (on the swapped orientation, mapped back in time) and / or a forward pass
+bool has_reversed_pass(int coll) { return coll == TACOS_REDUCE_SCATTER || coll == TACOS_ALL_REDUCE || coll == TACOS_REDUCE; }
+bool has_forward_pass(int coll) { return coll == TACOS_ALL_GATHER || coll == TACOS_ALL_REDUCE || coll == TACOS_BROADCAST; }
+
+int validate(const tacos_topology_t *topo, uint32_t cpn, uint64_t chunk_bytes, int coll, const tacos_options_t *opts)
 {
   if (!topo || !topo->row_ptr || topo->n_npus == 0 || cpn == 0 || chunk_bytes == 0) return TACOS_E_INVAL;
-  if (coll != TACOS_ALL_GATHER && coll != TACOS_REDUCE_SCATTER && coll != TACOS_ALL_REDUCE) return TACOS_E_INVAL;
+  if (coll < TACOS_ALL_GATHER || coll > TACOS_REDUCE) return TACOS_E_INVAL;
+  if (is_rooted(coll) && opts && opts->root >= topo->n_npus) return TACOS_E_INVAL;
   const uint32_t N = topo->n_npus;
   if (topo->row_ptr[0] != 0) return TACOS_E_INVAL;
   for (uint32_t i = 0; i < N; ++i)
@@ -526,7 +535,7 @@ int validate(const tacos_topology_t *topo, uint32_t cpn, uint64_t chunk_bytes, i
   const uint32_t L = topo->row_ptr[N];
   if (L != topo->n_links) return TACOS_E_INVAL;
   if (L && (!topo->col_idx || !topo->alpha_ps || !topo->beta_fs_per_B)) return TACOS_E_INVAL;
-  if ((uint64_t)N * cpn > TACOS_MAX_CHUNKS) return TACOS_E_INVAL;
+  if ((is_rooted(coll) ? (uint64_t)cpn : (uint64_t)N * cpn) > TACOS_MAX_CHUNKS) return TACOS_E_INVAL;
   for (uint32_t i = 0; i < N; ++i)
     for (uint32_t l = topo->row_ptr[i]; l < topo->row_ptr[i + 1]; ++l)
       if (topo->col_idx[l] >= N || topo->col_idx[l] == i) return TACOS_E_INVAL;
@@ -587,7 +596,7 @@ int resolve_match_mode(const tacos_topology_t *topo, int coll, const tacos_optio
   }
   for (uint32_t i = 0; i < topo->n_npus; ++i) {
     // the reversed pass of a Reduce-Scatter walks the out-links as incoming links
-    const bool fwd = coll != TACOS_REDUCE_SCATTER, rev = coll != TACOS_ALL_GATHER;
+    const bool fwd = has_forward_pass(coll), rev = has_reversed_pass(coll);
     if ((fwd && deg_in[i] > 64) || (rev && deg_out[i] > 64)) return TACOS_E_INVAL;
   }
   *mode = opts->link_order == TACOS_LINK_ORDER_COST ? 2u : 1u;
@@ -604,10 +613,10 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
 {
   g_last_error.clear();
   if (!out) return TACOS_E_INVAL;
-  int rc = validate(topo, chunks_per_npu, chunk_bytes, (int)coll);
+  int rc = validate(topo, chunks_per_npu, chunk_bytes, (int)coll, opts);
   if (rc != TACOS_OK) return rc;
   const uint64_t max_events = opts ? opts->max_events : 0;
-  if (max_events && coll != TACOS_ALL_GATHER) return TACOS_E_INVAL;
+  if (max_events && has_reversed_pass((int)coll)) return TACOS_E_INVAL;
   if (opts && (opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 2 ||
                opts->matching > TACOS_MATCH_POSTCONDITION))
     return TACOS_E_INVAL;
@@ -617,6 +626,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
   if (rc != TACOS_OK) return rc;
   const bool time_kernels = opts && opts->time_kernels;
   const uint32_t launch_mode = opts ? opts->launch_mode : 0;
+  const uint32_t root = is_rooted((int)coll) ? (opts ? opts->root : 0u) : tacos::kNoRoot;
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
 
   const auto wall0 = std::chrono::steady_clock::now();
@@ -639,7 +649,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       // a single NPU holds everything at t = 0: no span is expanded
       for (int i = 0; i < n_pass; ++i) {
         Pass ps;
-        ps.reversed = (coll != TACOS_ALL_GATHER) && i == 0;
+        ps.reversed = has_reversed_pass((int)coll) && i == 0;
         ps.canon_base.assign(1, 0);
         res->passes.push_back(std::move(ps));
       }
@@ -652,18 +662,18 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       if (rc != TACOS_OK) return rc;
       const std::vector<uint64_t> *order_cost = by_cost ? &host_cost : nullptr;
       uint64_t t_off = 0;
-      if (coll == TACOS_REDUCE_SCATTER || coll == TACOS_ALL_REDUCE) {
+      if (has_reversed_pass((int)coll)) {
         // reversed pass: every link (s -> d) is used as (d -> s), ids and costs unchanged
         res->passes.emplace_back();
-        rc = run_pass(N, L, res->link_dst, res->link_src, d_cost, chunks_per_npu, seed, 1u, true, 0,
+        rc = run_pass(N, L, res->link_dst, res->link_src, d_cost, chunks_per_npu, root, seed, 1u, true, 0,
                       time_kernels, launch_mode, order_cost, match_mode, stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), 0, &res->digest, stream);
         t_off = res->passes.back().T;
       }
-      if (coll == TACOS_ALL_GATHER || coll == TACOS_ALL_REDUCE) {
+      if (has_forward_pass((int)coll)) {
         res->passes.emplace_back();
-        rc = run_pass(N, L, res->link_src, res->link_dst, d_cost, chunks_per_npu, seed, 0u, false,
+        rc = run_pass(N, L, res->link_src, res->link_dst, d_cost, chunks_per_npu, root, seed, 0u, false,
                       max_events, time_kernels, launch_mode, order_cost, match_mode, stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), t_off, &res->digest, stream);
@@ -691,7 +701,7 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
 {
   g_last_error.clear();
   if (!seeds || n_seeds == 0 || !time_ps) return TACOS_E_INVAL;
-  int rc = validate(topo, chunks_per_npu, chunk_bytes, (int)coll);
+  int rc = validate(topo, chunks_per_npu, chunk_bytes, (int)coll, opts);
   if (rc != TACOS_OK) return rc;
   if (opts && (opts->max_events != 0 || opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 2 ||
                opts->matching > TACOS_MATCH_POSTCONDITION))
@@ -700,6 +710,7 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
   rc = resolve_match_mode(topo, (int)coll, opts, &match_mode);
   if (rc != TACOS_OK) return rc;
   const uint32_t launch_mode = opts ? opts->launch_mode : 0;
+  const uint32_t root = is_rooted((int)coll) ? (opts ? opts->root : 0u) : tacos::kNoRoot;
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
   int device = 0;
   rc = require_device(&device);
@@ -720,7 +731,7 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
   if (L == 0) return TACOS_E_UNREACHABLE;
 
   try {
-    const uint32_t C = N * chunks_per_npu;
+    const uint32_t C = total_chunks(N, chunks_per_npu, root);
     const uint32_t NP = (C + 8191u) / 8192u;
     const bool concurrent = launch_mode != 1 && fits_small_kernel(N, L, NP);
     if (!concurrent && launch_mode == 2) {
@@ -750,7 +761,7 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
     rc = device_costs(topo, chunk_bytes, stream, d_cost, by_cost ? &host_cost : nullptr);
     if (rc != TACOS_OK) return rc;
     const std::vector<uint64_t> *order_cost = by_cost ? &host_cost : nullptr;
-    const bool want_rev = coll != TACOS_ALL_GATHER, want_fwd = coll != TACOS_REDUCE_SCATTER;
+    const bool want_rev = has_reversed_pass((int)coll), want_fwd = has_forward_pass((int)coll);
     PassGraph g_rev, g_fwd;
     if (want_rev) build_pass_graph(N, L, link_dst, link_src, order_cost, stream, g_rev);
     if (want_fwd) build_pass_graph(N, L, link_src, link_dst, order_cost, stream, g_fwd);
@@ -772,7 +783,7 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
           const uint32_t j = i * per_seed + k;
           const bool rev = want_rev && k == 0;
           const PassGraph &g = rev ? g_rev : g_fwd;
-          jobs[j].p = make_pass_dev(g, d_cost, chunks_per_npu, seeds[s0 + i], rev ? 1u : 0u, rev,
+          jobs[j].p = make_pass_dev(g, d_cost, chunks_per_npu, root, seeds[s0 + i], rev ? 1u : 0u, rev,
                                     d_held.as<unsigned long long>() + (size_t)j * N * (row_bytes / 8),
                                     d_carry.as<uint32_t>() + (size_t)j * L,
                                     d_free.as<unsigned long long>() + (size_t)j * L, d_ctl.as<Ctl>() + j);

@@ -42,9 +42,12 @@ struct Ctl {
 // (lane, piece, half, bit), and one wave prefix sum over per-lane popcounts locates
 // the k-th candidate.  Bits of chunk ids >= C are stored as 1 ("held") in every row so
 // that they never become candidates.
+constexpr uint32_t kNoRoot = 0xFFFFFFFFu;
+
 struct PassDev {
   uint32_t N, L, cpn, NP;
-  uint32_t C;
+  uint32_t C;                      // chunks: N*cpn, or cpn for a rooted collective
+  uint32_t root;                   // kNoRoot: NPU i owns chunks [i*cpn, (i+1)*cpn); else the root owns all C
   uint32_t phase;
   uint32_t seed_lo, seed_hi;
   uint32_t row_words;              // 64-bit words per row = NP*128

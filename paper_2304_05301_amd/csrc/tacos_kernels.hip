@@ -152,7 +152,9 @@ __global__ void init_rows_kernel(PassDev p)
   const u32 piece = ph >> 7, ln = (ph & 127u) >> 1, half = ph & 1u;
   const u32 w = ln * 2u * p.NP + piece * 2u + half;  // logical word
   const u64 c0 = (u64)w * 64ull;
-  const u64 own_lo = (u64)npu * p.cpn, own_hi = own_lo + p.cpn;  // [own_lo, own_hi)
+  // chunks the NPU holds at t = 0: [own_lo, own_hi)
+  u64 own_lo = (u64)npu * p.cpn, own_hi = own_lo + p.cpn;
+  if (p.root != kNoRoot) { own_lo = 0; own_hi = npu == p.root ? p.C : 0; }
   u64 bits = 0;
   for (u32 b = 0; b < 64; ++b) {
     const u64 c = c0 + b;

@@ -3,7 +3,7 @@
     python tests/fuzz_parity.py [--cases 400] [--seed 1]
 
 Draws small random workloads (random out-regular heterogeneous graphs, rings, meshes, tori,
-unwound switches; 1..70 chunks per NPU; all three collectives; both matching orders; both
+unwound switches; 1..70 chunks per NPU; all five collectives; both matching orders; both
 link orders; every launch mode) and compares the GPU schedule with the CPU oracle record
 by record.  Prints one line per case and stops at the first difference."""
 import argparse
@@ -57,7 +57,10 @@ def main():
         max_cpn = max(1, min(70, 16000 // topo.n_npus))
         cpn = int(rng.integers(1, max_cpn + 1))
         cb = int(rng.integers(1, 1 << 22))
-        coll = int(rng.integers(0, 3))
+        coll = int(rng.integers(0, 5))  # 3, 4: Broadcast / Reduce with a random root
+        root = int(rng.integers(0, topo.n_npus))
+        if coll >= 3:
+            cpn = int(rng.integers(1, 9000))
         seed = int(rng.integers(0, 1 << 62))
         matching = int(rng.integers(0, 2))
         link_order = int(rng.integers(0, 2))
@@ -66,7 +69,7 @@ def main():
         deg_out = np.diff(topo.row_ptr).max()
         if matching == 1 and max(deg_in, deg_out) > 64:
             matching = 0
-        kw = dict(matching=matching, link_order=link_order)
+        kw = dict(matching=matching, link_order=link_order, root=root)
         ref = oracle.synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B,
                                 cpn, cb, coll, seed, **kw)
         r = binding.tacos_synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B,

@@ -45,7 +45,8 @@ def test_invalid_arguments_are_rejected_before_any_device_work():
         return binding.tacos_synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps,
                                         topo.beta_fs_per_B, cpn, cb, coll, 0, **kw)
 
-    for kw in (dict(cpn=0), dict(cb=0), dict(coll=3)):
+    for kw in (dict(cpn=0), dict(cb=0), dict(coll=5), dict(coll=3, root=4), dict(coll=4, root=2**32 - 1),
+               dict(coll=3, cpn=binding.TACOS_MAX_CHUNKS + 1), dict(coll=4, max_events=3)):
         with pytest.raises(binding.TacosError) as e:
             call(good, **kw)
         assert e.value.code == binding.TACOS_E_INVAL

@@ -518,3 +518,63 @@ def test_best_of_seeds_returns_the_winning_schedule(stream):
         ref = oracle.synthesize_workload(T.Workload(w.name, w.topo, w.chunks_per_npu, w.chunk_bytes,
                                                     w.collective, seed))
         assert_same(r, ref, "best of 40 seeds")
+
+
+# ---------------------------------------------------------------- Broadcast / Reduce
+
+ROOTED = [
+    ("ring7_k5", lambda: T.ring(7), 5, 3),
+    ("biring10_k1", lambda: T.ring(10, bidirectional=True), 1, 9),
+    ("fc12_k40", lambda: T.fully_connected(12), 40, 0),
+    ("mesh6x5_k300", lambda: T.mesh2d(6, 5), 300, 14),
+    ("hetero_torus_k77", lambda: T.grid([3, 3, 4], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000]), 77, 35),
+    ("random50_k9000_two_piece_rows", lambda: T.random_regular_out(50, 3, seed=21)[0], 9000, 17),
+    ("switch9d2_k13", lambda: T.switch_unwound(9, 2), 13, 8),
+]
+
+
+@pytest.mark.parametrize("name,mk,k,root", ROOTED, ids=[c[0] for c in ROOTED])
+@pytest.mark.parametrize("coll", [T.BROADCAST, T.REDUCE])
+@pytest.mark.parametrize("mode", [1, 2])
+def test_broadcast_and_reduce_bit_exact(name, mk, k, root, coll, mode, stream):
+    """Rooted collectives (the root's k chunks to every NPU; Reduce = the reverse) against
+    the oracle, through the per-span launches and the single-workgroup kernel."""
+    topo = mk()
+    cb = 256 << 10
+    ref = cpu(topo, k, cb, coll, 31, root=root)
+    with gpu(topo, k, cb, coll, 31, stream, root=root, launch_mode=mode) as r:
+        assert_same(r, ref, name)
+        assert r.num_passes == 1 and r.num_xfers == k * (topo.n_npus - 1)
+
+
+@pytest.mark.parametrize("coll", [T.BROADCAST, T.REDUCE])
+def test_rooted_collectives_with_both_matching_orders_and_link_orders(coll, stream):
+    topo = T.grid([4, 3, 3], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000])
+    for matching in (0, 1):
+        for link_order in (0, 1):
+            ref = cpu(topo, 50, MiB, coll, 8, root=20, matching=matching, link_order=link_order)
+            with gpu(topo, 50, MiB, coll, 8, stream, root=20, matching=matching, link_order=link_order) as r:
+                assert_same(r, ref, f"matching {matching} link_order {link_order}")
+
+
+def test_broadcast_on_the_40960_npu_torus(stream):
+    """Broadcast of 4,096 chunks from one corner of the 32x32x40 torus, record by record."""
+    topo = T.workload(5).topo
+    ref = oracle.synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B,
+                            64, MiB, T.BROADCAST, 12, root=0, max_events=60, n_threads=min(16, oracle.max_threads()))
+    with gpu(topo, 64, MiB, T.BROADCAST, 12, stream, root=0, max_events=60) as r:
+        assert_same(r, ref, "prefix of 60 spans")
+
+
+def test_rooted_seed_search_and_limits(stream):
+    topo = T.mesh2d(5, 5)
+    seeds = np.arange(30, dtype=np.uint64)
+    for coll in (T.BROADCAST, T.REDUCE):
+        want_t, want_e = oracle_times(topo, 20, MiB, coll, seeds, root=12)
+        times, events, best = search(topo, 20, MiB, coll, seeds, stream, root=12)
+        assert np.array_equal(times, want_t) and np.array_equal(events, want_e) and best == int(np.argmin(want_t))
+    with pytest.raises(binding.TacosError) as e:
+        gpu(topo, 3, MiB, T.BROADCAST, 0, stream, root=25)
+    assert e.value.code == binding.TACOS_E_INVAL
+    with gpu(T.from_edge_list(1, []), 5, MiB, T.BROADCAST, 0, stream, root=0) as r:
+        assert r.num_xfers == 0 and r.collective_time_ps == 0
