@@ -578,3 +578,23 @@ def test_rooted_seed_search_and_limits(stream):
     assert e.value.code == binding.TACOS_E_INVAL
     with gpu(T.from_edge_list(1, []), 5, MiB, T.BROADCAST, 0, stream, root=0) as r:
         assert r.num_xfers == 0 and r.collective_time_ps == 0
+
+
+@pytest.mark.parametrize("coll", [T.ALL_GATHER, T.ALL_REDUCE])
+def test_heterogeneous_4096_npu_torus_through_the_per_span_launches(coll, stream):
+    """16x16x16 torus with three link classes (24,576 links: too many for the single-workgroup
+    kernel): spans at many distinct times, several events at one time, complete destinations
+    dropped from the launches.  Times, spans, transfers, digest over all 16.8 M (33.5 M)
+    transfers, the per-span trace and the first and last 100,000 records."""
+    topo = T.grid([16, 16, 16], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000])
+    nt = min(16, oracle.max_threads())
+    ref = cpu(topo, 1, MiB, coll, 77, keep_first=0, keep_xfers=100_000, n_threads=nt)
+    with gpu(topo, 1, MiB, coll, 77, stream) as r:
+        assert r.collective_time_ps == ref.collective_time_ps and r.num_events == ref.n_events
+        assert r.num_xfers == ref.n_xfers and r.digest == ref.digest
+        if coll == T.ALL_GATHER:
+            t, m = r.event_trace(0)
+            assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches)
+            assert np.array_equal(r.read(0, 100_000), ref.xfers)
+            tail = cpu(topo, 1, MiB, coll, 77, keep_first=ref.n_xfers - 100_000, keep_xfers=100_000, n_threads=nt)
+            assert np.array_equal(r.read(ref.n_xfers - 100_000, 100_000), tail.xfers)
