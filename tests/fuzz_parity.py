@@ -47,6 +47,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--cases", type=int, default=400)
     ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--max-chunks", type=int, default=16000,
+                    help="upper limit of N * chunks_per_npu (rows of up to ceil(max/8192) one-KiB pieces)")
     args = ap.parse_args()
     import torch
     torch.cuda.set_device(0)
@@ -54,21 +56,32 @@ def main():
     rng = np.random.default_rng(args.seed)
     for case in range(args.cases):
         topo = draw_topology(rng)
-        max_cpn = max(1, min(70, 16000 // topo.n_npus))
+        max_cpn = max(1, min(700, args.max_chunks // topo.n_npus))
         cpn = int(rng.integers(1, max_cpn + 1))
         cb = int(rng.integers(1, 1 << 22))
         coll = int(rng.integers(0, 5))  # 3, 4: Broadcast / Reduce with a random root
         root = int(rng.integers(0, topo.n_npus))
         if coll >= 3:
-            cpn = int(rng.integers(1, 9000))
+            cpn = int(rng.integers(1, max(2, args.max_chunks // 2)))
         seed = int(rng.integers(0, 1 << 62))
         matching = int(rng.integers(0, 2))
         link_order = int(rng.integers(0, 2))
         mode = int(rng.integers(0, 3))
+        n_chunks = cpn if coll >= 3 else cpn * topo.n_npus
+        if mode == 2 and n_chunks > 16384:  # the single-workgroup kernel takes rows of up to two pieces
+            mode = 0
         deg_in = np.bincount(topo.col_idx, minlength=topo.n_npus).max()
         deg_out = np.diff(topo.row_ptr).max()
         if matching == 1 and max(deg_in, deg_out) > 64:
             matching = 0
+        # heterogeneous link costs: about one span per transfer, and the oracle walks every
+        # destination in every span -- keep its work bounded
+        hetero = len(set(zip(topo.alpha_ps.tolist(), topo.beta_fs_per_B.tolist()))) > 1
+        if hetero and n_chunks * topo.n_npus > 300_000:
+            cpn = max(1, 300_000 // (topo.n_npus * (1 if coll >= 3 else topo.n_npus)))
+            n_chunks = cpn if coll >= 3 else cpn * topo.n_npus
+        print(f"case {case}: {topo.name} N={topo.n_npus} L={topo.n_links} cpn={cpn} coll={coll} matching={matching} "
+              f"link_order={link_order} launch_mode={mode} ...", flush=True)
         kw = dict(matching=matching, link_order=link_order, root=root)
         ref = oracle.synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B,
                                 cpn, cb, coll, seed, **kw)
