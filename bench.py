@@ -128,7 +128,13 @@ def report_all(binding, T, stream, with_cpu):
         wall = time.perf_counter() - t0
         alg = algorithmic_bytes(r.num_xfers, topo.n_npus, topo.n_links, n_chunks)
         k_s = r.kernel_ms * 1e-3
+        # the paper's Ideal, bandwidth term only (collective size over the ingress bandwidth of the
+        # worst-connected NPU; the latency diameter is left out): efficiency = Ideal / collective time
+        from paper_2304_05301_amd import metrics
+        ideal = metrics.ideal_time_ps(topo.n_npus, w.chunks_per_npu, w.chunk_bytes, w.collective, topo.link_src,
+                                      topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B, with_diameter=False)
         row = {"idx": idx, "name": w.name, "npus": topo.n_npus, "links": topo.n_links, "spans": r.num_events,
+               "eff": ideal / r.collective_time_ps,
                "matches": r.num_xfers, "T_ps": r.collective_time_ps, "wall_s": wall, "kernel_s": k_s,
                "matches_per_s": r.num_xfers / wall, "alg_GBps": alg / k_s / 1e9 if k_s > 0 else 0.0}
         r.free()
@@ -137,17 +143,17 @@ def report_all(binding, T, stream, with_cpu):
             row["cpu"] = cb
         rows.append(row)
         print(f"[report] workload {idx} done", file=sys.stderr, flush=True)
-    print("| # | workload | NPUs | links | TEN spans | matches | collective time (ps) | GPU synthesis (s) | "
+    print("| # | workload | NPUs | links | TEN spans | matches | collective time (ps) | Ideal (bandwidth term) / time | GPU synthesis (s) | "
           "matches/s | matching kernel (s) | algorithmic GB/s in the matching kernel | fraction of 8 TB/s | "
           "oracle matches/s (host threads; sample) |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     for r in rows:
         cpu = "-"
         if "cpu" in r:
             c = r["cpu"]
             cpu = f"{c['value']:.3g} ({c['cores']}; {c['sample']}, {c['seconds']:.1f} s)"
         print(f"| {r['idx']} | {r['name']} | {r['npus']} | {r['links']} | {r['spans']} | {r['matches']} | {r['T_ps']} | "
-              f"{r['wall_s']:.4f} | {r['matches_per_s']:.3g} | {r['kernel_s']:.4f} | {r['alg_GBps']:.1f} | "
+              f"{r['eff']:.4f} | {r['wall_s']:.4f} | {r['matches_per_s']:.3g} | {r['kernel_s']:.4f} | {r['alg_GBps']:.1f} | "
               f"{r['alg_GBps'] / HBM_PEAK_GBS:.4f} | {cpu} |")
 
 
