@@ -21,7 +21,8 @@ TACOS_OK = 0
 TACOS_E_INVAL, TACOS_E_UNREACHABLE, TACOS_E_OVERFLOW, TACOS_E_NOMEM, TACOS_E_DEVICE = -1, -2, -3, -4, -5
 TACOS_LINK_ORDER_ID, TACOS_LINK_ORDER_COST = 0, 1
 TACOS_MATCH_LINK_CENTRIC, TACOS_MATCH_POSTCONDITION = 0, 1
-TACOS_MAX_CHUNKS = 65536
+TACOS_MAX_CHUNKS = 262144
+TACOS_MAX_CHUNKS_IN_REGISTERS = 65536
 TACOS_NO_CHUNK = 0xFFFFFFFF
 
 XFER_DTYPE = np.dtype([("t_ps", "<u8"), ("src", "<u4"), ("dst", "<u4"),

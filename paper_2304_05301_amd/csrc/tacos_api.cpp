@@ -584,11 +584,13 @@ int device_costs(const tacos_topology_t *topo, uint64_t chunk_bytes, hipStream_t
 
 // Kernel matching mode from the options: 0 link-centric; 1 postcondition-centric, random
 // holder; 2 postcondition-centric, first holder of the cheapest-first list.
-int resolve_match_mode(const tacos_topology_t *topo, int coll, const tacos_options_t *opts, uint32_t *mode)
+int resolve_match_mode(const tacos_topology_t *topo, int coll, const tacos_options_t *opts, uint64_t n_chunks,
+                       uint32_t *mode)
 {
   *mode = 0;
   if (!opts || opts->matching == TACOS_MATCH_LINK_CENTRIC) return TACOS_OK;
   if (opts->matching != TACOS_MATCH_POSTCONDITION) return TACOS_E_INVAL;
+  if (n_chunks > TACOS_MAX_CHUNKS_IN_REGISTERS) return TACOS_E_INVAL;  // streamed rows: link-centric only
   std::vector<uint32_t> deg_in(topo->n_npus, 0), deg_out(topo->n_npus, 0);
   for (uint32_t i = 0; i < topo->n_npus; ++i) {
     deg_out[i] = topo->row_ptr[i + 1] - topo->row_ptr[i];
@@ -622,7 +624,9 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
     return TACOS_E_INVAL;
   // kernel variant: 0 link-centric; 1 postcondition-centric, random holder; 2 first holder
   uint32_t match_mode = 0;
-  rc = resolve_match_mode(topo, (int)coll, opts, &match_mode);
+  rc = resolve_match_mode(topo, (int)coll, opts,
+                          is_rooted((int)coll) ? (uint64_t)chunks_per_npu : (uint64_t)topo->n_npus * chunks_per_npu,
+                          &match_mode);
   if (rc != TACOS_OK) return rc;
   const bool time_kernels = opts && opts->time_kernels;
   const uint32_t launch_mode = opts ? opts->launch_mode : 0;
@@ -707,7 +711,9 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
                opts->matching > TACOS_MATCH_POSTCONDITION))
     return TACOS_E_INVAL;
   uint32_t match_mode = 0;
-  rc = resolve_match_mode(topo, (int)coll, opts, &match_mode);
+  rc = resolve_match_mode(topo, (int)coll, opts,
+                          is_rooted((int)coll) ? (uint64_t)chunks_per_npu : (uint64_t)topo->n_npus * chunks_per_npu,
+                          &match_mode);
   if (rc != TACOS_OK) return rc;
   const uint32_t launch_mode = opts ? opts->launch_mode : 0;
   const uint32_t root = is_rooted((int)coll) ? (opts ? opts->root : 0u) : tacos::kNoRoot;

@@ -708,6 +708,186 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   }
 }
 
+// ---------------------------------------------------------------- rows of more than 8 pieces
+
+// Link-centric matching for ONE destination when a row (more than 65,536 chunks) no longer
+// fits a wavefront's registers: the source row is STREAMED.  Pass 1 reads it piece by piece,
+// forms cand = piece & need on the fly and keeps only the lane's candidate count per piece
+// (one byte each: a lane's share of a piece is 128 bits); the wave prefix sum over the lane
+// totals finds the owning lane, its per-piece counts the owning piece; pass 2 reloads that
+// one 16-byte share and selects the bit.  The need row (NP KiB) is in LDS as before.
+// np <= kMaxStreamedPieces pieces; same results as match_destination.
+constexpr u32 kMaxStreamedPieces = 32;
+
+__device__ __forceinline__ u64 match_destination_streamed(const PassDev &p, u32 d, u32 jb, u32 je, u32 event,
+                                                          u64 t, u32 *__restrict__ sched_row, int lane,
+                                                          uint4 *need_lds)
+{
+  const u32 np = p.NP, nw = 2u * np;
+  Ctl *ctl = p.ctl;
+  u64 my_min = kInf;
+  // clear chunk c in the LDS need row (lane-major layout: lane c/64/nw, word c/64 mod nw)
+  auto need_word = [&](u32 c) {
+    const u32 w = c >> 6;
+    const u32 ln = w / nw;
+    const u32 iw = w - ln * nw;
+    return reinterpret_cast<u32 *>(&need_lds[(iw >> 1) * 64u + ln]) + ((iw & 1u) * 2u + ((c >> 5) & 1u));
+  };
+  bool any_idle = false;
+  for (u32 base = jb; base < je && !any_idle; base += 64) {
+    const u32 j = base + (u32)lane;
+    any_idle = __ballot(j < je && p.carry[j < je ? j : jb] == kNone) != 0ull;
+  }
+  bool need_any = false;
+  if (any_idle) {
+    const uint4 *hp = reinterpret_cast<const uint4 *>(p.held + (u64)d * p.row_words) + lane;
+    u32 acc = 0;
+    for (u32 i = 0; i < np; ++i) {
+      uint4 v = hp[i * 64u];
+      v.x = ~v.x; v.y = ~v.y; v.z = ~v.z; v.w = ~v.w;
+      need_lds[i * 64u + lane] = v;
+      acc |= v.x | v.y | v.z | v.w;
+    }
+    need_any = __ballot(acc != 0u) != 0ull;
+    if (!need_any && p.dest_done && lane == 0) p.dest_done[d] = 1u;
+    for (u32 base = jb; base < je; base += 64) {  // chunks in flight to d are not needed
+      const u32 j = base + (u32)lane;
+      const u32 cr = j < je ? p.carry[j] : kNone;
+      if (cr != kNone) atomicAnd(need_word(cr), ~(1u << (cr & 31u)));
+    }
+  }
+
+  for (u32 base = jb; base < je; base += 64) {
+    const u32 j = base + (u32)lane;
+    const bool valid = j < je;
+    u32 l = 0, s = 0, cr = kNone, r = 0;
+    u64 cs = 0;
+    if (valid) {
+      const uint4 rec = p.in_rec[j];
+      cr = p.carry[j];
+      r = p.rnd[j];
+      l = rec.x; s = rec.y; cs = ((u64)rec.w << 32) | rec.z;
+    }
+    u32 res = kNone;
+    u64 idle = need_any ? __ballot(valid && cr == kNone) : 0ull;
+    while (idle) {
+      const u32 b = (u32)__ffsll((long long)idle) - 1u;
+      idle &= idle - 1ull;
+      const uint4 *sp = reinterpret_cast<const uint4 *>(p.held + (u64)read_lane(s, b) * p.row_words) + lane;
+      // pass 1: candidate count of this lane per piece, packed four to a register
+      u32 pc[kMaxStreamedPieces / 4];
+      u32 cnt = 0;
+#pragma unroll
+      for (u32 g = 0; g < kMaxStreamedPieces / 4; ++g) {
+        pc[g] = 0;
+        if (g * 4u < np) {
+          uint4 v[4];
+#pragma unroll
+          for (u32 q = 0; q < 4; ++q)
+            if (g * 4u + q < np) v[q] = sp[(g * 4u + q) * 64u];
+#pragma unroll
+          for (u32 q = 0; q < 4; ++q)
+            if (g * 4u + q < np) {
+              const uint4 nd = need_lds[(g * 4u + q) * 64u + lane];
+              const u32 c = (u32)__popc(v[q].x & nd.x) + (u32)__popc(v[q].y & nd.y) + (u32)__popc(v[q].z & nd.z) +
+                            (u32)__popc(v[q].w & nd.w);
+              pc[g] |= c << (8u * q);
+              cnt += c;
+            }
+        }
+      }
+      const u32 incl = wave_inclusive_scan(cnt);
+      const u32 pop = read_lane(incl, 63);
+      if (pop == 0) continue;
+      u32 k = read_lane(r, b) % pop;
+      const u32 ln = (u32)__ffsll((long long)__ballot(incl > k)) - 1u;
+      k -= read_lane(incl - cnt, ln);
+      // the owning lane's piece: walk its per-piece counts (wave-uniform)
+      u32 piece = 0;
+      bool found = false;
+#pragma unroll
+      for (u32 g = 0; g < kMaxStreamedPieces / 4; ++g) {
+        const u32 packed = read_lane(pc[g], ln);
+#pragma unroll
+        for (u32 q = 0; q < 4; ++q) {
+          const u32 c = (packed >> (8u * q)) & 0xFFu;
+          if (!found) {
+            if (k < c) { piece = g * 4u + q; found = true; }
+            else k -= c;
+          }
+        }
+      }
+      // pass 2: the owning lane's 16 bytes of that piece again
+      uint4 cv = make_uint4(0, 0, 0, 0);
+      if ((u32)lane == ln) {
+        const uint4 v = sp[piece * 64u];
+        const uint4 nd = need_lds[piece * 64u + lane];
+        cv = make_uint4(v.x & nd.x, v.y & nd.y, v.z & nd.z, v.w & nd.w);
+      }
+      const u32 w0 = read_lane(cv.x, ln), w1 = read_lane(cv.y, ln), w2 = read_lane(cv.z, ln), w3 = read_lane(cv.w, ln);
+      u32 dw = 0, word = w0;
+      const u32 c0 = (u32)__popc(w0), c1 = (u32)__popc(w1), c2 = (u32)__popc(w2);
+      if (k >= c0) { k -= c0; dw = 1; word = w1;
+        if (k >= c1) { k -= c1; dw = 2; word = w2;
+          if (k >= c2) { k -= c2; dw = 3; word = w3; } } }
+      const u32 bit = kth_set_bit_wave(word, 0u, k);
+      // dwords 0,1 of a lane's share are logical word 2*piece, dwords 2,3 word 2*piece+1
+      const u32 chunk = ((ln * nw + 2u * piece + (dw >> 1)) << 6) + (dw & 1u) * 32u + bit;
+      if (lane == 0) *need_word(chunk) &= ~(1u << (chunk & 31u));  // now in flight to d
+      if ((u32)lane == b) res = chunk;
+    }
+    if (valid) {
+      if (sched_row && res != kNone) sched_row[l] = res;  // rows are pre-filled with kNone
+      if (res != kNone) {
+        if (res >= p.C) {
+          ctl->status = kStInternal;
+          ctl->done = 1u;
+        } else if (cs > kInf - 1ull - t) {
+          ctl->status = kStOverflow;
+          ctl->done = 1u;
+        } else {
+          const u64 fa = t + cs;
+          p.carry[j] = res;
+          p.free_at[j] = fa;
+          my_min = fa < my_min ? fa : my_min;
+        }
+      } else if (cr != kNone) {
+        const u64 fa = p.free_at[j];
+        my_min = fa < my_min ? fa : my_min;
+      }
+    }
+  }
+  return my_min;
+}
+
+__global__ __launch_bounds__(256) void match_kernel_streamed(PassDev p, u32 event, u32 *__restrict__ sched_row)
+{
+  extern __shared__ __align__(16) unsigned char streamed_lds[];  // 4 wavefronts x NP KiB of need rows
+  const int lane = threadIdx.x & 63;
+  const u32 per_xcd = gridDim.x >> 3;  // as match_kernel
+  const u32 pos = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  const u32 slot = uniform(pos * 4u + (threadIdx.x >> 6));
+  if (slot >= p.n_slots) return;
+  const uint4 sr = p.slot_rec[slot];
+  const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
+  Ctl *ctl = p.ctl;
+  if (ctl->done) return;
+  const u64 rem = ctl->remaining - wave_sum64(ctl->arrived[lane]);
+  const u64 t = ctl->next_t[event & 1u];
+  if (rem == 0) {
+    if (slot == 0 && lane == 0) { ctl->T = t; ctl->n_events = event; ctl->done = 1u; }
+    return;
+  }
+  uint4 *my_need = reinterpret_cast<uint4 *>(streamed_lds) + (size_t)(threadIdx.x >> 6) * p.NP * 64u;
+  const u64 my_min = match_destination_streamed(p, d, jb, je, event, t, sched_row, lane, my_need);
+  const u64 m = wave_min64(my_min);
+  if (lane == 0 && m != kInf) {
+    u64 *nt = &ctl->next_t[(event + 1u) & 1u];
+    const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (m < cur) atomicMin(nt, m);
+  }
+}
+
 // ---------------------------------------------------------------- small topologies
 
 // One workgroup of 16 wavefronts sweeps many TEN spans without leaving the chip: the
@@ -1020,6 +1200,16 @@ template <int MODE> static void launch_match_mode(const PassDev &p, u32 event, u
 
 void launch_match(const PassDev &p, u32 event, u32 *sched_row, u32 mode, hipStream_t s)
 {
+  if (p.NP > 8) {  // streamed rows (link-centric only; the host rejects the rest)
+    const u32 n_wg = (p.n_slots + 3u) / 4u;
+    const dim3 grid(8u * ((n_wg + 7u) / 8u + (n_wg == 0u)), 1, 1), block(256);
+    const size_t lds = (size_t)4 * p.NP * 1024;
+    // more than 64 KiB of dynamic LDS has to be allowed explicitly
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&match_kernel_streamed),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(match_kernel_streamed, grid, block, lds, s, p, event, sched_row);
+    return;
+  }
   if (mode == 0) launch_match_mode<0>(p, event, sched_row, s);
   else if (mode == 1) launch_match_mode<1>(p, event, sched_row, s);
   else launch_match_mode<2>(p, event, sched_row, s);

@@ -598,3 +598,60 @@ def test_heterogeneous_4096_npu_torus_through_the_per_span_launches(coll, stream
             assert np.array_equal(r.read(0, 100_000), ref.xfers)
             tail = cpu(topo, 1, MiB, coll, 77, keep_first=ref.n_xfers - 100_000, keep_xfers=100_000, n_threads=nt)
             assert np.array_equal(r.read(ref.n_xfers - 100_000, 100_000), tail.xfers)
+
+
+# ---------------------------------------------------------------- more than 65,536 chunks
+
+BIG_ROWS = [
+    ("fc12_c70000_9_pieces", lambda: T.fully_connected(12), 5834, T.ALL_GATHER, {}),
+    ("torus3x3x2_c131076_17_pieces", lambda: T.torus3d(3, 3, 2), 7282, T.ALL_REDUCE, {}),
+    ("hetero_mesh4x4_c262144_32_pieces", lambda: T.grid([4, 4], False, [300_000, 700_000], [5_000, 20_000]), 16384,
+     T.ALL_GATHER, dict(max_events=400)),
+    ("broadcast_c200001_25_pieces", lambda: T.random_regular_out(20, 3, seed=3)[0], 200_001, T.BROADCAST, dict(root=7, max_events=3000)),
+    ("reduce_c65537_9_pieces", lambda: T.mesh2d(4, 3), 65_537, T.REDUCE, dict(root=5)),
+]
+
+
+@pytest.mark.parametrize("name,mk,cpn,coll,kw", BIG_ROWS, ids=[c[0] for c in BIG_ROWS])
+def test_more_than_65536_chunks_streamed_rows(name, mk, cpn, coll, kw, stream):
+    """Rows of 9 to 32 one-KiB pieces: the source rows are streamed instead of kept in
+    registers.  Digest over all transfers, times, spans, the per-span trace (All-Gather),
+    the first and the last 50,000 records."""
+    topo = mk()
+    nt = min(16, oracle.max_threads())
+    ref = cpu(topo, cpn, MiB, coll, 13, keep_first=0, keep_xfers=50_000, n_threads=nt, **kw)
+    with gpu(topo, cpn, MiB, coll, 13, stream, **kw) as r:
+        assert r.collective_time_ps == ref.collective_time_ps and r.num_events == ref.n_events, name
+        assert r.num_xfers == ref.n_xfers and r.digest == ref.digest, name
+        if coll in (T.ALL_GATHER, T.BROADCAST):
+            t, m = r.event_trace(0)
+            assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches)
+            n = min(50_000, ref.n_xfers)
+            assert np.array_equal(r.read(0, n), ref.xfers[:n])
+            tail = cpu(topo, cpn, MiB, coll, 13, keep_first=ref.n_xfers - n, keep_xfers=n, n_threads=nt, **kw)
+            assert np.array_equal(r.read(ref.n_xfers - n, n), tail.xfers)
+
+
+def test_chunk_count_limits(stream):
+    ring = T.ring(4)
+    with pytest.raises(binding.TacosError) as e:   # 262,148 chunks
+        gpu(ring, 65_537, MiB, T.ALL_GATHER, 0, stream)
+    assert e.value.code == binding.TACOS_E_INVAL
+    with pytest.raises(binding.TacosError) as e:   # the postcondition-centric order keeps rows in registers
+        gpu(ring, 16_385, MiB, T.ALL_GATHER, 0, stream, matching=1)
+    assert e.value.code == binding.TACOS_E_INVAL
+    with pytest.raises(binding.TacosError) as e:   # and so does the single-workgroup kernel
+        gpu(ring, 16_385, MiB, T.ALL_GATHER, 0, stream, launch_mode=2)
+    assert e.value.code == binding.TACOS_E_INVAL
+
+
+def test_163840_chunks_on_the_40960_npu_torus_prefix(stream):
+    """Four chunks per NPU on the 32x32x40 torus (163,840 chunks, rows of 20 KiB, 839 MB of
+    rows): the first 10 spans record by record (2.4 M records)."""
+    w = T.workload(5)
+    t = w.topo
+    nt = min(16, oracle.max_threads())
+    ref = oracle.synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B, 4, 256 << 10,
+                            T.ALL_GATHER, 21, max_events=10, n_threads=nt)
+    with gpu(t, 4, 256 << 10, T.ALL_GATHER, 21, stream, max_events=10) as r:
+        assert_same(r, ref, "prefix of 10 spans")
