@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--max-chunks", type=int, default=16000,
                     help="upper limit of N * chunks_per_npu (rows of up to ceil(max/8192) one-KiB pieces)")
+    ap.add_argument("--min-chunks", type=int, default=0,
+                    help="lower limit of the chunk count (above 65536: the streamed-row kernel)")
     args = ap.parse_args()
     import torch
     torch.cuda.set_device(0)
@@ -56,13 +58,14 @@ def main():
     rng = np.random.default_rng(args.seed)
     for case in range(args.cases):
         topo = draw_topology(rng)
-        max_cpn = max(1, min(700, args.max_chunks // topo.n_npus))
-        cpn = int(rng.integers(1, max_cpn + 1))
+        max_cpn = max(1, min(700 if args.min_chunks == 0 else 1 << 30, args.max_chunks // topo.n_npus))
+        min_cpn = min(max_cpn, -(-args.min_chunks // topo.n_npus) if args.min_chunks else 1)
+        cpn = int(rng.integers(min_cpn, max_cpn + 1))
         cb = int(rng.integers(1, 1 << 22))
         coll = int(rng.integers(0, 5))  # 3, 4: Broadcast / Reduce with a random root
         root = int(rng.integers(0, topo.n_npus))
         if coll >= 3:
-            cpn = int(rng.integers(1, max(2, args.max_chunks // 2)))
+            cpn = int(rng.integers(max(1, args.min_chunks), max(2, args.max_chunks)))
         seed = int(rng.integers(0, 1 << 62))
         matching = int(rng.integers(0, 2))
         link_order = int(rng.integers(0, 2))
@@ -70,6 +73,8 @@ def main():
         n_chunks = cpn if coll >= 3 else cpn * topo.n_npus
         if mode == 2 and n_chunks > 16384:  # the single-workgroup kernel takes rows of up to two pieces
             mode = 0
+        if n_chunks > 65536:  # streamed rows: link-centric matching only
+            matching = 0
         deg_in = np.bincount(topo.col_idx, minlength=topo.n_npus).max()
         deg_out = np.diff(topo.row_ptr).max()
         if matching == 1 and max(deg_in, deg_out) > 64:
