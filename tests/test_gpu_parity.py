@@ -609,6 +609,7 @@ BIG_ROWS = [
      T.ALL_GATHER, dict(max_events=400)),
     ("broadcast_c200001_25_pieces", lambda: T.random_regular_out(20, 3, seed=3)[0], 200_001, T.BROADCAST, dict(root=7, max_events=3000)),
     ("reduce_c65537_9_pieces", lambda: T.mesh2d(4, 3), 65_537, T.REDUCE, dict(root=5)),
+    ("fc70_indeg69_c70000_9_pieces", lambda: T.fully_connected(70), 1000, T.ALL_GATHER, dict(link_order=1)),
 ]
 
 
