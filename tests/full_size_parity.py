@@ -53,11 +53,16 @@ def main():
     ap.add_argument("--workload", type=int, default=5)
     ap.add_argument("--collective", choices=["ag", "rs", "ar"], default=None,
                     help="override the workload's collective (rs/ar: digest, times and counts only)")
+    ap.add_argument("--cpn", type=int, default=0,
+                    help="override chunks per NPU (the collective size stays: chunk bytes are divided)")
     ap.add_argument("--matching", type=int, default=0, help="0 link-centric, 1 postcondition-centric")
     ap.add_argument("--link-order", type=int, default=0, help="0 by link id, 1 cheapest first")
     args = ap.parse_args()
     opt = dict(matching=args.matching, link_order=args.link_order)
     w = T.workload(args.workload)
+    if args.cpn:
+        w = T.Workload(f"{w.name}_cpn{args.cpn}", w.topo, args.cpn,
+                       w.chunk_bytes * w.chunks_per_npu // args.cpn, w.collective, w.seed)
     if args.collective:
         coll = {"ag": T.ALL_GATHER, "rs": T.REDUCE_SCATTER, "ar": T.ALL_REDUCE}[args.collective]
         w = T.Workload(w.name + "_" + args.collective, w.topo, w.chunks_per_npu, w.chunk_bytes, coll, w.seed)
