@@ -774,24 +774,27 @@ __device__ __forceinline__ u64 match_destination_streamed(const PassDev &p, u32 
       const u32 b = (u32)__ffsll((long long)idle) - 1u;
       idle &= idle - 1ull;
       const uint4 *sp = reinterpret_cast<const uint4 *>(p.held + (u64)read_lane(s, b) * p.row_words) + lane;
-      // pass 1: candidate count of this lane per piece, packed four to a register
+      // pass 1: candidate count of this lane per piece, packed four to a register; eight
+      // pieces of the row are asked for at a time (few wavefronts fit beside the need rows,
+      // so each keeps many loads in flight)
       u32 pc[kMaxStreamedPieces / 4];
       u32 cnt = 0;
 #pragma unroll
-      for (u32 g = 0; g < kMaxStreamedPieces / 4; ++g) {
-        pc[g] = 0;
-        if (g * 4u < np) {
-          uint4 v[4];
+      for (u32 g = 0; g < kMaxStreamedPieces / 4; ++g) pc[g] = 0;
 #pragma unroll
-          for (u32 q = 0; q < 4; ++q)
-            if (g * 4u + q < np) v[q] = sp[(g * 4u + q) * 64u];
+      for (u32 h = 0; h < kMaxStreamedPieces / 8; ++h) {
+        if (h * 8u < np) {
+          uint4 v[8];
 #pragma unroll
-          for (u32 q = 0; q < 4; ++q)
-            if (g * 4u + q < np) {
-              const uint4 nd = need_lds[(g * 4u + q) * 64u + lane];
+          for (u32 q = 0; q < 8; ++q)
+            if (h * 8u + q < np) v[q] = sp[(h * 8u + q) * 64u];
+#pragma unroll
+          for (u32 q = 0; q < 8; ++q)
+            if (h * 8u + q < np) {
+              const uint4 nd = need_lds[(h * 8u + q) * 64u + lane];
               const u32 c = (u32)__popc(v[q].x & nd.x) + (u32)__popc(v[q].y & nd.y) + (u32)__popc(v[q].z & nd.z) +
                             (u32)__popc(v[q].w & nd.w);
-              pc[g] |= c << (8u * q);
+              pc[h * 2u + (q >> 2)] |= c << (8u * (q & 3u));
               cnt += c;
             }
         }
