@@ -489,8 +489,9 @@ void finish_pass(Pass &pass, uint64_t t_off, uint64_t *digest, hipStream_t strea
   pass.t_off = t_off;
   pass.row_time.assign(pass.n_rows, 0);
   pass.row_count.assign(pass.n_rows, 0);
-  DevBuf d_digest(8);
-  HIP_TRY(hipMemsetAsync(d_digest.p, 0, 8, stream));
+  const size_t digest_bytes = (size_t)tacos::kDigestSlots * 16 * 8;  // partial sums, one per cache line
+  DevBuf d_digest(digest_bytes);
+  HIP_TRY(hipMemsetAsync(d_digest.p, 0, digest_bytes, stream));
   const uint64_t t_base = pass.reversed ? pass.T : t_off;
   for (size_t k = 0; k < pass.segs.size(); ++k) {
     const uint64_t first = (uint64_t)k * pass.rows_per_seg;
@@ -508,10 +509,10 @@ void finish_pass(Pass &pass, uint64_t t_off, uint64_t *digest, hipStream_t strea
                            hipMemcpyDeviceToHost, stream));
     HIP_TRY(hipStreamSynchronize(stream));
   }
-  uint64_t dg = 0;
-  HIP_TRY(hipMemcpyAsync(&dg, d_digest.p, 8, hipMemcpyDeviceToHost, stream));
+  std::vector<uint64_t> partial((size_t)tacos::kDigestSlots * 16);
+  HIP_TRY(hipMemcpyAsync(partial.data(), d_digest.p, digest_bytes, hipMemcpyDeviceToHost, stream));
   HIP_TRY(hipStreamSynchronize(stream));
-  *digest += dg;
+  for (uint32_t k = 0; k < tacos::kDigestSlots; ++k) *digest += partial[(size_t)k * 16];
   pass.canon_base.assign(pass.n_rows + 1, 0);
   for (uint64_t k = 0; k < pass.n_rows; ++k)
     pass.canon_base[k + 1] = pass.canon_base[k] + pass.row_count[pass.event_of(k)];

@@ -111,7 +111,9 @@ hipError_t launch_small_sweep_batch(const SmallJob *jobs, uint32_t n_jobs, const
                                     uint32_t first_event, uint32_t n_events, uint32_t mode, hipStream_t s);
 // LDS the small-topology kernel needs, (size_t)-1 if the shape is not supported
 size_t small_sweep_lds_bytes(uint32_t N, uint32_t L, uint32_t NP);
-// epilogue: per-row match counts and the schedule digest of a block of rows
+// epilogue: per-row match counts and the schedule digest of a block of rows; `digest` points at
+// kDigestSlots partial sums, one every 16 words (128 bytes), which the caller adds up
+constexpr uint32_t kDigestSlots = 256;
 void launch_row_stats(const uint32_t *rows, uint32_t n_rows, uint32_t L,
                       const unsigned long long *row_time, unsigned long long t_base,
                       uint32_t reversed, uint32_t *row_count, unsigned long long *digest,

@@ -1110,7 +1110,8 @@ __device__ __forceinline__ u64 mix_record(u64 t, u32 link, u32 chunk)
   return h;
 }
 
-// grid = n_rows * ceil(L / 2048) blocks; every block covers 2048 links of one schedule row
+// grid = n_rows * ceil(L / 2048) blocks; every block covers 2048 links of one schedule row;
+// digest: kDigestSlots partial sums, 128 bytes apart, to be added up by the caller
 __global__ __launch_bounds__(256) void row_stats_kernel(const u32 *__restrict__ rows, u32 L,
                                                         const u64 *__restrict__ row_time, u64 t_base,
                                                         u32 reversed, u32 blocks_per_row,
@@ -1140,9 +1141,18 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const u32 *__restrict__ 
     const u32 hi = (u32)__shfl_xor((int)(u32)(dg >> 32), off, 64);
     dg += ((u64)hi << 32) | lo;
   }
-  if ((threadIdx.x & 63u) == 0 && n) {
-    atomicAdd(&row_count[row], n);
-    atomicAdd(digest, dg);
+  // one atomic per workgroup; the digest goes to one of kDigestSlots partial sums, each on
+  // a cache line of its own (a single address would serialise every workgroup of the grid)
+  __shared__ u32 s_n[4];
+  __shared__ u64 s_dg[4];
+  if ((threadIdx.x & 63u) == 0) { s_n[threadIdx.x >> 6] = n; s_dg[threadIdx.x >> 6] = dg; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const u32 nb = s_n[0] + s_n[1] + s_n[2] + s_n[3];
+    if (nb) {
+      atomicAdd(&row_count[row], nb);
+      atomicAdd(&digest[(blockIdx.x % kDigestSlots) * 16u], s_dg[0] + s_dg[1] + s_dg[2] + s_dg[3]);
+    }
   }
 }
 
