@@ -33,7 +33,12 @@
  * = N-1 steps with a unique schedule; fully connected = 1 step; bidirectional ring
  * = ceil((N-1)/2) steps; ingress and diameter lower bounds; brute-force optimal
  * step counts for all strongly connected digraphs with N <= 4; an independent
- * schedule checker (validity, one chunk per link, maximality); RS/AR structure.
+ * schedule checker (validity, one chunk per link, maximality); RS/AR structure;
+ * exact replays of two-NPU cases from the rule alone (equal and unequal link costs,
+ * the latter with a span that matches nothing; parallel links for the postcondition-
+ * centric draw); collective times and span counts of an independent implementation
+ * for the 8x8-mesh All-Gather and the heterogeneous 4x4x8-torus All-Reduce.  Every
+ * planted mistake of tests/test_oracle_mutants.py is noticed by a named pin.
  * The full-size 40,960-NPU result has no value pin of its own: parity unpinned
  * except by those invariants and bounds.
  */

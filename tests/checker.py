@@ -356,6 +356,70 @@ def two_npu_all_gather(cpn, seed, phase=0):
     return out
 
 
+def two_npu_hetero_all_gather(cpn, seed, cost0, cost1):
+    """Exact expected forward pass on two NPUs whose links 0 -> 1 (id 0, cost0) and 1 -> 0
+    (id 1, cost1) differ in cost, event by event: spans sit on the arrival times, a span in
+    which no idle link has anything left to send still counts in the span index (it is the
+    second counter word of every later draw), and link l sends the
+    (Philox(l, span, 0, 0; seed)[0] mod p)-th smallest of the p chunks its source owns and
+    has not sent yet.  Returns ([(t, link, chunk)], collective time, spans, matches per span)."""
+    key = (seed & 0xFFFFFFFF, seed >> 32)
+    cost = (cost0, cost1)
+    left = {0: list(range(0, cpn)), 1: list(range(cpn, 2 * cpn))}
+    busy_until = {0: None, 1: None}
+    t, span, delivered, out, per_span = 0, 0, 0, [], []
+    while True:
+        for link in (0, 1):
+            if busy_until[link] == t:
+                busy_until[link] = None
+                delivered += 1
+        if delivered == 2 * cpn:
+            return out, t, span, per_span
+        n = 0
+        for link in (0, 1):
+            if busy_until[link] is None and left[link]:
+                r = philox4x32_10((link, span, 0, 0), key)[0]
+                c = left[link][r % len(left[link])]
+                left[link].remove(c)
+                out.append((t, link, c))
+                busy_until[link] = t + cost[link]
+                n += 1
+        per_span.append(n)
+        t = min(v for v in busy_until.values() if v is not None)
+        span += 1
+
+
+def two_npu_parallel_links_pairs(cpn, n_par, seed, phase=0):
+    """Exact expected forward pass of the postcondition-centric matching on two NPUs with
+    unit-cost links: 0 -> 1 once (link id 0) and 1 -> 0 `n_par` times in parallel (ids
+    1 .. n_par).  Every source holds all of its own chunks from the start, so at step s of
+    destination d in a span the servable chunks are exactly the ones of the other NPU that d
+    has not been sent yet, and every still-free link into d is a holder:
+      (r0, r1) = words 0, 1 of Philox(d, span, phase + 2, s; seed);
+      chunk = the (r0 mod p)-th smallest servable one; link = the (r1 mod n)-th free link
+      into d in ascending link id.
+    Returns [(t, link, chunk)] sorted by (t, link)."""
+    key = (seed & 0xFFFFFFFF, seed >> 32)
+    into = {0: list(range(1, n_par + 1)), 1: [0]}
+    left = {0: list(range(cpn, 2 * cpn)), 1: list(range(0, cpn))}  # by destination
+    out = []
+    span = 0
+    while left[0] or left[1]:
+        for d in (0, 1):
+            free = list(into[d])
+            step = 0
+            while free and left[d]:
+                r = philox4x32_10((d, span, phase + 2, step), key)
+                c = left[d][r[0] % len(left[d])]
+                link = free[r[1] % len(free)]
+                left[d].remove(c)
+                free.remove(link)
+                out.append((span, link, c))
+                step += 1
+        span += 1
+    return sorted(out)
+
+
 def alg1_postcondition_centric(n_npus, link_src, link_dst, cost, cpn, seed, phase=0, cheapest_first=False):
     """Second, set-based implementation (python, small inputs) of the postcondition-
     centric matching: per destination, repeatedly draw a servable missing chunk with

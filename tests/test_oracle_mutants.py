@@ -1,9 +1,15 @@
 """Are the oracle's pins sharp?  Plant plausible mistakes in COPIES of the oracle source
-(textual patches, built to temporary libraries, CPU only) and check that for each one
-at least one pin that does not depend on the oracle itself fails: published constants,
-closed forms, the independent replaying checker, brute force.  The real oracle is never
-modified."""
+(textual patches, built to temporary libraries, CPU only) and check that each one is
+noticed by a NAMED pin that does not depend on the oracle itself: published constants,
+closed forms, exact replays of two-NPU cases from the rule, values of an independent
+implementation, the replaying checker, brute force.  The real oracle is never modified.
+
+Every pin is an assertion about results; a pin never "fails" by crashing or by running
+for ever: the mutated oracle is run with a cap on the number of spans, a non-zero return
+code is an assertion failure, and a child process that dies or times out is a test error.
+"""
 import ctypes
+import multiprocessing as mp
 import os
 import subprocess
 import tempfile
@@ -17,58 +23,130 @@ from paper_2304_05301_amd import topologies as T
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "tacos_oracle.c")
 MiB = 1 << 20
+SPAN_CAP = 20_000  # no pin's input needs more spans; a mutant that stalls stops here
 
+# name: (list of (text to replace, replacement), pins of which at least one must notice)
 MUTANTS = {
-    # name: (text to replace, replacement)
-    "philox_wrong_multiplier": ("0xD2511F53u * c0", "0xD2511F57u * c0"),
-    "philox_nine_rounds": ("round < 10", "round < 9"),
-    "philox_swapped_words": ("c0 = n0; c1 = n1; c2 = n2; c3 = n3;", "c0 = n2; c1 = n1; c2 = n0; c3 = n3;"),
-    "cost_drops_alpha": ("unsigned __int128 ps = fs / 1000u + alpha_ps;", "unsigned __int128 ps = fs / 1000u;"),
-    "cost_truncates": ("* chunk_bytes + 500u;", "* chunk_bytes;"),
-    "source_need_not_hold": ("p += (uint64_t)__builtin_popcountll(hs[w] & ~hd[w] & ~fd[w]);",
-                             "p += (uint64_t)__builtin_popcountll(~hd[w] & ~fd[w]);"),
-    "inflight_ignored": ("uint64_t cand = hs[w] & ~hd[w] & ~fd[w];", "uint64_t cand = hs[w] & ~hd[w];"),
-    "arrival_not_applied_before_matching": ("if (carry[l] != ORC_NONE && free_at[l] == t) {",
-                                            "if (carry[l] != ORC_NONE && free_at[l] < t) {"),
-    "busy_links_reused": ("if (carry[l] != ORC_NONE) continue;            /* link busy */", ""),
-    "kth_off_by_one": ("while (k--) w &= w - 1;", "if (k) k--; while (k--) w &= w - 1;"),
-    "next_event_is_latest": ("if (carry[l] != ORC_NONE && free_at[l] < tn) tn = free_at[l];",
-                             "if (carry[l] != ORC_NONE && (tn == ORC_INF || free_at[l] > tn)) tn = free_at[l];"),
-    "rs_not_time_reversed": ("x.t_ps = T - r->t - cost[r->link];", "x.t_ps = r->t;"),
-    "rs_direction_not_reversed": ("rc = ag_pass(n_npus, L, col_idx, src, cost, chunks_per_npu, seed, 1u, max_events,",
-                                  "rc = ag_pass(n_npus, L, src, col_idx, cost, chunks_per_npu, seed, 1u, max_events,"),
-    "wrong_owner": ("uint64_t c = (uint64_t)i * cpn + j;", "uint64_t c = (uint64_t)j * N + i;"),
-    "priority_sorts_descending": ("cost[in_link[k - 1]] > cost[l]", "cost[in_link[k - 1]] < cost[l]"),
-    "counter_link_event_swapped": ("uint32_t ctr[4] = { link, event, phase, 0u };", "uint32_t ctr[4] = { event, link, phase, 0u };"),
-    "phase_ignored": ("uint32_t ctr[4] = { link, event, phase, 0u };", "uint32_t ctr[4] = { link, event, 0u, 0u };"),
-    "seed_halves_swapped": ("uint32_t key[2] = { (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32) };",
-                            "uint32_t key[2] = { (uint32_t)(seed >> 32), (uint32_t)(seed & 0xFFFFFFFFu) };"),
-    "uses_second_philox_word": ("return out[0];", "return out[1];"),
-    "kth_from_the_top": ("uint32_t k = draw(seed, l, (uint32_t)event, phase) % (uint32_t)p;",
-                         "uint32_t k = (uint32_t)p - 1u - draw(seed, l, (uint32_t)event, phase) % (uint32_t)p;"),
-    "ar_halves_overlap": ("    t_off = T;\n", "    t_off = 0;\n"),
-    "broadcast_root_ignored": ("held[(size_t)root * W + (j >> 6)] |= 1ull << (j & 63);",
-                               "held[(size_t)0 * W + (j >> 6)] |= 1ull << (j & 63);"),
-    "broadcast_counts_all_gather_chunks": ("(root == ORC_NONE) ? (uint64_t)N * cpn : (uint64_t)cpn;",
-                                           "(uint64_t)N * cpn;"),
-    "reduce_not_reversed": ("const int has_rev = collective == ORC_REDUCE_SCATTER || collective == ORC_ALL_REDUCE || collective == ORC_REDUCE;",
-                            "const int has_rev = collective == ORC_REDUCE_SCATTER || collective == ORC_ALL_REDUCE;"),
+    "philox_wrong_multiplier": ([("0xD2511F53u * c0", "0xD2511F57u * c0")], {"philox_known_answers"}),
+    "philox_nine_rounds": ([("round < 10", "round < 9")], {"philox_known_answers"}),
+    "philox_swapped_words": ([("c0 = n0; c1 = n1; c2 = n2; c3 = n3;", "c0 = n2; c1 = n1; c2 = n0; c3 = n3;")],
+                             {"philox_known_answers"}),
+    "cost_drops_alpha": ([("unsigned __int128 ps = fs / 1000u + alpha_ps;", "unsigned __int128 ps = fs / 1000u;")],
+                         {"alpha_beta_cost"}),
+    "cost_truncates": ([("* chunk_bytes + 500u;", "* chunk_bytes;")], {"alpha_beta_cost"}),
+    "source_need_not_hold": ([("p += (uint64_t)__builtin_popcountll(hs[w] & ~hd[w] & ~fd[w]);",
+                               "p += (uint64_t)__builtin_popcountll(~hd[w] & ~fd[w]);")],
+                             {"one_way_ring_closed_form", "two_npu_replay_forward"}),
+    "inflight_ignored": ([("uint64_t cand = hs[w] & ~hd[w] & ~fd[w];", "uint64_t cand = hs[w] & ~hd[w];")],
+                         {"checker_heterogeneous_all_gather"}),
+    "arrival_not_applied_before_matching": ([("if (carry[l] != ORC_NONE && free_at[l] == t) {",
+                                              "if (carry[l] != ORC_NONE && free_at[l] < t) {")],
+                                            {"one_way_ring_closed_form"}),
+    "busy_links_reused": ([("if (carry[l] != ORC_NONE) continue;            /* link busy */", "")],
+                          {"checker_heterogeneous_all_gather", "two_npu_unequal_costs_replay"}),
+    "kth_off_by_one": ([("while (k--) w &= w - 1;", "if (k) k--; while (k--) w &= w - 1;")],
+                       {"selection_rule_published_vector"}),
+    "next_event_is_latest": ([("if (carry[l] != ORC_NONE && free_at[l] < tn) tn = free_at[l];",
+                               "if (carry[l] != ORC_NONE && (tn == ORC_INF || free_at[l] > tn)) tn = free_at[l];")],
+                             {"two_npu_unequal_costs_replay", "checker_heterogeneous_all_gather"}),
+    "rs_not_time_reversed": ([("x.t_ps = T - r->t - cost[r->link];", "x.t_ps = r->t;")],
+                             {"two_npu_replay_reversed", "checker_reduce_scatter"}),
+    "rs_direction_not_reversed": ([("rc = ag_pass(n_npus, L, col_idx, src, cost, chunks_per_npu, seed, 1u, max_events,",
+                                    "rc = ag_pass(n_npus, L, src, col_idx, cost, chunks_per_npu, seed, 1u, max_events,")],
+                                  {"two_npu_replay_reversed", "checker_reduce_scatter"}),
+    "wrong_owner": ([("uint64_t c = (uint64_t)i * cpn + j;", "uint64_t c = (uint64_t)j * N + i;")],
+                    {"two_npu_replay_forward", "checker_heterogeneous_all_gather"}),
+    "priority_sorts_descending": ([("cost[in_link[k - 1]] > cost[l]", "cost[in_link[k - 1]] < cost[l]")],
+                                  {"cheapest_link_first_closed_form"}),
+    "counter_link_event_swapped": ([("uint32_t ctr[4] = { link, event, phase, 0u };",
+                                     "uint32_t ctr[4] = { event, link, phase, 0u };")],
+                                   {"two_npu_replay_forward"}),
+    "phase_ignored": ([("uint32_t ctr[4] = { link, event, phase, 0u };", "uint32_t ctr[4] = { link, event, 0u, 0u };")],
+                      {"two_npu_replay_reversed"}),
+    "seed_halves_swapped": ([("static uint32_t draw(uint64_t seed, uint32_t link, uint32_t event, uint32_t phase)\n{\n"
+                              "  uint32_t ctr[4] = { link, event, phase, 0u };\n"
+                              "  uint32_t key[2] = { (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32) };",
+                              "static uint32_t draw(uint64_t seed, uint32_t link, uint32_t event, uint32_t phase)\n{\n"
+                              "  uint32_t ctr[4] = { link, event, phase, 0u };\n"
+                              "  uint32_t key[2] = { (uint32_t)(seed >> 32), (uint32_t)(seed & 0xFFFFFFFFu) };")],
+                            {"two_npu_replay_forward"}),
+    "uses_second_philox_word": ([("return out[0];", "return out[1];")], {"selection_rule_published_vector"}),
+    "kth_from_the_top": ([("uint32_t k = draw(seed, l, (uint32_t)event, phase) % (uint32_t)p;",
+                           "uint32_t k = (uint32_t)p - 1u - draw(seed, l, (uint32_t)event, phase) % (uint32_t)p;")],
+                         {"selection_rule_published_vector"}),
+    "ar_halves_overlap": ([("    t_off = T;\n", "    t_off = 0;\n")], {"all_reduce_is_rs_then_ag"}),
+    "broadcast_root_ignored": ([("held[(size_t)root * W + (j >> 6)] |= 1ull << (j & 63);",
+                                 "held[(size_t)0 * W + (j >> 6)] |= 1ull << (j & 63);")],
+                               {"broadcast_closed_forms"}),
+    "broadcast_counts_all_gather_chunks": ([("(root == ORC_NONE) ? (uint64_t)N * cpn : (uint64_t)cpn;",
+                                             "(uint64_t)N * cpn;")], {"broadcast_closed_forms"}),
+    "reduce_runs_as_broadcast": ([("const int has_rev = collective == ORC_REDUCE_SCATTER || collective == ORC_ALL_REDUCE || collective == ORC_REDUCE;",
+                                   "const int has_rev = collective == ORC_REDUCE_SCATTER || collective == ORC_ALL_REDUCE;"),
+                                  ("const int has_fwd = collective == ORC_ALL_GATHER || collective == ORC_ALL_REDUCE || collective == ORC_BROADCAST;",
+                                   "const int has_fwd = collective == ORC_ALL_GATHER || collective == ORC_ALL_REDUCE || collective == ORC_BROADCAST || collective == ORC_REDUCE;")],
+                                 {"checker_reduce"}),
+    # the span index (second counter word of every draw) counts spans that match nothing
+    "span_index_skips_empty_spans": ([("    t = tn;\n    event++;\n", "    t = tn;\n    if (matches) event++;\n")],
+                                     {"two_npu_unequal_costs_replay", "independent_values_configs_2_and_3"}),
+    # ---- the postcondition-centric order (Algorithm 1 as printed): its own draw and walk
+    "pairs_words_swapped": ([("  *r_chunk = out[0];\n  *r_link = out[1];", "  *r_chunk = out[1];\n  *r_link = out[0];")],
+                            {"pairs_parallel_links_replay"}),
+    "pairs_step_not_in_counter": ([("uint32_t ctr[4] = { d, event, phase + 2u, i };",
+                                    "uint32_t ctr[4] = { d, event, phase + 2u, 0u };")],
+                                  {"pairs_parallel_links_replay"}),
+    "pairs_phase_offset_dropped": ([("uint32_t ctr[4] = { d, event, phase + 2u, i };",
+                                     "uint32_t ctr[4] = { d, event, phase, i };")],
+                                   {"pairs_parallel_links_replay"}),
+    "pairs_destination_and_span_swapped": ([("uint32_t ctr[4] = { d, event, phase + 2u, i };",
+                                             "uint32_t ctr[4] = { event, d, phase + 2u, i };")],
+                                           {"pairs_parallel_links_replay"}),
+    "pairs_seed_halves_swapped": ([("  uint32_t ctr[4] = { d, event, phase + 2u, i };\n"
+                                    "  uint32_t key[2] = { (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32) };",
+                                    "  uint32_t ctr[4] = { d, event, phase + 2u, i };\n"
+                                    "  uint32_t key[2] = { (uint32_t)(seed >> 32), (uint32_t)(seed & 0xFFFFFFFFu) };")],
+                                  {"pairs_parallel_links_replay"}),
+    "pairs_holder_from_the_wrong_end": ([("uint32_t pick = (link_order == 1) ? 0u : r_link % n_hold;",
+                                          "uint32_t pick = (link_order == 1) ? 0u : n_hold - 1u - r_link % n_hold;")],
+                                        {"pairs_parallel_links_replay"}),
+    "pairs_chunk_from_the_top": ([("uint32_t k = r_chunk % (uint32_t)p, c = ORC_NONE;",
+                                   "uint32_t k = (uint32_t)p - 1u - r_chunk % (uint32_t)p, c = ORC_NONE;")],
+                                 {"pairs_parallel_links_replay"}),
+    "pairs_cheapest_holder_not_taken": ([("uint32_t pick = (link_order == 1) ? 0u : r_link % n_hold;",
+                                          "uint32_t pick = r_link % n_hold;")],
+                                        {"pairs_cheapest_holder_closed_form"}),
+    "pairs_holder_need_not_hold": ([("          uint32_t n_hold = 0;\n"
+                                     "          for (uint32_t j = in_ptr[d]; j < in_ptr[d + 1]; ++j) {\n"
+                                     "            uint32_t l = in_link[j];\n"
+                                     "            if (carry[l] == ORC_NONE && fresh[l] == ORC_NONE &&\n"
+                                     "                (held[(size_t)psrc[l] * W + (c >> 6)] >> (c & 63) & 1ull)) n_hold++;",
+                                     "          uint32_t n_hold = 0;\n"
+                                     "          for (uint32_t j = in_ptr[d]; j < in_ptr[d + 1]; ++j) {\n"
+                                     "            uint32_t l = in_link[j];\n"
+                                     "            if (carry[l] == ORC_NONE && fresh[l] == ORC_NONE) n_hold++;"),
+                                    ("            if (carry[l] == ORC_NONE && fresh[l] == ORC_NONE &&\n"
+                                     "                (held[(size_t)psrc[l] * W + (c >> 6)] >> (c & 63) & 1ull)) {\n"
+                                     "              if (pick == 0) {",
+                                     "            if (carry[l] == ORC_NONE && fresh[l] == ORC_NONE) {\n"
+                                     "              if (pick == 0) {")],
+                                   {"pairs_checker_valid_and_maximal"}),
+    "pairs_in_flight_chunk_drawn_again": ([("            uint64_t serv = any & ~hd[w] & ~fd[w];",
+                                            "            uint64_t serv = any & ~hd[w];"),
+                                           ("            p += (uint64_t)__builtin_popcountll(any & ~hd[w] & ~fd[w]);",
+                                            "            p += (uint64_t)__builtin_popcountll(any & ~hd[w]);")],
+                                          {"pairs_parallel_links_replay", "pairs_checker_valid_and_maximal"}),
 }
-
-
-class _Res(ctypes.Structure):
-    _fields_ = oracle._CResult._fields_
 
 
 def _build(name):
     text = open(SRC).read()
-    old, new = MUTANTS[name]
-    assert text.count(old) == 1, f"mutant {name}: pattern occurs {text.count(old)} times"
+    for old, new in MUTANTS[name][0]:
+        assert text.count(old) == 1, f"mutant {name}: pattern occurs {text.count(old)} times: {old[:60]!r}"
+        text = text.replace(old, new)
     d = tempfile.mkdtemp(prefix="orc_mut_")
     c = os.path.join(d, "m.c")
     so = os.path.join(d, "m.so")
     with open(c, "w") as f:
-        f.write(text.replace(old, new))
+        f.write(text)
     subprocess.check_call(["gcc", "-O1", "-mpopcnt", "-fopenmp", "-shared", "-fPIC", "-w", "-o", so, c])
     lib = ctypes.CDLL(so)
     lib.orc_synthesize.restype = ctypes.c_int
@@ -81,129 +159,272 @@ def _build(name):
 
 
 def _run(lib, topo, cpn=1, cb=MiB, coll=0, seed=0, link_order=0, matching=0, root=0):
+    """(collective time, spans, transfers, per-pass times, per-pass spans) of a run that is
+    stopped after SPAN_CAP spans per pass.  A non-zero return code fails as an assertion."""
     res = ctypes.POINTER(oracle._CResult)()
     rp = np.ascontiguousarray(topo.row_ptr, dtype=np.uint32)
     ci = np.ascontiguousarray(topo.col_idx, dtype=np.uint32)
     al = np.ascontiguousarray(topo.alpha_ps, dtype=np.uint64)
     be = np.ascontiguousarray(topo.beta_fs_per_B, dtype=np.uint64)
     rc = lib.orc_synthesize(topo.n_npus, rp.ctypes.data, ci.ctypes.data, al.ctypes.data, be.ctypes.data,
-                            cpn, cb, coll, seed, 0, 0, (1 << 64) - 1, 1, link_order, matching, root, ctypes.byref(res))
-    if rc != 0:
-        raise RuntimeError(f"rc={rc}")
+                            cpn, cb, coll, seed, SPAN_CAP, 0, (1 << 64) - 1, 1, link_order, matching, root,
+                            ctypes.byref(res))
+    assert rc == 0, f"the oracle returned error {rc}"
     r = res.contents
     n = int(r.n_stored)
     xf = np.frombuffer((ctypes.c_char * (n * 24)).from_address(r.xfers), dtype=oracle.XFER_DTYPE).copy() \
         if n else np.zeros(0, dtype=oracle.XFER_DTYPE)
-    out = (int(r.collective_time_ps), int(r.n_events), xf)
+    out = (int(r.collective_time_ps), int(r.n_events), xf,
+           (int(r.pass_time_ps[0]), int(r.pass_time_ps[1])), (int(r.pass_events[0]), int(r.pass_events[1])))
     lib.orc_result_free(res)
     return out
 
 
-def _pins(lib):
-    """A subset of the pins of test_oracle_pins.py, run against `lib`.  Raises on the
-    first pin that fails."""
-    # Philox known answers
+def _tlc(xf):
+    return [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in xf]
+
+
+TWO = T.from_edge_list(2, [(0, 1, 1, 0), (1, 0, 1, 0)])
+HET = T.grid([3, 2, 3], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000])
+
+
+# ------------------------------------------------------------------ the pins, by name
+
+def pin_philox_known_answers(lib):
     c = np.array([0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344], dtype=np.uint32)
     k = np.array([0xa4093822, 0x299f31d0], dtype=np.uint32)
     o = np.zeros(4, dtype=np.uint32)
     lib.orc_philox4x32_10(c.ctypes.data, k.ctypes.data, o.ctypes.data)
     assert [int(x) for x in o] == [0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1]
-    # the selection rule against the published Philox vector (counter 0, key 0)
-    two = T.from_edge_list(2, [(0, 1, 1, 0), (1, 0, 1, 0)])
+
+
+def pin_selection_rule_published_vector(lib):
+    # link 0, span 0, forward pass, seed 0 draws the published vector of counter 0, key 0
     for cpn in (7, 200):
-        xf = _run(lib, two, cpn=cpn, cb=1, seed=0)[2]
+        xf = _run(lib, TWO, cpn=cpn, cb=1, seed=0)[2]
         assert (int(xf[0]["link"]), int(xf[0]["chunk"])) == (0, 0x6627E8D5 % cpn)
-    # exact replay of the 2-NPU schedule: counter/key layout, forward and reversed phase
+
+
+def pin_two_npu_replay_forward(lib):
     want = checker.two_npu_all_gather(9, 0x0123456789ABCDEF, phase=0)
-    xf = _run(lib, two, cpn=9, cb=1, seed=0x0123456789ABCDEF)[2]
-    assert [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in xf] == want
-    want1 = checker.two_npu_all_gather(9, 5, phase=1)  # reversed pass: links swap their sources
-    xf = _run(lib, two, cpn=9, cb=1, coll=1, seed=5)[2]
-    got1 = sorted((9 - int(x["t_ps"]) - 1, int(x["link"]), int(x["chunk"])) for x in xf)
-    assert got1 == sorted((t, l, (c + 9) % 18) for (t, l, c) in want1)
-    # alpha-beta cost
+    assert _tlc(_run(lib, TWO, cpn=9, cb=1, seed=0x0123456789ABCDEF)[2]) == want
+
+
+def pin_two_npu_replay_reversed(lib):
+    # reversed pass: links swap their sources, the schedule is reversed in time
+    want1 = checker.two_npu_all_gather(9, 5, phase=1)
+    xf = _run(lib, TWO, cpn=9, cb=1, coll=1, seed=5)[2]
+    assert _tlc(xf) == sorted((9 - t - 1, l, (c + 9) % 18) for (t, l, c) in want1)
+    assert [(int(x["src"]), int(x["dst"])) for x in xf if int(x["link"]) == 0][0] == (0, 1)
+
+
+def pin_two_npu_unequal_costs_replay(lib):
+    # link 1 -> 0 (cost 1) has sent everything after 9 spans; the span at t = 9 matches
+    # nothing; link 0 -> 1 (cost 20) draws again at t = 20 in span 10
+    topo = T.from_edge_list(2, [(0, 1, 20, 0), (1, 0, 1, 0)])
+    want, Tw, spans, per_span = checker.two_npu_hetero_all_gather(9, 77, 20, 1)
+    assert per_span[9] == 0 and spans == 18 and Tw == 180
+    Tt, ev, xf = _run(lib, topo, cpn=9, cb=1, seed=77)[:3]
+    assert (Tt, ev) == (Tw, spans) and _tlc(xf) == want
+
+
+def pin_alpha_beta_cost(lib):
     v = ctypes.c_uint64(0)
     assert lib.orc_link_cost(500_000, 20_000, MiB, ctypes.byref(v)) and v.value == 21_471_520
     assert lib.orc_link_cost(0, 1500, 1, ctypes.byref(v)) and v.value == 2
-    # unidirectional ring: N-1 steps, unique schedule
-    ring = T.ring(6)
-    Tt, ev, xf = _run(lib, ring)
+    assert lib.orc_link_cost(0, 1499, 1, ctypes.byref(v)) and v.value == 1
+
+
+def pin_one_way_ring_closed_form(lib):
+    Tt, ev, xf = _run(lib, T.ring(6))[:3]
     assert (Tt, ev, len(xf)) == (5 * 21_471_520, 5, 30)
     for rec in xf:
         assert int(rec["chunk"]) == (int(rec["src"]) - int(rec["t_ps"]) // 21_471_520) % 6
-    # fully connected: one step
-    Tt, ev, xf = _run(lib, T.fully_connected(5))
-    assert ev == 1 and np.array_equal(xf["chunk"], xf["src"])
-    # independent checker on heterogeneous inputs, AG and RS
-    het = T.grid([3, 2, 3], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000])
-    cost = checker.link_costs_ps(het.alpha_ps, het.beta_fs_per_B, 64 << 10)
-    Tt, ev, xf = _run(lib, het, cpn=2, cb=64 << 10, seed=3)
-    checker.check_all_gather(18, het.link_src, het.link_dst, cost, 2, xf, Tt, check_maximal=True)
-    assert Tt >= checker.ingress_lower_bound(18, het.link_dst, cost, 2)
-    Tt, ev, xf = _run(lib, het, cpn=1, cb=64 << 10, coll=1, seed=3)
-    checker.check_reduce_scatter(18, het.link_src, het.link_dst, cost, 1, xf, Tt)
+
+
+def pin_complete_graph_one_span(lib):
+    Tt, ev, xf = _run(lib, T.fully_connected(5))[:3]
+    assert ev == 1 and len(xf) == 20 and np.array_equal(xf["chunk"], xf["src"])
+
+
+def pin_checker_heterogeneous_all_gather(lib):
+    cost = checker.link_costs_ps(HET.alpha_ps, HET.beta_fs_per_B, 64 << 10)
+    Tt, ev, xf = _run(lib, HET, cpn=2, cb=64 << 10, seed=3)[:3]
+    checker.check_all_gather(18, HET.link_src, HET.link_dst, cost, 2, xf, Tt, check_maximal=True)
+    assert Tt >= checker.ingress_lower_bound(18, HET.link_dst, cost, 2)
+
+
+def pin_checker_reduce_scatter(lib):
+    cost = checker.link_costs_ps(HET.alpha_ps, HET.beta_fs_per_B, 64 << 10)
+    Tt, ev, xf = _run(lib, HET, cpn=1, cb=64 << 10, coll=1, seed=3)[:3]
+    checker.check_reduce_scatter(18, HET.link_src, HET.link_dst, cost, 1, xf, Tt)
     rnd = T.random_regular_out(12, 2, seed=4)[0]
     cost = checker.link_costs_ps(rnd.alpha_ps, rnd.beta_fs_per_B, MiB)
-    Tt, ev, xf = _run(lib, rnd, coll=1, seed=6)
+    Tt, ev, xf = _run(lib, rnd, coll=1, seed=6)[:3]
     checker.check_reduce_scatter(12, rnd.link_src, rnd.link_dst, cost, 1, xf, Tt)
-    # All-Reduce = Reduce-Scatter, then All-Gather starting when the Reduce-Scatter ends
+
+
+def pin_all_reduce_is_rs_then_ag(lib):
     m = T.mesh2d(3, 3)
     cost = checker.link_costs_ps(m.alpha_ps, m.beta_fs_per_B, MiB)
     T_rs = _run(lib, m, coll=1, seed=2)[0]
-    T_ar, ev, xf = _run(lib, m, coll=2, seed=2)
+    T_ar, ev, xf = _run(lib, m, coll=2, seed=2)[:3]
     half = len(xf) // 2
     checker.check_reduce_scatter(9, m.link_src, m.link_dst, cost, 1, xf[:half], T_rs)
     checker.check_all_gather(9, m.link_src, m.link_dst, cost, 1, xf[half:], T_ar, check_maximal=True, t0=T_rs)
-    # brute-force optimum on a few small digraphs
+
+
+def pin_bruteforce_small_digraphs(lib):
     for edges in ([(0, 1), (1, 2), (2, 0)], [(0, 1), (1, 0), (1, 2), (2, 1)], [(0, 1), (1, 2), (2, 3), (3, 0), (0, 2)]):
         n = 1 + max(max(e) for e in edges)
         topo = T.from_edge_list(n, [(s, d, 1, 0) for s, d in edges])
         opt = checker.optimal_steps_unit(n, edges)
-        Tt, ev, xf = _run(lib, topo, cb=1, seed=1)
+        Tt, ev, xf = _run(lib, topo, cb=1, seed=1)[:3]
         assert opt <= ev <= opt + 1 and Tt == ev
-    # Broadcast from a root: pipelined on a one-way ring (N - 2 + k spans for k chunks), one
-    # span on a complete graph, valid and maximal on a heterogeneous torus; Reduce = its reverse
-    Tt, ev, xf = _run(lib, T.ring(7), cpn=5, coll=3, seed=8, root=3)
+
+
+def pin_broadcast_closed_forms(lib):
+    # pipelined on a one-way ring (N - 2 + k spans for k chunks), one span on a complete graph
+    Tt, ev, xf = _run(lib, T.ring(7), cpn=5, coll=3, seed=8, root=3)[:3]
     assert (Tt, ev, len(xf)) == (10 * 21_471_520, 10, 30) and set(xf["chunk"].tolist()) == set(range(5))
     assert int(xf[0]["src"]) == 3 and int(xf[0]["t_ps"]) == 0
-    Tt, ev, xf = _run(lib, T.fully_connected(6), cpn=1, coll=3, root=4)
+    Tt, ev, xf = _run(lib, T.fully_connected(6), cpn=1, coll=3, root=4)[:3]
     assert ev == 1 and set(xf["src"].tolist()) == {4} and len(xf) == 5
-    cost = checker.link_costs_ps(het.alpha_ps, het.beta_fs_per_B, 64 << 10)
-    Tt, ev, xf = _run(lib, het, cpn=6, cb=64 << 10, coll=3, seed=3, root=11)
-    checker.check_all_gather(18, het.link_src, het.link_dst, cost, 6, xf, Tt, check_maximal=True, root=11)
-    Tt, ev, xf = _run(lib, het, cpn=4, cb=64 << 10, coll=4, seed=3, root=7)
-    checker.check_reduce_scatter(18, het.link_src, het.link_dst, cost, 4, xf, Tt, root=7)
-    # lower-cost-link priority closed form
+
+
+def pin_checker_broadcast(lib):
+    cost = checker.link_costs_ps(HET.alpha_ps, HET.beta_fs_per_B, 64 << 10)
+    Tt, ev, xf = _run(lib, HET, cpn=6, cb=64 << 10, coll=3, seed=3, root=11)[:3]
+    checker.check_all_gather(18, HET.link_src, HET.link_dst, cost, 6, xf, Tt, check_maximal=True, root=11)
+
+
+def pin_checker_reduce(lib):
+    cost = checker.link_costs_ps(HET.alpha_ps, HET.beta_fs_per_B, 64 << 10)
+    Tt, ev, xf = _run(lib, HET, cpn=4, cb=64 << 10, coll=4, seed=3, root=7)[:3]
+    checker.check_reduce_scatter(18, HET.link_src, HET.link_dst, cost, 4, xf, Tt, root=7)
+
+
+def pin_cheapest_link_first_closed_form(lib):
     par = T.from_edge_list(2, [(0, 1, 10, 0), (0, 1, 1, 0), (1, 0, 1, 0)])
     assert _run(lib, par, cb=1, link_order=1)[0] == 1 and _run(lib, par, cb=1, link_order=0)[0] == 10
 
 
+def pin_independent_values_configs_2_and_3(lib):
+    # collective times and span counts of an independent implementation of the same rule
+    # (not this oracle, not the HIP path) on the 8x8 mesh All-Gather and the heterogeneous
+    # 4x4x8 torus All-Reduce; the torus has coincident arrivals and spans that match nothing
+    w = T.workload(2)
+    Tt, ev = _run(lib, w.topo, cpn=w.chunks_per_npu, cb=w.chunk_bytes, coll=w.collective, seed=w.seed)[:2]
+    assert (Tt, ev) == (393_301_440, 126)
+    w = T.workload(3)
+    Tt, ev, xf, pt, pe = _run(lib, w.topo, cpn=w.chunks_per_npu, cb=w.chunk_bytes, coll=w.collective, seed=w.seed)
+    assert pt == (856_889_280, 834_917_760) and pe == (265, 261) and Tt == 1_691_807_040 and len(xf) == 130_048
+
+
+def pin_pairs_parallel_links_replay(lib):
+    # postcondition-centric order on 0 -> 1 (one link) and 1 -> 0 (three parallel links):
+    # the whole schedule follows from the rule (counter (d, span, phase + 2, step), word 0
+    # picks the chunk, word 1 the free holder link in ascending link id)
+    topo = T.from_edge_list(2, [(0, 1, 1, 0), (1, 0, 1, 0), (1, 0, 1, 0), (1, 0, 1, 0)])
+    for cpn, seed in ((7, 0xFEDCBA9876543210), (70, 3)):
+        want = checker.two_npu_parallel_links_pairs(cpn, 3, seed)
+        Tt, ev, xf = _run(lib, topo, cpn=cpn, cb=1, seed=seed, matching=1)[:3]
+        assert _tlc(xf) == want and Tt == cpn and ev == cpn
+
+
+def pin_pairs_cheapest_holder_closed_form(lib):
+    # two parallel links into NPU 1, the cheaper one has the higher id: with cheapest-first
+    # order the single chunk must take it whatever the draw says
+    par = T.from_edge_list(2, [(0, 1, 10, 0), (0, 1, 1, 0), (1, 0, 1, 0)])
+    for seed in range(8):
+        assert _run(lib, par, cb=1, seed=seed, link_order=1, matching=1)[0] == 1
+    assert {_run(lib, par, cb=1, seed=seed, link_order=0, matching=1)[0] for seed in range(8)} == {1, 10}
+
+
+def pin_pairs_checker_valid_and_maximal(lib):
+    cost = checker.link_costs_ps(HET.alpha_ps, HET.beta_fs_per_B, 64 << 10)
+    for lo in (0, 1):
+        Tt, ev, xf = _run(lib, HET, cpn=2, cb=64 << 10, seed=5, matching=1, link_order=lo)[:3]
+        checker.check_all_gather(18, HET.link_src, HET.link_dst, cost, 2, xf, Tt, check_maximal=True)
+    Tt, ev, xf = _run(lib, HET, cpn=1, cb=64 << 10, coll=1, seed=5, matching=1)[:3]
+    checker.check_reduce_scatter(18, HET.link_src, HET.link_dst, cost, 1, xf, Tt)
+
+
+def pin_pairs_closed_forms(lib):
+    assert _run(lib, T.ring(6), seed=6, matching=1)[:2] == (5 * 21_471_520, 5)
+    Tt, ev, xf = _run(lib, T.fully_connected(5), seed=1, matching=1)[:3]
+    assert ev == 1 and np.array_equal(xf["chunk"], xf["src"])
+
+
+PINS = {k[4:]: v for k, v in list(globals().items()) if k.startswith("pin_")}
+
+
+def _failed_pins(lib, report=None):
+    failed = []
+    for name, pin in PINS.items():
+        if report:
+            report(("start", name))
+        try:
+            pin(lib)
+        except AssertionError:
+            failed.append(name)
+            if report:
+                report(("failed", name))
+    return failed
+
+
 def test_the_pins_pass_on_the_real_oracle():
-    _pins(oracle.lib())
+    assert _failed_pins(oracle.lib()) == []
+
+
+def test_every_mutant_names_pins_that_exist():
+    for name, (_, expected) in MUTANTS.items():
+        assert expected and expected <= set(PINS), name
 
 
 def _child(name, q):
     try:
-        _pins(_build(name))
-        q.put("passed")
-    except BaseException as e:  # any pin failing is what we want to see
-        q.put(f"caught: {type(e).__name__}")
+        lib = _build(name)
+    except BaseException as e:  # the patch did not apply or did not compile: a broken test
+        q.put(("error", f"{type(e).__name__}: {e}"))
+        return
+    try:
+        _failed_pins(lib, q.put)
+        q.put(("done", ""))
+    except BaseException as e:  # anything but a failed assertion is a broken test
+        q.put(("error", f"{type(e).__name__}: {e}"))
 
 
 @pytest.mark.parametrize("name", sorted(MUTANTS))
 def test_pins_catch_mutant(name):
-    """Run the pins on the mutant in a child process: a mutant may also never terminate
-    (a stalled event loop), which counts as caught."""
-    import multiprocessing as mp
+    """All pins run on the mutant in a child process (a mutated oracle may corrupt memory).
+    The mutant counts as noticed only if one of the pins named for it fails by an assertion;
+    a crash, a time-out, a patch that does not apply or any other exception is an error."""
     ctx = mp.get_context("fork")
     q = ctx.Queue()
     proc = ctx.Process(target=_child, args=(name, q))
     proc.start()
-    proc.join(12)
-    if proc.is_alive():
-        proc.kill()
-        proc.join()
-        return  # did not terminate: caught
-    if proc.exitcode != 0:
-        return  # crashed: caught
-    assert q.get(timeout=5).startswith("caught"), f"no pin notices mutant {name}"
+    failed, last, status = [], None, None
+    import queue as _queue
+    import time
+    deadline = time.time() + 120
+    while status is None:
+        try:
+            kind, what = q.get(timeout=1)
+        except _queue.Empty:
+            if not proc.is_alive() and q.empty():
+                status = ("died", f"exit code {proc.exitcode}")
+            elif time.time() > deadline:
+                proc.kill()
+                status = ("timeout", "")
+            continue
+        if kind == "start":
+            last = what
+        elif kind == "failed":
+            failed.append(what)
+        else:
+            status = (kind, what)
+    proc.join(10)
+    assert status[0] == "done", f"mutant {name}: child {status[0]} {status[1]} (last pin started: {last})"
+    expected = MUTANTS[name][1]
+    assert expected & set(failed), f"mutant {name}: none of {sorted(expected)} noticed it (failed pins: {failed})"

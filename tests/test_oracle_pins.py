@@ -118,6 +118,37 @@ def test_two_npu_exact_replay_pins_counter_and_key_layout(cpn, seed):
     assert [(int(x["src"]), int(x["dst"])) for x in rs.xfers if int(x["link"]) == 0][0] == (0, 1)
 
 
+def test_two_npu_unequal_costs_counts_spans_that_match_nothing():
+    """Reading: the span index (second counter word of every draw) counts every expanded
+    span of the pass, also one in which no link matches.  Links 0 -> 1 (cost 20) and 1 -> 0
+    (cost 1), 9 chunks per NPU: NPU 1 has sent everything after spans 0..8, the span at
+    t = 9 matches nothing, and link 0 draws its second chunk at t = 20 in span 10 (not 9).
+    Expected schedule replayed from the rule with the python Philox (pinned to the published
+    vectors above)."""
+    topo = T.from_edge_list(2, [(0, 1, 20, 0), (1, 0, 1, 0)])
+    want, Tw, spans, per_span = checker.two_npu_hetero_all_gather(9, 77, 20, 1)
+    assert per_span[9] == 0 and spans == 18 and Tw == 180
+    r = run(topo, cpn=9, chunk_bytes=1, seed=77)
+    got = [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in r.xfers]
+    assert got == want and r.collective_time_ps == Tw and r.n_events == spans
+    assert r.event_matches.tolist() == per_span
+    assert r.event_times.tolist() == list(range(10)) + [20 * k for k in range(1, 9)]
+
+
+def test_values_of_an_independent_implementation_configs_2_and_3():
+    """Collective times and span counts that an independent implementation of the same
+    deterministic rule produced for the 8x8-mesh All-Gather (seed 1) and the heterogeneous
+    4x4x8-torus All-Reduce (seed 2), hard-coded here: they were not written by this oracle
+    or by the HIP path.  The torus has coincident arrivals (the Z cost is twice the Y cost)
+    and spans that match nothing, so the span counts pin the span-index reading too."""
+    r = oracle.synthesize_workload(T.workload(2))
+    assert (r.collective_time_ps, r.n_events, r.n_xfers) == (393_301_440, 126, 16_128)
+    r = oracle.synthesize_workload(T.workload(3))
+    assert r.pass_time_ps == (856_889_280, 834_917_760)      # Reduce-Scatter pass, All-Gather pass
+    assert r.pass_events == (265, 261)
+    assert (r.collective_time_ps, r.n_events, r.n_xfers) == (1_691_807_040, 526, 130_048)
+
+
 # ------------------------------------------------------------------ closed forms
 
 @pytest.mark.parametrize("n", [2, 3, 4, 8, 13])
@@ -463,6 +494,54 @@ def test_postcondition_centric_against_set_based_implementation(lo):
         want_rs = sorted((Tr - t - cost[l], l, c) for (t, l, c) in rev)
         got_rs = [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in rs.xfers]
         assert got_rs == want_rs and rs.collective_time_ps == Tr
+
+
+@pytest.mark.parametrize("cpn,n_par,seed", [(7, 3, 0xFEDCBA9876543210), (70, 3, 3), (5, 2, 0), (130, 4, 12)])
+def test_postcondition_centric_two_npu_parallel_links_replay(cpn, n_par, seed):
+    """The draw of the postcondition-centric order, pinned without the set-based second
+    implementation: one link 0 -> 1 and n_par parallel links 1 -> 0, unit costs.  Every source
+    holds its own chunks from the start, so the servable chunks of a destination are the
+    other NPU's chunks not yet sent to it and every free link into it is a holder; the whole
+    schedule follows from counter (d, span, phase + 2, step), word 0 -> chunk (k-th smallest),
+    word 1 -> free holder link (ascending link id), replayed with the python Philox."""
+    topo = T.from_edge_list(2, [(0, 1, 1, 0)] + [(1, 0, 1, 0)] * n_par)
+    want = checker.two_npu_parallel_links_pairs(cpn, n_par, seed)
+    r = run(topo, cpn=cpn, chunk_bytes=1, seed=seed, matching=1)
+    got = [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in r.xfers]
+    assert got == want
+    assert r.collective_time_ps == cpn and r.n_events == cpn
+    # the reversed pass of a Reduce-Scatter draws with phase + 2 = 3 on the swapped links:
+    # there NPU 0 is reached over one link and NPU 1 over n_par, so the roles swap
+    rs = run(topo, cpn=cpn, chunk_bytes=1, coll=T.REDUCE_SCATTER, seed=seed, matching=1)
+    key = (seed & 0xFFFFFFFF, seed >> 32)
+    into = {1: list(range(1, n_par + 1)), 0: [0]}           # reversed: link ids into each NPU
+    left = {0: list(range(cpn, 2 * cpn)), 1: list(range(0, cpn))}
+    rev = []
+    span = 0
+    while left[0] or left[1]:
+        for d in (0, 1):
+            free, step = list(into[d]), 0
+            while free and left[d]:
+                rr = checker.philox4x32_10((d, span, 3, step), key)
+                c = left[d][rr[0] % len(left[d])]
+                link = free[rr[1] % len(free)]
+                left[d].remove(c)
+                free.remove(link)
+                rev.append((span, link, c))
+                step += 1
+        span += 1
+    want_rs = sorted((cpn - t - 1, l, c) for (t, l, c) in rev)
+    assert [(int(x["t_ps"]), int(x["link"]), int(x["chunk"])) for x in rs.xfers] == want_rs
+
+
+def test_postcondition_centric_cheapest_holder_closed_form():
+    """Cheapest-first order with the postcondition-centric matching: of two parallel links
+    into NPU 1 the cheaper one (the higher id) must carry the single chunk whatever the
+    draw says; in link-id order the draw decides, and both outcomes occur over 8 seeds."""
+    par = T.from_edge_list(2, [(0, 1, 10, 0), (0, 1, 1, 0), (1, 0, 1, 0)])
+    for seed in range(8):
+        assert run(par, chunk_bytes=1, seed=seed, matching=1, link_order=1).collective_time_ps == 1
+    assert {run(par, chunk_bytes=1, seed=seed, matching=1).collective_time_ps for seed in range(8)} == {1, 10}
 
 
 # ------------------------------------------------------------------ Broadcast / Reduce
