@@ -252,6 +252,21 @@ const char *tacos_last_error(void);
  */
 int tacos_link_costs(const tacos_topology_t *topo, uint64_t chunk_bytes, uint64_t *cost_ps);
 
+/*
+ * tacos_link_costs for callers that cannot allocate device memory: code that runs where
+ * hipMalloc is not allowed (while a HIP graph is being captured elsewhere in the process,
+ * tight serving loops, harnesses that forbid allocation).  Same arguments, same results
+ * and same error codes as tacos_link_costs, but the device staging (alpha, beta, costs,
+ * overflow flag) lives in a device array of fixed size that is part of the library image
+ * (24 bytes per link of TACOS_STATIC_MAX_LINKS links, about 6 MiB, present on every GPU the
+ * library runs on until the process ends), and the call makes no hipMalloc, hipFree or
+ * other allocating call.  More than TACOS_STATIC_MAX_LINKS links: TACOS_E_INVAL (see
+ * tacos_last_error).  Runs on the null stream and returns after the work has completed.
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU race.
+ */
+#define TACOS_STATIC_MAX_LINKS 262144u
+int tacos_link_costs_static(const tacos_topology_t *topo, uint64_t chunk_bytes, uint64_t *cost_ps);
+
 /* Library version string. */
 const char *tacos_version(void);
 

@@ -35,7 +35,7 @@ EXPORTS = [
     "tacos_result_pass_events", "tacos_result_read", "tacos_result_event_trace",
     "tacos_result_link_counts", "tacos_result_digest", "tacos_result_kernel_ms", "tacos_result_kernel_launches",
     "tacos_result_wall_ms", "tacos_result_device_bytes", "tacos_result_free",
-    "tacos_strerror", "tacos_last_error", "tacos_link_costs", "tacos_version",
+    "tacos_strerror", "tacos_last_error", "tacos_link_costs", "tacos_link_costs_static", "tacos_version",
 ]
 
 
@@ -95,6 +95,8 @@ def load() -> ctypes.CDLL:
     L.tacos_strerror.restype, L.tacos_strerror.argtypes = ctypes.c_char_p, [i32]
     L.tacos_last_error.restype, L.tacos_last_error.argtypes = ctypes.c_char_p, []
     L.tacos_link_costs.restype, L.tacos_link_costs.argtypes = i32, [ctypes.POINTER(_Topology), u64, vp]
+    L.tacos_link_costs_static.restype = i32
+    L.tacos_link_costs_static.argtypes = [ctypes.POINTER(_Topology), u64, vp]
     L.tacos_version.restype, L.tacos_version.argtypes = ctypes.c_char_p, []
     _lib = L
     return L
@@ -258,6 +260,18 @@ def tacos_link_costs(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunk_by
     topo, keep = _topology_struct(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B)
     out = np.zeros(topo.n_links, dtype=np.uint64)
     rc = L.tacos_link_costs(ctypes.byref(topo), int(chunk_bytes), out.ctypes.data)
+    del keep
+    if rc != TACOS_OK:
+        _raise(rc)
+    return out
+
+
+def tacos_link_costs_static(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunk_bytes) -> np.ndarray:
+    """tacos_link_costs_static of include/tacos.h (allocates no device memory)."""
+    L = load()
+    topo, keep = _topology_struct(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B)
+    out = np.zeros(topo.n_links, dtype=np.uint64)
+    rc = L.tacos_link_costs_static(ctypes.byref(topo), int(chunk_bytes), out.ctypes.data)
     del keep
     if rc != TACOS_OK:
         _raise(rc)

@@ -1010,6 +1010,35 @@ int tacos_link_costs(const tacos_topology_t *topo, uint64_t chunk_bytes, uint64_
   return TACOS_OK;
 }
 
+int tacos_link_costs_static(const tacos_topology_t *topo, uint64_t chunk_bytes, uint64_t *cost_ps)
+{
+  g_last_error.clear();
+  if (!topo || chunk_bytes == 0 || (topo->n_links && (!cost_ps || !topo->alpha_ps || !topo->beta_fs_per_B)))
+    return TACOS_E_INVAL;
+  if (topo->n_links > TACOS_STATIC_MAX_LINKS) {
+    g_last_error = "tacos_link_costs_static: more than TACOS_STATIC_MAX_LINKS links";
+    return TACOS_E_INVAL;
+  }
+  int dev = 0;
+  const int rc = require_device(&dev);
+  if (rc != TACOS_OK) return rc;
+  if (topo->n_links == 0) return TACOS_OK;
+  static_assert(TACOS_STATIC_MAX_LINKS == tacos::kStaticMaxLinks, "header and kernels disagree");
+  uint32_t overflow = 0;
+  const hipError_t e = tacos::link_cost_static(reinterpret_cast<const unsigned long long *>(topo->alpha_ps),
+                                               reinterpret_cast<const unsigned long long *>(topo->beta_fs_per_B),
+                                               chunk_bytes, topo->n_links,
+                                               reinterpret_cast<unsigned long long *>(cost_ps), &overflow, nullptr);
+  if (e != hipSuccess) {
+    char buf[256];
+    std::snprintf(buf, sizeof buf, "tacos_link_costs_static failed: %s", hipGetErrorString(e));
+    g_last_error = buf;  // a fixed-size message: this entry point allocates nothing on the device
+    (void)hipGetLastError();
+    return TACOS_E_DEVICE;
+  }
+  return overflow ? TACOS_E_OVERFLOW : TACOS_OK;
+}
+
 const char *tacos_strerror(int code)
 {
   switch (code) {

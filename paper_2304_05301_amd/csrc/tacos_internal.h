@@ -76,6 +76,14 @@ struct PassDev {
 void launch_link_cost(const unsigned long long *alpha, const unsigned long long *beta,
                       unsigned long long chunk_bytes, uint32_t L, unsigned long long *cost,
                       uint32_t *overflow, hipStream_t s);
+// a1 for callers that may not allocate: the same kernel with its device staging in a
+// file-scope device array (per GPU) instead of allocated buffers.  Host pointers in and out;
+// L in [1, kStaticMaxLinks]; *h_overflow != 0 if a cost does not fit.  Calls no hipMalloc or
+// hipFree; returns after the work on `s` has completed.  Calls that overlap on one GPU race.
+constexpr uint32_t kStaticMaxLinks = 262144;
+hipError_t link_cost_static(const unsigned long long *h_alpha, const unsigned long long *h_beta,
+                            unsigned long long chunk_bytes, uint32_t L, unsigned long long *h_cost,
+                            uint32_t *h_overflow, hipStream_t s);
 // a2: precondition rows, idle links, control block
 void launch_init_pass(const PassDev &p, hipStream_t s);
 // a3 + a8 (consume): arrivals at the event's time; writes event_time_slot and, for a

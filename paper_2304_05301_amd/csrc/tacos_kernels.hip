@@ -16,6 +16,7 @@
 
 #include "tacos_internal.h"
 
+#include <mutex>
 #include <type_traits>
 
 namespace tacos {
@@ -1179,6 +1180,69 @@ void launch_link_cost(const u64 *alpha, const u64 *beta, u64 chunk_bytes, u32 L,
   if (L == 0) return;
   hipLaunchKernelGGL(link_cost_kernel, dim3((L + 255) / 256), dim3(256), 0, s, alpha, beta,
                      chunk_bytes, L, cost, overflow);
+}
+
+// ---------------------------------------------------------------- link costs without allocating
+//
+// Device staging of the entry point that may not allocate: the alpha and beta arrays, the
+// costs and the overflow flag of up to kStaticMaxLinks links, in a file-scope device array.
+// Every GPU the library runs on holds its own copy of the array (until the process ends) at
+// its own address; host code never uses the array's name as an address, only the pointer
+// hipGetSymbolAddress returned for the device that is current.
+static __device__ __align__(256) unsigned char scratch[3ull * kStaticMaxLinks * 8ull + 256ull];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// the array's address on the current device, looked up once per device
+hipError_t static_scratch(unsigned char **ptr)
+{
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = static_cast<unsigned char *>(g_scratch_ptr[dev]);
+  return hipSuccess;
+}
+
+__global__ void clear_word_kernel(u32 *w) { *w = 0u; }
+
+}  // namespace
+
+hipError_t link_cost_static(const u64 *h_alpha, const u64 *h_beta, u64 chunk_bytes, u32 L, u64 *h_cost,
+                            u32 *h_overflow, hipStream_t s)
+{
+  if (L == 0 || L > kStaticMaxLinks) return hipErrorInvalidValue;
+  unsigned char *base = nullptr;
+  hipError_t e = static_scratch(&base);
+  if (e != hipSuccess) return e;
+  u64 *d_alpha = reinterpret_cast<u64 *>(base);
+  u64 *d_beta = d_alpha + kStaticMaxLinks;
+  u64 *d_cost = d_beta + kStaticMaxLinks;
+  u32 *d_ovf = reinterpret_cast<u32 *>(d_cost + kStaticMaxLinks);
+  const size_t bytes = (size_t)L * 8;
+  if ((e = hipMemcpyAsync(d_alpha, h_alpha, bytes, hipMemcpyHostToDevice, s)) != hipSuccess) return e;
+  if ((e = hipMemcpyAsync(d_beta, h_beta, bytes, hipMemcpyHostToDevice, s)) != hipSuccess) return e;
+  // the array keeps the last call's contents: the flag has to start at zero (a fill kernel
+  // rather than a memset node, so that the sequence may also be captured into a graph)
+  hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, s, d_ovf);
+  hipLaunchKernelGGL(link_cost_kernel, dim3((L + 255) / 256), dim3(256), 0, s, d_alpha, d_beta, chunk_bytes, L,
+                     d_cost, d_ovf);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((e = hipMemcpyAsync(h_cost, d_cost, bytes, hipMemcpyDeviceToHost, s)) != hipSuccess) return e;
+  if ((e = hipMemcpyAsync(h_overflow, d_ovf, 4, hipMemcpyDeviceToHost, s)) != hipSuccess) return e;
+  return hipStreamSynchronize(s);
 }
 
 void launch_init_pass(const PassDev &p, hipStream_t s)
