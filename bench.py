@@ -8,8 +8,12 @@ links, 1 chunk of 1 MiB per NPU, seed 4).  Prints ONE JSON line.
 
   value      = link-chunk matches per second of the whole synthesis call (wall clock,
                inputs are a few MB of topology arrays uploaded inside the call)
-  roofline   = matching kernel: algorithmic bytes per launch / mean launch duration
-               (HIP events on the launch stream) against the 8 TB/s HBM peak
+  roofline   = matching kernel: algorithmic (cache-blind) bytes per launch / mean launch
+               duration (HIP events on the launch stream, one extra instrumented step after
+               the timed ones) against the 8 TB/s HBM peak; roofline.l2 = the bytes the
+               wavefronts ask L2 for / the same duration against the rate a no-arithmetic
+               probe of the same request pattern reaches on this device, measured now
+               (the ceiling that binds: a fraction <= 1)
   cpu_baseline = the CPU oracle timed on this machine's host cores on a bounded prefix of
                the same workload
 """
@@ -35,12 +39,25 @@ def algorithmic_bytes(n_matches, n_npus, n_links, n_chunks):
     return n_matches * wb * (1.0 + 2.0 / deg)
 
 
-def measured_traffic(kernel, workload_name):
-    """HBM-side bytes per launch of the matching kernel from the committed rocprofv3 --pmc
-    summary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size), or None."""
-    path = os.path.join(PROFILES, f"{kernel}_{workload_name}_traffic.txt")
+def library_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for rel in ("paper_2304_05301_amd/csrc/tacos_kernels.hip", "paper_2304_05301_amd/csrc/tacos_api.cpp",
+                "paper_2304_05301_amd/csrc/tacos_internal.h"):
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(kernel, workload_name, matching):
+    """Counter summary of the matching kernel written by bench_profile.py from rocprofv3 --pmc
+    runs: bytes beyond L2 per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known
+    size) and bytes asked of L2 (TCC_REQ_sum x 128 B).  Returns {} when there is none, or
+    when it was measured on other library sources than the ones in the tree (stale)."""
+    variant = f"_matching{matching}" if matching else ""
+    path = os.path.join(PROFILES, f"{kernel}_{workload_name}{variant}_traffic.txt")
     if not os.path.exists(path):
-        return None
+        return {}
     vals = {}
     with open(path) as f:
         for line in f:
@@ -48,28 +65,58 @@ def measured_traffic(kernel, workload_name):
                 k, v = line.split("=", 1)
                 vals[k.strip()] = v.strip()
     if vals.get("workload") != workload_name:
-        return None
-    return float(vals["hbm_bytes_per_launch"])
+        return {}
+    if vals.get("library_sources_sha256") != library_source_hash():
+        print(f"bench.py: {os.path.relpath(path, ROOT)} was measured on other library sources: "
+              "roofline.traffic = null (run bench_profile.py again)", file=sys.stderr)
+        return {}
+    return vals
 
 
-def measured_read_peak_gbs(torch):
-    """Streaming-read rate of this device, measured live: a read-only reduction over 2 GiB
-    (torch's sum kernel), mean of 10 runs after 2 warm-up runs, in GB/s."""
-    a = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
-    a.fill_(1)
-    v = a.view(torch.int64)
-    for _ in range(2):
-        v.sum()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(10):
-        v.sum()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / 10
-    del v, a
-    return (2 << 30) / ms / 1e6
+class Probes:
+    """ctypes access to libbench_probe.so (bench_probe.hip): no-arithmetic memory probes."""
+
+    def __init__(self):
+        import ctypes
+        path = os.path.join(ROOT, "libbench_probe.so")
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: python -c 'import __graft_entry__ as g; g.build()'")
+        L = ctypes.CDLL(path)
+        d = ctypes.POINTER(ctypes.c_double)
+        L.probe_row_stream.restype = ctypes.c_int
+        L.probe_row_stream.argtypes = [ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
+                                       ctypes.c_uint32, d, d]
+        for f in (L.probe_read_stream, L.probe_copy):
+            f.restype = ctypes.c_int
+            f.argtypes = [ctypes.c_uint64, ctypes.c_uint32, d]
+        self.L = L
+        self.ctypes = ctypes
+
+    def row_stream(self, topo, row_bytes, iters=200):
+        import numpy as np
+        c = self.ctypes
+        rp = np.ascontiguousarray(topo.row_ptr, dtype=np.uint32)
+        ci = np.ascontiguousarray(topo.col_idx, dtype=np.uint32)
+        us, req = c.c_double(0), c.c_double(0)
+        rc = self.L.probe_row_stream(topo.n_npus, rp.ctypes.data, ci.ctypes.data, int(row_bytes), iters,
+                                     c.byref(us), c.byref(req))
+        if rc != 0:
+            raise RuntimeError(f"probe_row_stream: hipError {rc}")
+        return us.value, req.value
+
+    def read_stream(self, nbytes=2 << 30, iters=10):
+        v = self.ctypes.c_double(0)
+        rc = self.L.probe_read_stream(nbytes, iters, self.ctypes.byref(v))
+        if rc != 0:
+            raise RuntimeError(f"probe_read_stream: hipError {rc}")
+        return v.value
+
+    def copy(self, nbytes=1 << 30, iters=10):
+        v = self.ctypes.c_double(0)
+        rc = self.L.probe_copy(nbytes, iters, self.ctypes.byref(v))
+        if rc != 0:
+            raise RuntimeError(f"probe_copy: hipError {rc}")
+        return v.value
 
 
 def cpu_baseline(w, target_s=15.0):
@@ -188,7 +235,12 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", type=int, default=5, help="1..7 (default 5: 40,960-NPU torus)")
+    ap.add_argument("--matching", type=int, default=0, help="0 link-centric (default), 1 Algorithm 1's own order")
+    ap.add_argument("--link-order", type=int, default=0, help="0 ascending link id (default), 1 cheapest link first")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="skip the extra instrumented step (profile runs: rocprofv3 times the kernels)")
+    ap.add_argument("--no-probes", action="store_true", help="skip the memory probes (profile runs)")
     ap.add_argument("--report-all", action="store_true",
                     help="instead of the one JSON line: a table over workloads 1..7 (GPU time, spans, "
                          "matches/s, fraction of the HBM roofline, oracle time on the host cores)")
@@ -217,7 +269,8 @@ def main():
     n_chunks = topo.n_npus * w.chunks_per_npu
 
     def step(timed):
-        r = binding.synthesize_workload(w, stream=stream, time_kernels=timed)
+        r = binding.synthesize_workload(w, stream=stream, time_kernels=timed, matching=args.matching,
+                                        link_order=args.link_order)
         out = (r.num_xfers, r.num_events, r.collective_time_ps, r.kernel_ms, r.kernel_launches,
                r.digest, r.wall_ms)
         r.free()
@@ -233,23 +286,66 @@ def main():
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
+    # the timed steps run without any instrumentation
     t0 = time.perf_counter()
-    results = [step(True) for _ in range(args.steps)]
+    results = [step(False) for _ in range(args.steps)]
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    n_xfers, n_events, T_ps, _, launches, digest, _ = results[0]
+    n_xfers, n_events, T_ps, _, _, digest, _ = results[0]
     assert all(r[0] == n_xfers and r[5] == digest for r in results), "non-deterministic result"
     ms_per_step = 1e3 * elapsed / args.steps
-    kernel_ms = sum(r[3] for r in results) / args.steps
-    launches = max(1, launches)
+
+    # one extra step with HIP events around every launch of the matching kernel
+    kernel_ms, launches, instrumented_wall_ms = None, None, None
+    if not args.no_kernel_timing:
+        k = step(True)
+        assert k[0] == n_xfers and k[5] == digest, "non-deterministic result"
+        kernel_ms, launches, instrumented_wall_ms = k[3], max(1, k[4]), k[6]
     alg_bytes = algorithmic_bytes(n_xfers, topo.n_npus, topo.n_links, n_chunks)
-    mean_launch_s = kernel_ms * 1e-3 / launches
-    achieved = alg_bytes / launches / mean_launch_s / 1e9 if mean_launch_s > 0 else 0.0
-    # small topologies run in the single-workgroup kernel: a few launches, each many spans
-    kernel = "small_sweep_kernel" if launches < n_events else "match_kernel"
-    traffic = measured_traffic(kernel, w.name)
-    read_peak = measured_read_peak_gbs(torch)
+    roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+                "traffic": None, "kernel": None,
+                "note": "achieved = algorithmic (cache-blind) bytes per launch / launch duration: every source row "
+                        "counted once per matched link although about 70 % of the requests hit in L2, so it may "
+                        "exceed the HBM peak; the ceilings that bind are in l2 and hbm_side"}
+    if kernel_ms:
+        mean_launch_s = kernel_ms * 1e-3 / launches
+        achieved = alg_bytes / launches / mean_launch_s / 1e9
+        # small topologies run in the single-workgroup kernel: a few launches, each many spans
+        kernel = "small_sweep_kernel" if launches < n_events else "match_kernel"
+        tr = measured_traffic(kernel, w.name, args.matching)
+        traffic = float(tr["hbm_bytes_per_launch"]) if tr else None
+        roofline.update({"achieved": achieved, "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": kernel,
+                         "algorithmic_bytes_per_launch": alg_bytes / launches, "mean_launch_us": mean_launch_s * 1e6})
+        probes = None
+        if not args.no_probes:
+            try:
+                probes = Probes()
+            except ImportError as e:
+                print(f"bench.py: {e}", file=sys.stderr)
+        if probes and kernel == "match_kernel" and n_chunks <= 65536:
+            row_bytes = 1024 * ((n_chunks + 8191) // 8192)
+            probe_us, probe_req = probes.row_stream(topo, row_bytes)
+            read_peak, copy_rate = probes.read_stream(), probes.copy()
+            # bytes the wavefronts ask L2 for per launch: counted (TCC_REQ_sum x 128 B, committed
+            # summary of the same sources) or else the rows the kernel must request when every
+            # incoming link is idle: (1 + in-degree) rows per destination
+            if tr and "l2_request_bytes_per_launch" in tr:
+                l2_req, l2_src = float(tr["l2_request_bytes_per_launch"]), "rocprofv3 TCC_REQ_sum x 128 B"
+            else:
+                l2_req, l2_src = probe_req, "(NPUs + links) x row bytes"
+            ceiling = probe_req / (probe_us * 1e-6) / 1e9
+            l2_rate = l2_req / mean_launch_s / 1e9
+            roofline["l2"] = {"bound": "l2", "request_bytes_per_launch": l2_req, "request_bytes_source": l2_src,
+                              "achieved": l2_rate, "ceiling": ceiling, "unit": "GB/s", "frac": l2_rate / ceiling,
+                              "ceiling_source": "bench_probe.hip probe_row_stream: the same rows in the same order, "
+                                                "no arithmetic, measured in this run",
+                              "probe_launch_us": probe_us, "probe_request_bytes_per_launch": probe_req}
+            roofline["hbm_side"] = {"measured_read_stream_GBps": read_peak, "measured_copy_GBps": copy_rate,
+                                    "traffic_GBps": traffic / mean_launch_s / 1e9 if traffic else None,
+                                    "frac_of_peak": traffic / mean_launch_s / 1e9 / HBM_PEAK_GBS if traffic else None,
+                                    "frac_of_measured_read_stream": traffic / mean_launch_s / 1e9 / read_peak
+                                    if traffic else None}
 
     line = {
         "metric": "ten_link_chunk_matches_per_sec",
@@ -267,7 +363,7 @@ def main():
         "config": {"workload": w.name, "topology": topo.name, "n_npus": topo.n_npus,
                    "n_links": topo.n_links, "chunks": n_chunks, "chunk_bytes": w.chunk_bytes,
                    "collective": ["all_gather", "reduce_scatter", "all_reduce"][w.collective],
-                   "seed": w.seed},
+                   "seed": w.seed, "matching": args.matching, "link_order": args.link_order},
         "synthesis_wall_s": ms_per_step * 1e-3,
         "synthesis_wall_s_median": sorted(r[6] for r in results)[len(results) // 2] * 1e-3,
         "matches": n_xfers,
@@ -276,19 +372,9 @@ def main():
         "schedule_digest": digest,
         "match_kernel_ms_per_step": kernel_ms,
         "match_kernel_launches": launches,
-        "match_kernel_matches_per_s": n_xfers / (kernel_ms * 1e-3) if kernel_ms > 0 else None,
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": kernel,
-                     "algorithmic_bytes_per_launch": alg_bytes / launches,
-                     "mean_launch_us": mean_launch_s * 1e6,
-                     # HBM-side bytes per launch (rocprofv3 counters, committed summary) over the
-                     # launch duration measured now, and the same against a streaming read
-                     # measured now on this device
-                     "traffic_GBps": (traffic / mean_launch_s / 1e9) if traffic and mean_launch_s > 0 else None,
-                     "measured_read_peak_GBps": read_peak,
-                     "traffic_frac_of_measured_peak": (traffic / mean_launch_s / 1e9 / read_peak)
-                     if traffic and mean_launch_s > 0 and read_peak else None},
+        "match_kernel_matches_per_s": n_xfers / (kernel_ms * 1e-3) if kernel_ms else None,
+        "instrumented_step_wall_ms": instrumented_wall_ms,
+        "roofline": roofline,
         "paper_context": "paper reports wall-clock only: 128-NPU All-Reduce synthesized in 1.08 s, "
                          "40K-NPU 2D mesh All-Reduce in 2.52 h (Xeon E5-2699v3, 64 threads)",
     }
