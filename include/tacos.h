@@ -131,14 +131,23 @@ typedef struct {
   uint32_t time_kernels;  /* != 0: bracket every launch of the kernel that does the matching
                              with HIP events on `stream` so that tacos_result_kernel_ms is
                              available                                                      */
-  uint32_t launch_mode;   /* 0 = automatic (2 when the shape allows it, else 1).
+  uint32_t launch_mode;   /* 0 = automatic.
                              1 = two plain launches per span (arrivals; matching + next-event
                              reduction), queued in batches.
                              2 = small topologies: ONE workgroup sweeps many spans per launch
                              with the per-link state and a work list in LDS and matches only
                              the destinations something changed for; needs links, NPUs and
                              need rows to fit the LDS of one CU (<= 16,384 chunks, a few
-                             thousand links), else TACOS_E_INVAL.  Same results in all modes. */
+                             thousand links), else TACOS_E_INVAL.
+                             3 = homogeneous TEN (paper, section "Time-expanded Network": links of
+                             equal cost, spans of equal length): ONE launch per span; a chunk
+                             matched in span e arrives exactly at span e + 1, so arrivals,
+                             matching and the next event need no separate steps.  Needs equal
+                             link costs (<= 2^31 ps), <= 65,536 chunks, link-centric matching,
+                             max_events == 0, else TACOS_E_INVAL.  Automatic: 2 if it fits, else
+                             3 if it applies and its two held tables take at most 256 MiB
+                             (about 32,768 NPUs with one chunk each), else 1.  Same results
+                             in all modes.                                                   */
   uint32_t link_order;    /* order in which a destination's idle incoming links are tried:
                              0 = ascending link id; 1 = cheapest link first, ties by link id
                              (paper, "Prioritizing Lower-cost Links").  The random draw of a

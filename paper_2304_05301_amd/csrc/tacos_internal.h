@@ -18,18 +18,24 @@ constexpr uint32_t kStInternal = 3;
 // Device-resident control block of one pass.  next_t is double-buffered by event
 // parity: the matching kernel of event e min-reduces the end times of all transfers
 // in flight into next_t[(e+1)&1]; the arrival kernel of event e+1 reads it as "now".
+// The pass has ended when nothing is in flight after a span's matching: every NPU holds
+// every chunk if no destination of that span still needed one (need_flag), else the
+// topology is not strongly connected.
 struct Ctl {
   unsigned long long next_t[2];
-  unsigned long long remaining;  // unsatisfied postconditions (NPU, chunk) at the start of the pass,
-                                 // net of what the single-workgroup kernel has delivered
+  unsigned long long remaining;  // single-workgroup kernel: unsatisfied postconditions (NPU, chunk)
   unsigned long long T;          // time of the last arrival, valid once done
+  unsigned long long now;        // time of the span the arrival kernel processed last
   uint32_t done;
   uint32_t status;
   uint32_t n_events;             // matching sweeps run, valid once done
   uint32_t pad;
-  // arrivals counted by the per-span arrival kernel, spread over 64 words so that its
-  // workgroups do not serialise on one address; unsatisfied = remaining - sum(arrived)
-  unsigned long long arrived[64];
+  // Set by the matching of span e if a destination with an idle incoming link still misses a
+  // chunk, read by the launch that follows, cleared one span ahead.  Two launches per span:
+  // index e & 1 (set by match_kernel, read and cleared by arrive_kernel); homogeneous-TEN path:
+  // index e % 3, with match_flag[e % 3] set if a link was matched in span e.
+  uint32_t need_flag[4];
+  uint32_t match_flag[4];
 };
 
 // HBM layout of the per-NPU held bitsets ("precondition" rows).
@@ -76,6 +82,29 @@ struct PassDev {
 void launch_link_cost(const unsigned long long *alpha, const unsigned long long *beta,
                       unsigned long long chunk_bytes, uint32_t L, unsigned long long *cost,
                       uint32_t *overflow, hipStream_t s);
+// Homogeneous TEN (every link of the topology has the same cost, so all spans have the same
+// length and a chunk matched in span e arrives exactly at span e + 1; paper, section
+// "Time-expanded Network"): arrivals, matching and the next event collapse into ONE launch
+// per span.  The held table is double-buffered: span e reads held[e & 1], which is complete
+// as of that span, and every destination's wavefront brings its own row of the other table
+// (one span behind) up to date for span e + 1 by setting the bits of the chunks that arrived
+// now (matched in span e - 1, prev[(e - 1) & 1]) and of the ones it matches now.
+struct UniformDev {
+  unsigned long long *held[2];  // [N][row_words] each
+  uint32_t *prev[2];            // [L] by in-list position: chunk matched in span e (prev[e & 1]) or kNone
+  uint32_t *rnd[2];             // [L] by in-list position: word 0 of Philox(link, e, phase, 0) for span e
+                                //     (rnd[e & 1]); link-centric matching only, else null
+  unsigned long long cost;      // the common link cost: span e is at time e * cost
+};
+// prev = kNone, the random words of span 0 (p.held / p.carry / p.free_at / p.rnd are not used
+// by this path; the control block and in_rec come from launch_init_pass)
+void launch_uniform_init(const PassDev &p, const UniformDev &u, uint32_t mode, hipStream_t s);
+// a3-a8 of span `event` in one launch.  row: schedule row of the span (forward pass), row_next:
+// schedule row of span event + 1 (reversed pass: rows are keyed by arrival); the other is null.
+// The pass has ended when the launch of span e finds that span e - 1 needed nothing.
+void launch_match_uniform(const PassDev &p, const UniformDev &u, uint32_t event, uint32_t *row, uint32_t *row_next,
+                          unsigned long long *event_time_slot, uint32_t mode, hipStream_t s);
+
 // a1 for callers that may not allocate: the same kernel with its device staging in a
 // file-scope device array (per GPU) instead of allocated buffers.  Host pointers in and out;
 // L in [1, kStaticMaxLinks]; *h_overflow != 0 if a cost does not fit.  Calls no hipMalloc or

@@ -49,17 +49,6 @@ __device__ __forceinline__ u32 wave_inclusive_scan(u32 v)
   return v;
 }
 
-__device__ __forceinline__ u64 wave_sum64(u64 v)
-{
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    const u32 lo = (u32)__shfl_xor((int)(u32)v, off, 64);
-    const u32 hi = (u32)__shfl_xor((int)(u32)(v >> 32), off, 64);
-    v += ((u64)hi << 32) | lo;
-  }
-  return v;
-}
-
 // Minimum over the 64 lanes (uniform result) with DPP moves: a reduction towards the last
 // lane of each row of 16 (row_shr 1,2,4,8), then across rows (row_bcast:15, row_bcast:31);
 // lanes a move does not reach keep the identity (all ones).  The result is read from lane 63.
@@ -184,7 +173,8 @@ __global__ void init_links_kernel(PassDev p)
     c->status = 0u;
     c->n_events = 0u;
     c->pad = 0u;
-    for (int i = 0; i < 64; ++i) c->arrived[i] = 0ull;
+    c->now = 0ull;
+    for (int i = 0; i < 4; ++i) { c->need_flag[i] = 0u; c->match_flag[i] = 0u; }
   }
 }
 
@@ -206,11 +196,22 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
   if (ctl->done) return;
   const u64 t = ctl->next_t[event & 1u];
   if (l == 0) {
-    *event_time_slot = t;
-    ctl->next_t[(event + 1u) & 1u] = kInf;
-    if (t == kInf) {  // chunks missing (else done) and nothing in flight
-      ctl->status = kStUnreachable;
+    if (t == kInf) {
+      // a4 / a8: nothing is in flight after the previous span's matching.  If no destination
+      // needed a chunk there, every postcondition is satisfied and the collective ended at
+      // that span's time; else the topology is not strongly connected.
+      if (event != 0u && ctl->need_flag[(event - 1u) & 1u] == 0u) {
+        ctl->T = ctl->now;
+        ctl->n_events = event - 1u;
+      } else {
+        ctl->status = kStUnreachable;
+      }
       ctl->done = 1u;
+    } else {
+      *event_time_slot = t;
+      ctl->now = t;
+      ctl->next_t[(event + 1u) & 1u] = kInf;
+      ctl->need_flag[event & 1u] = 0u;
     }
   }
   if (t == kInf) return;
@@ -223,13 +224,6 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
     p.carry[l] = kNone;
   }
   if (sched_row && arrived) sched_row[link] = c;  // rows are pre-filled with kNone
-  const u32 n = (u32)__popcll(__ballot(arrived));
-  __shared__ u32 block_n;
-  if (threadIdx.x == 0) block_n = 0;
-  __syncthreads();
-  if ((threadIdx.x & 63u) == 0 && n) atomicAdd(&block_n, n);
-  __syncthreads();
-  if (threadIdx.x == 0 && block_n) atomicAdd(&ctl->arrived[blockIdx.x & 63u], (u64)block_n);
 }
 
 // ---------------------------------------------------------------- a4-a8: matching
@@ -300,6 +294,98 @@ __device__ __forceinline__ u32 kth_set_bit_wave(u32 lo, u32 hi, u32 k)
   return (u32)__ffsll((long long)hit) - 1u;
 }
 
+// The link-centric draws of ONE destination for up to 64 of its incoming links (one per
+// lane): for every link whose bit is set in `idle`, in ascending lane order,
+//   cand = held[source] & need;  p = |cand|;  nothing if p == 0;
+//   the link carries the (r mod p)-th smallest chunk of cand, which leaves `need`.
+// s, r: the lane's link's source NPU and random word; need_lds: the destination's need row
+// (this wavefront's NP*64 uint4 of LDS), updated in place.  Returns the lane's link's chunk or
+// kNone.  Source rows land in two register buffers used in turn, so that the next link's
+// row is in flight while the current link is decided; the candidate set is formed in place
+// in the buffer.
+template <int NP>
+__device__ __forceinline__ u32 draw_chunks(const u64 *__restrict__ held, u32 row_words, u32 s, u32 r, u64 idle,
+                                           uint4 *need_lds, int lane)
+{
+  constexpr int NW = 2 * NP;
+  constexpr int NDW = 4 * NP;
+  typedef RowRegs<NDW> RT;
+  u32 res = kNone;
+  typename RT::A buf0_a, buf1_a;
+  typename RT::B buf0_b, buf1_b;
+  auto fetch = [&](typename RT::A &ba, typename RT::B &bb, u64 pending) {
+    const u32 src = read_lane(s, (u32)__ffsll((long long)pending) - 1u);
+    const uint4 *sp = reinterpret_cast<const uint4 *>(held + (u64)src * row_words) + lane;
+    static_for<0, NP>([&](auto I) {
+      constexpr int i = decltype(I)::value;
+      const uint4 v = sp[i * 64];
+      RT::template set<4 * i>(ba, bb, v.x); RT::template set<4 * i + 1>(ba, bb, v.y);
+      RT::template set<4 * i + 2>(ba, bb, v.z); RT::template set<4 * i + 3>(ba, bb, v.w);
+    });
+  };
+  auto decide = [&](typename RT::A &ca, typename RT::B &cb, typename RT::A &na, typename RT::B &nb) {
+    const u32 b = (u32)__ffsll((long long)idle) - 1u;
+    idle &= idle - 1ull;
+    // cand = held[src] & need in place, with the running in-lane candidate counts
+    u32 pre[NW];
+    u32 cnt = 0;
+    static_for<0, NP>([&](auto I) {
+      constexpr int i = decltype(I)::value;
+      const uint4 nd = need_lds[i * 64 + lane];
+      const u32 c0 = RT::template get<4 * i>(ca, cb) & nd.x;
+      const u32 c1 = RT::template get<4 * i + 1>(ca, cb) & nd.y;
+      const u32 c2 = RT::template get<4 * i + 2>(ca, cb) & nd.z;
+      const u32 c3 = RT::template get<4 * i + 3>(ca, cb) & nd.w;
+      RT::template set<4 * i>(ca, cb, c0); RT::template set<4 * i + 1>(ca, cb, c1);
+      RT::template set<4 * i + 2>(ca, cb, c2); RT::template set<4 * i + 3>(ca, cb, c3);
+      cnt = popc_acc(c0, cnt);
+      cnt = popc_acc(c1, cnt);
+      pre[2 * i] = cnt;
+      cnt = popc_acc(c2, cnt);
+      cnt = popc_acc(c3, cnt);
+      pre[2 * i + 1] = cnt;
+    });
+    // pin the candidate computation ahead of the next row's loads: it waits for THIS
+    // row only, and the next row's latency hides behind the selection below
+    asm volatile("" ::"v"(cnt));
+    if (idle) fetch(na, nb, idle);
+    const u32 incl = wave_inclusive_scan(cnt);
+    const u32 pop = read_lane(incl, 63);
+    if (pop != 0) {
+      u32 k = read_lane(r, b) % pop;
+      const u64 above = __ballot(incl > k);
+      const u32 ln = (u32)__ffsll((long long)above) - 1u;
+      k -= read_lane(incl - cnt, ln);
+      u32 idx = 0, before = 0;
+#pragma unroll
+      for (int i = 0; i < NW - 1; ++i) {
+        const u32 pi = read_lane(pre[i], ln);
+        const u32 le = ((k - pi) >> 31) ^ 1u;
+        idx += le;
+        const u32 cand_before = pi * le;
+        before = cand_before > before ? cand_before : before;
+      }
+      const u32 lo = read_lane(RT::at(ca, cb, 2u * idx), ln);
+      const u32 hi = read_lane(RT::at(ca, cb, 2u * idx + 1u), ln);
+      const u32 bit = kth_set_bit_wave(lo, hi, k - before);
+      const u32 chunk = ((ln * (u32)NW + idx) << 6) + bit;
+      // now in flight to d: one lane removes it from the LDS row
+      if (lane == 0) {
+        u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(idx >> 1) * 64u + ln]) + ((idx & 1u) * 2u + (bit >> 5));
+        *ptr &= ~(1u << (bit & 31u));
+      }
+      if ((u32)lane == b) res = chunk;
+    }
+  };
+  if (idle) fetch(buf0_a, buf0_b, idle);
+  while (idle) {
+    decide(buf0_a, buf0_b, buf1_a, buf1_b);
+    if (!idle) break;
+    decide(buf1_a, buf1_b, buf0_a, buf0_b);
+  }
+  return res;
+}
+
 // Algorithm 1 for ONE destination d at TEN span `event` (time t), run by one wavefront.
 // Returns (per lane) the earliest end time among the transfers in flight on the links
 // this lane looked at; the caller min-reduces it.
@@ -314,8 +400,6 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb
                                                      u32 *__restrict__ sched_row, int lane, uint4 *need_lds)
 {
   constexpr int NW = 2 * NP;
-  constexpr int NDW = 4 * NP;
-  typedef RowRegs<NDW> RT;
   Ctl *ctl = p.ctl;
   u64 my_min = kInf;  // [jb, je) = d's in-list positions
 
@@ -363,6 +447,7 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb
     // d holds every chunk: nothing is or will be in flight to it, its links stay idle for
     // good, and the host may drop it from the processing order
     if (!need_any && p.dest_done && lane == 0) p.dest_done[d] = 1u;
+    if (need_any && lane == 0) ctl->need_flag[event & 1u] = 1u;
     for (u32 base = jb; base < je; base += 64) {
       const u32 j = base + lane;
       u32 cr = kNone;
@@ -396,82 +481,11 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb
     }
     u32 res = kNone;
     if (need_any) {
-      u64 idle = __ballot(valid && cr == kNone);
+      const u64 idle = __ballot(valid && cr == kNone);
       u32 r = 0;
       if constexpr (LATENCY_BOUND) r = philox4x32_10_word0(l, event, p.phase, 0u, p.seed_lo, p.seed_hi);
       else if (valid) r = p.rnd[j];
-      typename RT::A buf0_a, buf1_a;
-      typename RT::B buf0_b, buf1_b;
-      auto fetch = [&](typename RT::A &ba, typename RT::B &bb, u64 pending) {
-        const u32 src = read_lane(s, (u32)__ffsll((long long)pending) - 1u);
-        const uint4 *sp = reinterpret_cast<const uint4 *>(p.held + (u64)src * p.row_words) + lane;
-        static_for<0, NP>([&](auto I) {
-          constexpr int i = decltype(I)::value;
-          const uint4 v = sp[i * 64];
-          RT::template set<4 * i>(ba, bb, v.x); RT::template set<4 * i + 1>(ba, bb, v.y);
-          RT::template set<4 * i + 2>(ba, bb, v.z); RT::template set<4 * i + 3>(ba, bb, v.w);
-        });
-      };
-      auto decide = [&](typename RT::A &ca, typename RT::B &cb, typename RT::A &na, typename RT::B &nb) {
-        const u32 b = (u32)__ffsll((long long)idle) - 1u;
-        idle &= idle - 1ull;
-        // cand = held[src] & need in place, with the running in-lane candidate counts
-        u32 pre[NW];
-        u32 cnt = 0;
-        static_for<0, NP>([&](auto I) {
-          constexpr int i = decltype(I)::value;
-          const uint4 nd = need_lds[i * 64 + lane];
-          const u32 c0 = RT::template get<4 * i>(ca, cb) & nd.x;
-          const u32 c1 = RT::template get<4 * i + 1>(ca, cb) & nd.y;
-          const u32 c2 = RT::template get<4 * i + 2>(ca, cb) & nd.z;
-          const u32 c3 = RT::template get<4 * i + 3>(ca, cb) & nd.w;
-          RT::template set<4 * i>(ca, cb, c0); RT::template set<4 * i + 1>(ca, cb, c1);
-          RT::template set<4 * i + 2>(ca, cb, c2); RT::template set<4 * i + 3>(ca, cb, c3);
-          cnt = popc_acc(c0, cnt);
-          cnt = popc_acc(c1, cnt);
-          pre[2 * i] = cnt;
-          cnt = popc_acc(c2, cnt);
-          cnt = popc_acc(c3, cnt);
-          pre[2 * i + 1] = cnt;
-        });
-        // pin the candidate computation ahead of the next row's loads: it waits for THIS
-        // row only, and the next row's latency hides behind the selection below
-        asm volatile("" ::"v"(cnt));
-        if (idle) fetch(na, nb, idle);
-        const u32 incl = wave_inclusive_scan(cnt);
-        const u32 pop = read_lane(incl, 63);
-        if (pop != 0) {
-          u32 k = read_lane(r, b) % pop;
-          const u64 above = __ballot(incl > k);
-          const u32 ln = (u32)__ffsll((long long)above) - 1u;
-          k -= read_lane(incl - cnt, ln);
-          u32 idx = 0, before = 0;
-#pragma unroll
-          for (int i = 0; i < NW - 1; ++i) {
-            const u32 pi = read_lane(pre[i], ln);
-            const u32 le = ((k - pi) >> 31) ^ 1u;
-            idx += le;
-            const u32 cand_before = pi * le;
-            before = cand_before > before ? cand_before : before;
-          }
-          const u32 lo = read_lane(RT::at(ca, cb, 2u * idx), ln);
-          const u32 hi = read_lane(RT::at(ca, cb, 2u * idx + 1u), ln);
-          const u32 bit = kth_set_bit_wave(lo, hi, k - before);
-          const u32 chunk = ((ln * (u32)NW + idx) << 6) + bit;
-          // now in flight to d: one lane removes it from the LDS row
-          if (lane == 0) {
-            u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(idx >> 1) * 64u + ln]) + ((idx & 1u) * 2u + (bit >> 5));
-            *ptr &= ~(1u << (bit & 31u));
-          }
-          if ((u32)lane == b) res = chunk;
-        }
-      };
-      if (idle) fetch(buf0_a, buf0_b, idle);
-      while (idle) {
-        decide(buf0_a, buf0_b, buf1_a, buf1_b);
-        if (!idle) break;
-        decide(buf1_a, buf1_b, buf0_a, buf0_b);
-      }
+      res = draw_chunks<NP>(p.held, p.row_words, s, r, idle, need_lds, lane);
     }
     if (valid) {
       if (sched_row && res != kNone) sched_row[l] = res;  // rows are pre-filled with kNone
@@ -557,7 +571,9 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
       need_lds[i * 64 + lane] = v;
       acc |= v.x | v.y | v.z | v.w;
     }
-    if (__ballot(acc != 0u) == 0ull && p.dest_done && lane == 0) p.dest_done[d] = 1u;  // d holds every chunk
+    const bool need_any = __ballot(acc != 0u) != 0ull;
+    if (!need_any && p.dest_done && lane == 0) p.dest_done[d] = 1u;  // d holds every chunk
+    if (need_any && lane == 0) ctl->need_flag[event & 1u] = 1u;
     if (cr != kNone) {  // chunks in flight to d are not needed
       const u32 w = cr >> 6;
       const u32 ln = w / (u32)NW;
@@ -688,12 +704,7 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
   Ctl *ctl = p.ctl;
   if (ctl->done) return;
-  const u64 rem = ctl->remaining - wave_sum64(ctl->arrived[lane]);
   const u64 t = ctl->next_t[event & 1u];
-  if (rem == 0) {  // every postcondition satisfied: the collective ends now
-    if (slot == 0 && lane == 0) { ctl->T = t; ctl->n_events = event; ctl->done = 1u; }
-    return;
-  }
   __shared__ uint4 need_lds[4 * NP * 64];
   uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
   u64 my_min;
@@ -706,6 +717,136 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
     u64 *nt = &ctl->next_t[(event + 1u) & 1u];
     const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (m < cur) atomicMin(nt, m);
+  }
+}
+
+// ---------------------------------------------------------------- homogeneous TEN: one launch per span
+
+__global__ void uniform_init_kernel(PassDev p, UniformDev u)
+{
+  const u32 j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= p.L) return;
+  u.prev[0][j] = kNone;
+  u.prev[1][j] = kNone;
+  if (u.rnd[0]) u.rnd[0][j] = philox4x32_10_word0(p.in_link[j], 0u, p.phase, 0u, p.seed_lo, p.seed_hi);
+}
+
+// Algorithm 1 (link-centric form) for ONE destination d at span `event` of a homogeneous TEN,
+// run by one wavefront.  Every incoming link is idle at the start of a span (the transfers of
+// the previous span have just arrived) and nothing is in flight, so need = ~held[d].  Returns
+// whether a link was matched.
+template <int NP>
+__device__ __forceinline__ bool match_destination_uniform(const PassDev &p, const UniformDev &u, u32 d, u32 jb, u32 je,
+                                                          u32 event, u32 *__restrict__ sched_row,
+                                                          u32 *__restrict__ sched_row_next, int lane, uint4 *need_lds)
+{
+  Ctl *ctl = p.ctl;
+  const u64 *H = u.held[event & 1u];
+  u64 *Hn = u.held[(event + 1u) & 1u] + (u64)d * p.row_words;
+  const u32 *prev_in = u.prev[(event + 1u) & 1u];
+  u32 *prev_out = u.prev[event & 1u];
+  const u32 *rnd = u.rnd[event & 1u];
+  const uint4 *hp = reinterpret_cast<const uint4 *>(H + (u64)d * p.row_words) + lane;
+  u32 acc = 0;
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    uint4 v = hp[i * 64];
+    v.x = ~v.x; v.y = ~v.y; v.z = ~v.z; v.w = ~v.w;
+    need_lds[i * 64 + lane] = v;
+    acc |= v.x | v.y | v.z | v.w;
+  }
+  const bool need_any = __ballot(acc != 0u) != 0ull;
+  // the chunks that arrived now are in held[event & 1] already; the other table lags a span
+  bool had_prev = false;
+  if (event != 0u) {
+    for (u32 base = jb; base < je; base += 64) {
+      const u32 j = base + (u32)lane;
+      const u32 pc = j < je ? prev_in[j] : kNone;
+      if (pc != kNone) atomicOr(&Hn[phys_word(pc >> 6, NP)], 1ull << (pc & 63u));
+      had_prev = had_prev || __ballot(pc != kNone) != 0ull;
+    }
+  }
+  if (!need_any) {
+    // d holds every chunk; once its last arrivals are in both tables the host may drop it
+    for (u32 base = jb; base < je; base += 64)
+      if (base + (u32)lane < je) prev_out[base + lane] = kNone;
+    if (!had_prev && p.dest_done && lane == 0) p.dest_done[d] = 1u;
+    return false;
+  }
+  if (lane == 0) ctl->need_flag[event % 3u] = 1u;
+  bool any = false;
+  for (u32 base = jb; base < je; base += 64) {
+    const u32 j = base + (u32)lane;
+    const bool valid = j < je;
+    u32 l = 0, s = 0, r = 0;
+    if (valid) {
+      const uint4 rec = p.in_rec[j];
+      l = rec.x; s = rec.y;
+      r = rnd[j];
+    }
+    const u32 res = draw_chunks<NP>(H, p.row_words, s, r, __ballot(valid), need_lds, lane);
+    if (valid) {
+      prev_out[j] = res;
+      if (res != kNone) {
+        if (res >= p.C) {
+          ctl->status = kStInternal;
+          ctl->done = 1u;
+        } else {
+          if (sched_row) sched_row[l] = res;            // rows are pre-filled with kNone
+          if (sched_row_next) sched_row_next[l] = res;  // reversed pass: keyed by arrival
+          atomicOr(&Hn[phys_word(res >> 6, NP)], 1ull << (res & 63u));
+        }
+      }
+    }
+    any = any || __ballot(res != kNone) != 0ull;
+  }
+  return any;
+}
+
+template <int NP, int MODE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NP == 5 && MODE == 0 ? 6 : 1)))
+void match_uniform_kernel(PassDev p, UniformDev u, u32 event, u32 *__restrict__ sched_row,
+                          u32 *__restrict__ sched_row_next, u64 *__restrict__ event_time_slot)
+{
+  const int lane = threadIdx.x & 63;
+  const u32 per_xcd = gridDim.x >> 3;  // as match_kernel: contiguous slices of the order per XCD
+  const u32 pos = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  const u32 slot = uniform(pos * 4u + (threadIdx.x >> 6));
+  if (slot >= p.n_slots) return;
+  const uint4 sr = p.slot_rec[slot];
+  const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
+  Ctl *ctl = p.ctl;
+  if (ctl->done) return;
+  if (event != 0u) {
+    // a4 / a8: what the previous span found.  Nothing needed: the collective ended there.
+    // Something needed and nothing matched: no transfer is in flight, the topology is not
+    // strongly connected.
+    const u32 pv = (event + 2u) % 3u;
+    const u32 nf = ctl->need_flag[pv], mf = ctl->match_flag[pv];
+    if (nf == 0u || mf == 0u) {
+      if (slot == 0 && lane == 0) {
+        if (nf == 0u) { ctl->T = (u64)(event - 1u) * u.cost; ctl->n_events = event - 1u; }
+        else ctl->status = kStUnreachable;
+        ctl->done = 1u;
+      }
+      return;
+    }
+  }
+  if (slot == 0 && lane == 0) {
+    const u32 nx = (event + 1u) % 3u;
+    ctl->need_flag[nx] = 0u;
+    ctl->match_flag[nx] = 0u;
+    *event_time_slot = (u64)event * u.cost;
+  }
+  __shared__ uint4 need_lds[4 * NP * 64];
+  uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
+  const bool any = match_destination_uniform<NP>(p, u, d, jb, je, event, sched_row, sched_row_next, lane, my_need);
+  if (any && lane == 0) ctl->match_flag[event % 3u] = 1u;
+  // a6, first half, for the NEXT span: this launch's wavefronts share out the links, 64 each
+  if (u.rnd[0]) {
+    u32 *rnd_next = u.rnd[(event + 1u) & 1u];
+    for (u32 q = slot * 64u + (u32)lane; q < p.L; q += p.n_slots * 64u)
+      rnd_next[q] = philox4x32_10_word0(p.in_rec[q].x, event + 1u, p.phase, 0u, p.seed_lo, p.seed_hi);
   }
 }
 
@@ -751,6 +892,7 @@ __device__ __forceinline__ u64 match_destination_streamed(const PassDev &p, u32 
     }
     need_any = __ballot(acc != 0u) != 0ull;
     if (!need_any && p.dest_done && lane == 0) p.dest_done[d] = 1u;
+    if (need_any && lane == 0) ctl->need_flag[event & 1u] = 1u;
     for (u32 base = jb; base < je; base += 64) {  // chunks in flight to d are not needed
       const u32 j = base + (u32)lane;
       const u32 cr = j < je ? p.carry[j] : kNone;
@@ -876,12 +1018,7 @@ __global__ __launch_bounds__(256) void match_kernel_streamed(PassDev p, u32 even
   const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
   Ctl *ctl = p.ctl;
   if (ctl->done) return;
-  const u64 rem = ctl->remaining - wave_sum64(ctl->arrived[lane]);
   const u64 t = ctl->next_t[event & 1u];
-  if (rem == 0) {
-    if (slot == 0 && lane == 0) { ctl->T = t; ctl->n_events = event; ctl->done = 1u; }
-    return;
-  }
   uint4 *my_need = reinterpret_cast<uint4 *>(streamed_lds) + (size_t)(threadIdx.x >> 6) * p.NP * 64u;
   const u64 my_min = match_destination_streamed(p, d, jb, je, event, t, sched_row, lane, my_need);
   const u64 m = wave_min64(my_min);
@@ -979,7 +1116,7 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   q.free_at = s_free;
   q.ctl = s_ctl;
   u64 t = ctl->next_t[first_event & 1u];
-  u64 remaining = ctl->remaining - wave_sum64(ctl->arrived[lane]);
+  u64 remaining = ctl->remaining;
   u32 e = first_event;
   bool finished = false;  // uniform
   __syncthreads();
@@ -1073,7 +1210,6 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   // ---- hand the state back for the next launch
   __syncthreads();
   for (u32 l = tid; l < p.L; l += 1024u) { p.free_at[l] = s_free[l]; p.carry[l] = s_carry[l]; }
-  if (tid < 64) ctl->arrived[tid] = 0ull;  // folded into `remaining` above
   if (tid == 0 && !finished) ctl->next_t[e & 1u] = t;
   if (tid == 0) ctl->remaining = remaining;
 }
@@ -1290,6 +1426,34 @@ void launch_match(const PassDev &p, u32 event, u32 *sched_row, u32 mode, hipStre
   if (mode == 0) launch_match_mode<0>(p, event, sched_row, s);
   else if (mode == 1) launch_match_mode<1>(p, event, sched_row, s);
   else launch_match_mode<2>(p, event, sched_row, s);
+}
+
+void launch_uniform_init(const PassDev &p, const UniformDev &u, uint32_t mode, hipStream_t s)
+{
+  (void)mode;
+  hipLaunchKernelGGL(uniform_init_kernel, dim3((p.L + 255) / 256 + (p.L == 0)), dim3(256), 0, s, p, u);
+}
+
+void launch_match_uniform(const PassDev &p, const UniformDev &u, u32 event, u32 *row, u32 *row_next,
+                          u64 *event_time_slot, u32 mode, hipStream_t s)
+{
+  (void)mode;  // link-centric only so far; the host sends the other orders down the general path
+  const u32 n_wg = (p.n_slots + 3u) / 4u;
+  const dim3 grid(8u * ((n_wg + 7u) / 8u + (n_wg == 0u)), 1, 1), block(256);
+#define TACOS_UNIFORM(NP_) \
+  hipLaunchKernelGGL((match_uniform_kernel<NP_, 0>), grid, block, 0, s, p, u, event, row, row_next, event_time_slot)
+  switch (p.NP) {
+    case 1: TACOS_UNIFORM(1); break;
+    case 2: TACOS_UNIFORM(2); break;
+    case 3: TACOS_UNIFORM(3); break;
+    case 4: TACOS_UNIFORM(4); break;
+    case 5: TACOS_UNIFORM(5); break;
+    case 6: TACOS_UNIFORM(6); break;
+    case 7: TACOS_UNIFORM(7); break;
+    case 8: TACOS_UNIFORM(8); break;
+    default: break;  // the host uses this path for rows of at most 8 pieces only
+  }
+#undef TACOS_UNIFORM
 }
 
 static size_t small_launch_lds(const PassDev &p, u32 *dst_in_lds)

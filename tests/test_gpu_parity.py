@@ -214,6 +214,65 @@ def test_explicit_launch_modes_bit_exact(name, mk, cpn, coll, mode, stream):
         assert_same(r, ref, name)
 
 
+HOMOGENEOUS = [
+    ("uniring13", lambda: T.ring(13), 1, T.ALL_GATHER),
+    ("biring9_cpn3", lambda: T.ring(9, bidirectional=True), 3, T.ALL_GATHER),
+    ("fc70_indeg_over_64", lambda: T.fully_connected(70), 2, T.ALL_GATHER),
+    ("mesh5x4_cpn7", lambda: T.mesh2d(5, 4), 7, T.ALL_GATHER),
+    ("torus2x3_parallel_links", lambda: T.grid([2, 3], True), 2, T.ALL_GATHER),
+    ("mesh6x5_rs", lambda: T.mesh2d(6, 5), 3, T.REDUCE_SCATTER),
+    ("torus3x3x3_ar", lambda: T.torus3d(3, 3, 3), 2, T.ALL_REDUCE),
+    ("switch12d3_rs", lambda: T.switch_unwound(12, 3), 1, T.REDUCE_SCATTER),
+    ("random40_equal_cost_ar", lambda: _equal_cost(T.random_regular_out(40, 3, seed=7)[0]), 2, T.ALL_REDUCE),
+    ("torus4x4x4_three_piece_rows", lambda: T.torus3d(4, 4, 4), 300, T.ALL_GATHER),
+]
+
+
+def _equal_cost(topo):
+    """The same graph with the paper's default link (0.5 us, 50 GB/s) on every link."""
+    return T.Topology(topo.n_npus, topo.row_ptr, topo.col_idx, np.full_like(topo.alpha_ps, 500_000),
+                      np.full_like(topo.beta_fs_per_B, 20_000), topo.name + "_equal")
+
+
+@pytest.mark.parametrize("name,mk,cpn,coll", HOMOGENEOUS, ids=[c[0] for c in HOMOGENEOUS])
+def test_homogeneous_ten_one_launch_per_span_bit_exact(name, mk, cpn, coll, stream):
+    """launch_mode 3 (links of equal cost: one launch per span on the double-buffered held
+    table) gives the oracle's schedule and trace, record by record; so does launch_mode 1 on
+    the same input (two launches per span)."""
+    topo = mk()
+    cb = 192 << 10
+    ref = cpu(topo, cpn, cb, coll, 9)
+    for mode in (3, 1):
+        with gpu(topo, cpn, cb, coll, 9, stream, launch_mode=mode) as r:
+            assert_same(r, ref, f"{name} mode {mode}")
+            if coll == T.ALL_GATHER:
+                t, m = r.event_trace(0)
+                assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches)
+
+
+def test_homogeneous_ten_mode_limits_and_errors(stream):
+    het = T.grid([3, 2, 3], True, [300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000])
+    with pytest.raises(binding.TacosError) as e:   # link costs differ
+        gpu(het, 1, MiB, T.ALL_GATHER, 0, stream, launch_mode=3)
+    assert e.value.code == binding.TACOS_E_INVAL
+    topo = T.mesh2d(4, 4)
+    for kw in ({"matching": 1}, {"max_events": 3}):
+        with pytest.raises(binding.TacosError) as e:
+            gpu(topo, 1, MiB, T.ALL_GATHER, 0, stream, launch_mode=3, **kw)
+        assert e.value.code == binding.TACOS_E_INVAL
+    # not strongly connected: NPU 2 can send but never receives
+    broken = T.from_edge_list(3, [(0, 1, 500_000, 20_000), (1, 0, 500_000, 20_000), (2, 0, 500_000, 20_000)])
+    with pytest.raises(binding.TacosError) as e:
+        gpu(broken, 1, MiB, T.ALL_GATHER, 0, stream, launch_mode=3)
+    assert e.value.code == binding.TACOS_E_UNREACHABLE
+    # rooted collectives take the path as well
+    ring = T.ring(7)
+    for coll in (T.BROADCAST, T.REDUCE):
+        ref = cpu(ring, 5, MiB, coll, 8, root=3)
+        with gpu(ring, 5, MiB, coll, 8, stream, root=3, launch_mode=3) as r:
+            assert_same(r, ref, f"rooted {coll}")
+
+
 def test_both_launch_modes_on_prefix_runs(stream):
     topo = T.torus3d(4, 4, 8)
     ref = cpu(topo, 65, MiB, T.ALL_GATHER, 3, max_events=37)
