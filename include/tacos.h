@@ -220,7 +220,12 @@ int tacos_result_read(const tacos_result_t *r, uint64_t first, uint64_t count,
 /*
  * Per-sweep trace of pass `pass`: time of every matching sweep and the number of
  * matches made in it, n = tacos_result_pass_events entries each (either pointer may
- * be NULL).  Link utilisation of a sweep = matches / n_links.
+ * be NULL).  Link utilisation of a sweep = matches / n_links.  The times are the pass's
+ * own, counted from its first sweep at 0: for a forward pass inside an All-Reduce add the
+ * Reduce-Scatter's time; a reversed pass (Reduce-Scatter, Reduce) is traced as it was
+ * synthesized, i.e. on the reversed links and before the reversal in time, so sweep i at
+ * time t_i holds the transfers that END at T - t_i in the schedule.  (For a reversed pass
+ * the counts are computed from the schedule on first use: one pass over its rows.)
  */
 int tacos_result_event_trace(const tacos_result_t *r, uint32_t pass,
                              uint64_t *event_time_ps, uint32_t *event_matches);

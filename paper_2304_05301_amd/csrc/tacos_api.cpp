@@ -121,6 +121,8 @@ struct Pass {
   std::vector<uint64_t> row_time;   // [n_rows] by event index
   std::vector<uint32_t> row_count;  // [n_rows] by event index
   std::vector<uint64_t> canon_base; // [n_rows+1] prefix of counts in canonical row order
+  // reversed pass: matches made in every span (row_count holds arrivals); filled on first use
+  mutable std::vector<uint32_t> start_count;
   // canonical row k is event k of a forward pass, event n_rows-1-k of a reversed one
   uint64_t event_of(uint64_t k) const { return reversed ? n_rows - 1 - k : k; }
   uint64_t time_of_event(uint64_t e) const { return reversed ? T - row_time[e] : row_time[e] + t_off; }
@@ -137,6 +139,7 @@ struct tacos_result {
   double kernel_ms = 0.0, wall_ms = 0.0;
   uint64_t kernel_launches = 0;
   uint64_t device_bytes = 0;
+  DevBuf d_cost;  // [L] link costs, kept for the per-span trace of a reversed pass
 };
 
 namespace {
@@ -703,7 +706,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       }
     } else {
       if (L == 0) return TACOS_E_UNREACHABLE;
-      DevBuf d_cost;
+      DevBuf &d_cost = res->d_cost;
       std::vector<uint64_t> host_cost;
       const bool by_cost = opts && opts->link_order == TACOS_LINK_ORDER_COST;
       rc = device_costs(topo, chunk_bytes, stream, d_cost, &host_cost);
@@ -912,13 +915,42 @@ uint64_t tacos_result_device_bytes(const tacos_result_t *r) { return r ? r->devi
 int tacos_result_event_trace(const tacos_result_t *r, uint32_t pass, uint64_t *event_time_ps,
                              uint32_t *event_matches)
 {
+  g_last_error.clear();
   if (!r || pass >= r->passes.size()) return TACOS_E_INVAL;
   const Pass &ps = r->passes[pass];
-  // forward pass: sweeps 0..E-1; reversed pass: its rows are keyed by arrival, sweeps 1..E
-  const uint64_t first = ps.reversed ? 1 : 0;
+  // The rows of a reversed pass are keyed by the span a chunk ARRIVED in, so their counts are
+  // arrivals per span; the matches per span are counted from the rows once, on first use.
+  if (ps.reversed && event_matches && ps.n_events && ps.start_count.empty()) {
+    try {
+      int prev = 0;
+      HIP_TRY(hipGetDevice(&prev));
+      if (prev != r->device) HIP_TRY(hipSetDevice(r->device));
+      DevBuf d_time((size_t)ps.n_rows * 8), d_counts((size_t)ps.n_rows * 4);
+      HIP_TRY(hipMemcpy(d_time.p, ps.row_time.data(), (size_t)ps.n_rows * 8, hipMemcpyHostToDevice));
+      HIP_TRY(hipMemset(d_counts.p, 0, (size_t)ps.n_rows * 4));
+      for (size_t k = 0; k < ps.segs.size(); ++k) {
+        const uint64_t first = (uint64_t)k * ps.rows_per_seg;
+        if (first >= ps.n_rows) break;
+        const uint32_t n = (uint32_t)std::min<uint64_t>(ps.rows_per_seg, ps.n_rows - first);
+        tacos::launch_start_span_counts(ps.segs[k].rows.as<uint32_t>(), (uint32_t)first, n, ps.L,
+                                        d_time.as<unsigned long long>(), r->d_cost.as<unsigned long long>(),
+                                        d_counts.as<uint32_t>(), nullptr);
+        HIP_TRY(hipGetLastError());
+      }
+      std::vector<uint32_t> counts(ps.n_rows);
+      HIP_TRY(hipMemcpy(counts.data(), d_counts.p, (size_t)ps.n_rows * 4, hipMemcpyDeviceToHost));
+      if (prev != r->device) HIP_TRY(hipSetDevice(prev));
+      ps.start_count.swap(counts);
+    } catch (const HipFail &f) {
+      return f.code;
+    } catch (const std::bad_alloc &) {
+      return TACOS_E_NOMEM;
+    }
+  }
+  // spans 0 .. E-1 of the pass, in the pass's own time (a reversed pass runs from its t = 0)
   for (uint64_t i = 0; i < ps.n_events; ++i) {
-    if (event_time_ps) event_time_ps[i] = ps.row_time[first + i];
-    if (event_matches) event_matches[i] = ps.row_count[first + i];
+    if (event_time_ps) event_time_ps[i] = ps.row_time[i];
+    if (event_matches) event_matches[i] = ps.reversed ? ps.start_count[i] : ps.row_count[i];
   }
   return TACOS_OK;
 }

@@ -156,6 +156,13 @@ void launch_row_stats(const uint32_t *rows, uint32_t n_rows, uint32_t L,
                       uint32_t reversed, uint32_t *row_count, unsigned long long *digest,
                       hipStream_t s);
 
+// reporting, reversed pass (rows keyed by arrival span): counts[k] += number of transfers of
+// the block of rows [first_row, first_row + n_rows) that STARTED in span k, i.e. whose arrival
+// time minus the link's cost is row_time[k]; row_time: times of all spans of the pass, ascending
+void launch_start_span_counts(const uint32_t *rows, uint32_t first_row, uint32_t n_rows, uint32_t L,
+                              const unsigned long long *row_time, const unsigned long long *cost,
+                              uint32_t *counts, hipStream_t s);
+
 // reporting: counts[l] += number of rows of the block in which link l carries a chunk
 void launch_link_counts(const uint32_t *rows, uint32_t n_rows, uint32_t L, unsigned long long *counts,
                         hipStream_t s);

@@ -1293,6 +1293,40 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const u32 *__restrict__ 
   }
 }
 
+// grid = (ceil(L/256), n_rows): a thread looks at one entry of one schedule row of a reversed
+// pass.  The row index is the span the chunk ARRIVED in; the span it was matched in is the one
+// whose time is the arrival time minus the link's cost (every transfer starts at a span's
+// time), found by binary search in the ascending span times.  Lanes of a wavefront that
+// found the same span add to its counter once.
+__global__ __launch_bounds__(256) void start_span_count_kernel(const u32 *__restrict__ rows, u32 first_row, u32 L,
+                                                               const u64 *__restrict__ row_time,
+                                                               const u64 *__restrict__ cost,
+                                                               u32 *__restrict__ counts)
+{
+  const u32 l = blockIdx.x * 256u + threadIdx.x;
+  const u32 r = first_row + blockIdx.y;
+  u32 idx = kNone;
+  if (l < L && rows[(u64)blockIdx.y * L + l] != kNone) {
+    const u64 t_start = row_time[r] - cost[l];
+    u32 lo = 0, hi = r;  // the first span with time >= t_start
+    while (lo < hi) {
+      const u32 mid = (lo + hi) >> 1;
+      if (row_time[mid] < t_start) lo = mid + 1u;
+      else hi = mid;
+    }
+    idx = lo;
+  }
+  u64 todo = __ballot(idx != kNone);
+  const int lane = threadIdx.x & 63;
+  while (todo) {
+    const u32 first = (u32)__ffsll((long long)todo) - 1u;
+    const u32 v = read_lane(idx, first);
+    const u64 same = __ballot(idx == v);
+    if ((u32)lane == first) atomicAdd(&counts[v], (u32)__popcll(same));
+    todo &= ~same;
+  }
+}
+
 // grid = (ceil(L/256), ceil(n_rows/64)): a thread sums 64 rows of one schedule column
 __global__ __launch_bounds__(256) void link_count_kernel(const u32 *__restrict__ rows, u32 n_rows, u32 L,
                                                          u64 *__restrict__ counts)
@@ -1456,11 +1490,22 @@ void launch_match_uniform(const PassDev &p, const UniformDev &u, u32 event, u32 
 #undef TACOS_UNIFORM
 }
 
+// LDS a workgroup may ask for on the current device (what the host's fit test compares
+// against), never more than the 160 KiB of a gfx950 compute unit.
+static size_t lds_limit()
+{
+  int dev = 0, v = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess || v <= 0)
+    return 64 * 1024;
+  return (size_t)v < kLdsPerWorkgroup ? (size_t)v : kLdsPerWorkgroup;
+}
+
 static size_t small_launch_lds(const PassDev &p, u32 *dst_in_lds)
 {
   size_t lds = small_lds_bytes(p.N, p.L, p.NP);
   const size_t dst_bytes = ((size_t)p.L * 4 + 15) & ~(size_t)15;
-  *dst_in_lds = lds + dst_bytes <= kLdsPerWorkgroup ? 1u : 0u;
+  *dst_in_lds = lds + dst_bytes <= lds_limit() ? 1u : 0u;
   if (*dst_in_lds) lds += dst_bytes;
   return lds;
 }
@@ -1530,6 +1575,17 @@ hipError_t launch_small_sweep_batch(const SmallJob *jobs, u32 n_jobs, const Pass
 }
 
 size_t small_sweep_lds_bytes(u32 N, u32 L, u32 NP) { return NP <= 2 ? small_lds_bytes(N, L, NP) : (size_t)-1; }
+
+void launch_start_span_counts(const u32 *rows, u32 first_row, u32 n_rows, u32 L, const u64 *row_time,
+                              const u64 *cost, u32 *counts, hipStream_t s)
+{
+  if (n_rows == 0 || L == 0) return;
+  for (u32 r0 = 0; r0 < n_rows; r0 += 65535u) {  // grid.y limit
+    const u32 nr = n_rows - r0 < 65535u ? n_rows - r0 : 65535u;
+    hipLaunchKernelGGL(start_span_count_kernel, dim3((L + 255) / 256, nr), dim3(256), 0, s, rows + (u64)r0 * L,
+                       first_row + r0, L, row_time, cost, counts);
+  }
+}
 
 void launch_link_counts(const u32 *rows, u32 n_rows, u32 L, u64 *counts, hipStream_t s)
 {

@@ -90,9 +90,30 @@ def test_small_cases_bit_exact(name, mk, cpn, coll, seed, stream):
     with gpu(topo, cpn, cb, coll, seed, stream) as r:
         assert_same(r, ref, name)
         assert r.num_passes == (2 if coll == T.ALL_REDUCE else 1)
-        if coll == T.ALL_GATHER:
+        # per-span trace (times and matches made) of the LAST pass is what the oracle keeps; the
+        # Reduce-Scatter half of an All-Reduce equals the Reduce-Scatter alone
+        last = r.num_passes - 1
+        t, m = r.event_trace(last)
+        assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches), name
+        assert int(m.sum()) == r.num_xfers // r.num_passes
+        if coll == T.ALL_REDUCE:
+            rs = cpu(topo, cpn, cb, T.REDUCE_SCATTER, seed)
             t, m = r.event_trace(0)
-            assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches)
+            assert np.array_equal(t, rs.event_times) and np.array_equal(m, rs.event_matches), name
+
+
+def test_event_trace_of_a_reversed_pass_two_npus(stream):
+    """Two NPUs, one chunk each, links of cost 7 and 3: the reversed pass of the
+    Reduce-Scatter matches both links in its sweep at t = 0, sweeps again (matching nothing)
+    when the faster link has delivered at t = 3, and ends at t = 7."""
+    topo = T.from_edge_list(2, [(0, 1, 7, 0), (1, 0, 3, 0)])
+    ref = cpu(topo, 1, 1, T.REDUCE_SCATTER, 0)
+    assert ref.event_times.tolist() == [0, 3] and ref.event_matches.tolist() == [2, 0]
+    for mode in (1, 2):
+        with gpu(topo, 1, 1, T.REDUCE_SCATTER, 0, stream, launch_mode=mode) as r:
+            assert r.collective_time_ps == 7
+            t, m = r.event_trace(0)
+            assert t.tolist() == [0, 3] and m.tolist() == [2, 0]
 
 
 def test_single_npu(stream):
@@ -245,9 +266,8 @@ def test_homogeneous_ten_one_launch_per_span_bit_exact(name, mk, cpn, coll, stre
     for mode in (3, 1):
         with gpu(topo, cpn, cb, coll, 9, stream, launch_mode=mode) as r:
             assert_same(r, ref, f"{name} mode {mode}")
-            if coll == T.ALL_GATHER:
-                t, m = r.event_trace(0)
-                assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches)
+            t, m = r.event_trace(r.num_passes - 1)
+            assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches)
 
 
 def test_homogeneous_ten_mode_limits_and_errors(stream):
