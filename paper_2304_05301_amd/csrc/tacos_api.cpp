@@ -208,7 +208,7 @@ std::vector<uint32_t> cluster_order(uint32_t N, uint32_t L, const std::vector<ui
 // The graph of one pass orientation on the device: in-lists (ascending link id, or
 // cheapest first), out-neighbour lists, link destinations, processing order.
 struct PassGraph {
-  uint32_t N = 0, L = 0;
+  uint32_t N = 0, L = 0, max_deg = 0;
   DevBuf in_ptr, in_link, in_src, in_rec, pos_dst, slot_rec, out_ptr, out_dst;
   std::vector<uint32_t> h_order, h_in_ptr;  // host copies, for dropping complete destinations
 };
@@ -259,6 +259,7 @@ void build_pass_graph(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc,
   for (uint32_t j = 0; j < L; ++j) pos_dst[j] = pdst[in_link[j]];
   g.h_order = order;
   g.h_in_ptr = in_ptr;
+  for (uint32_t d = 0; d < N; ++d) g.max_deg = std::max(g.max_deg, in_ptr[d + 1] - in_ptr[d]);
   upload(g.slot_rec, slot_rec.data(), slot_rec.size(), stream);
   upload(g.pos_dst, pos_dst.data(), pos_dst.size(), stream);
   upload(g.in_ptr, in_ptr.data(), in_ptr.size(), stream);
@@ -286,6 +287,7 @@ PassDev make_pass_dev(const PassGraph &g, const DevBuf &d_cost, uint32_t cpn, ui
   p.N = g.N; p.L = g.L; p.cpn = cpn; p.NP = NP; p.C = C; p.root = root; p.phase = phase;
   p.seed_lo = (uint32_t)(seed & 0xFFFFFFFFull); p.seed_hi = (uint32_t)(seed >> 32);
   p.row_words = NP * 128u; p.reversed = reversed ? 1u : 0u;
+  p.max_deg = g.max_deg;
   p.held = held;
   p.in_ptr = g.in_ptr.as<uint32_t>(); p.in_link = g.in_link.as<uint32_t>();
   p.in_src = g.in_src.as<uint32_t>(); p.pos_dst = g.pos_dst.as<uint32_t>();

@@ -58,6 +58,7 @@ struct PassDev {
   uint32_t seed_lo, seed_hi;
   uint32_t row_words;              // 64-bit words per row = NP*128
   uint32_t reversed;               // 1: schedule rows are keyed by ARRIVAL event
+  uint32_t max_deg;                // largest in-degree of the pass orientation
   unsigned long long *held;        // [N][row_words]
   const uint32_t *in_ptr;          // [N+1]
   const uint32_t *in_link;         // [L] incoming links of each NPU, ascending link id

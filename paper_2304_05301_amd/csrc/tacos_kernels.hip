@@ -356,6 +356,8 @@ __device__ __forceinline__ u32 draw_chunks(const u64 *__restrict__ held, u32 row
       const u64 above = __ballot(incl > k);
       const u32 ln = (u32)__ffsll((long long)above) - 1u;
       k -= read_lane(incl - cnt, ln);
+      // the owning lane's word, by a scalar walk over its in-lane prefixes (a vector search of
+      // every lane's own words was measured: 2 % slower, the vector unit is the busier one here)
       u32 idx = 0, before = 0;
 #pragma unroll
       for (int i = 0; i < NW - 1; ++i) {
@@ -537,16 +539,238 @@ __device__ __forceinline__ void philox4x32_10_words01(u32 c0, u32 c1, u32 c2, u3
 //   serv = need & OR_{free links} held[src];  c = (r0 mod |serv|)-th smallest of serv;
 //   holders = free links whose source holds c (list order);  link = holders[r1 mod n]
 //   (or the first holder when the list is sorted cheapest-first),
-// with (r0, r1) = words 0, 1 of Philox(d, event, phase + 2, step; seed).  The rows of the
-// free links are re-streamed (from L2) in every step.
+// with (r0, r1) = words 0, 1 of Philox(d, event, phase + 2, step; seed).
+//
+// Both cores below take the links of the destination one per lane (s: the lane's link's
+// source NPU; free_links: the lanes whose link is free) and the need row in LDS, and return
+// the chunk the lane's link carries or kNone.
+
+// Any in-degree up to 64: the rows of the free links are re-streamed (from L2) in every step.
 template <int NP>
+__device__ __forceinline__ u32 draw_pairs_streamed(const u64 *__restrict__ held, u32 row_words, u32 s, u64 free_links,
+                                                   u32 d, u32 event, u32 phase2, u32 seed_lo, u32 seed_hi,
+                                                   bool first_holder, uint4 *need_lds, int lane)
+{
+  constexpr int NW = 2 * NP;
+  constexpr int NDW = 4 * NP;
+  typedef RowRegs<NDW> RT;
+  u32 res = kNone;
+  for (u32 step = 0; free_links; ++step) {
+    // serv = need & (OR of the rows of the free links), in registers
+    typename RT::A acc_a = {};
+    typename RT::B acc_b = {};
+    u64 todo = free_links;
+    while (todo) {
+      const u32 b = (u32)__ffsll((long long)todo) - 1u;
+      todo &= todo - 1ull;
+      const u32 src = read_lane(s, b);
+      const uint4 *sp = reinterpret_cast<const uint4 *>(held + (u64)src * row_words) + lane;
+      static_for<0, NP>([&](auto I) {
+        constexpr int i = decltype(I)::value;
+        const uint4 v = sp[i * 64];
+        RT::template set<4 * i>(acc_a, acc_b, RT::template get<4 * i>(acc_a, acc_b) | v.x);
+        RT::template set<4 * i + 1>(acc_a, acc_b, RT::template get<4 * i + 1>(acc_a, acc_b) | v.y);
+        RT::template set<4 * i + 2>(acc_a, acc_b, RT::template get<4 * i + 2>(acc_a, acc_b) | v.z);
+        RT::template set<4 * i + 3>(acc_a, acc_b, RT::template get<4 * i + 3>(acc_a, acc_b) | v.w);
+      });
+    }
+    u32 pre[NW];
+    u32 cnt = 0;
+    static_for<0, NP>([&](auto I) {
+      constexpr int i = decltype(I)::value;
+      const uint4 nd = need_lds[i * 64 + lane];
+      const u32 c0 = RT::template get<4 * i>(acc_a, acc_b) & nd.x;
+      const u32 c1 = RT::template get<4 * i + 1>(acc_a, acc_b) & nd.y;
+      const u32 c2 = RT::template get<4 * i + 2>(acc_a, acc_b) & nd.z;
+      const u32 c3 = RT::template get<4 * i + 3>(acc_a, acc_b) & nd.w;
+      RT::template set<4 * i>(acc_a, acc_b, c0); RT::template set<4 * i + 1>(acc_a, acc_b, c1);
+      RT::template set<4 * i + 2>(acc_a, acc_b, c2); RT::template set<4 * i + 3>(acc_a, acc_b, c3);
+      cnt = popc_acc(c0, cnt);
+      cnt = popc_acc(c1, cnt);
+      pre[2 * i] = cnt;
+      cnt = popc_acc(c2, cnt);
+      cnt = popc_acc(c3, cnt);
+      pre[2 * i + 1] = cnt;
+    });
+    const u32 incl = wave_inclusive_scan(cnt);
+    const u32 pop = read_lane(incl, 63);
+    if (pop == 0) break;  // no free link can serve any missing chunk
+    u32 r0, r1;
+    philox4x32_10_words01(d, event, phase2, step, seed_lo, seed_hi, r0, r1);
+    u32 k = r0 % pop;
+    const u64 above = __ballot(incl > k);
+    const u32 ln = (u32)__ffsll((long long)above) - 1u;
+    k -= read_lane(incl - cnt, ln);
+    u32 idx = 0, before = 0;
+#pragma unroll
+    for (int i = 0; i < NW - 1; ++i) {
+      const u32 pi = read_lane(pre[i], ln);
+      const u32 le = ((k - pi) >> 31) ^ 1u;
+      idx += le;
+      const u32 cand_before = pi * le;
+      before = cand_before > before ? cand_before : before;
+    }
+    const u32 lo = read_lane(RT::at(acc_a, acc_b, 2u * idx), ln);
+    const u32 hi = read_lane(RT::at(acc_a, acc_b, 2u * idx + 1u), ln);
+    const u32 bit = kth_set_bit_wave(lo, hi, k - before);
+    const u32 chunk = ((ln * (u32)NW + idx) << 6) + bit;
+    // which free links' sources hold the chunk: lane j tests its own source's dword
+    const u32 dword = ((idx >> 1) * 128u + ln * 2u + (idx & 1u)) * 2u + (bit >> 5);
+    bool holds = false;
+    if ((free_links >> lane) & 1ull) {
+      const u32 wv = reinterpret_cast<const u32 *>(held + (u64)s * row_words)[dword];
+      holds = (wv >> (bit & 31u)) & 1u;
+    }
+    const u64 holders = __ballot(holds);
+    u32 pick;
+    if (first_holder) pick = (u32)__ffsll((long long)holders) - 1u;
+    else pick = kth_set_bit_wave((u32)holders, (u32)(holders >> 32), r1 % (u32)__popcll(holders));
+    if ((u32)lane == pick) res = chunk;
+    free_links &= ~(1ull << pick);
+    if (lane == 0) {  // now in flight to d
+      u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(idx >> 1) * 64u + ln]) + ((idx & 1u) * 2u + (bit >> 5));
+      *ptr &= ~(1u << (bit & 31u));
+    }
+  }
+  return res;
+}
+
+// In-degree <= DEG (the links sit in lanes 0 .. DEG-1): the rows of all free links are read
+// ONCE and stay in registers (DEG planes of a lane's share of a row), so that a step is
+// register and LDS work only: OR of the planes & need, selection, and the holders of the chosen
+// chunk from one dword of every plane; the plane of the link that was used is cleared.
+template <int NP, int DEG>
+__device__ __forceinline__ u32 draw_pairs_planes(const u64 *__restrict__ held, u32 row_words, u32 s, u64 free_links,
+                                                 u32 d, u32 event, u32 phase2, u32 seed_lo, u32 seed_hi,
+                                                 bool first_holder, uint4 *need_lds, int lane)
+{
+  constexpr int NW = 2 * NP;
+  constexpr int NDW = 4 * NP;
+  typedef RowRegs<NDW> RT;
+  u32 res = kNone;
+  typename RT::A pa[DEG];
+  typename RT::B pb[DEG];
+  static_for<0, DEG>([&](auto J) {
+    constexpr int j = decltype(J)::value;
+    pa[j] = typename RT::A{};
+    pb[j] = typename RT::B{};
+    if ((free_links >> j) & 1ull) {
+      const uint4 *sp = reinterpret_cast<const uint4 *>(held + (u64)read_lane(s, (u32)j) * row_words) + lane;
+      static_for<0, NP>([&](auto I) {
+        constexpr int i = decltype(I)::value;
+        const uint4 v = sp[i * 64];
+        RT::template set<4 * i>(pa[j], pb[j], v.x); RT::template set<4 * i + 1>(pa[j], pb[j], v.y);
+        RT::template set<4 * i + 2>(pa[j], pb[j], v.z); RT::template set<4 * i + 3>(pa[j], pb[j], v.w);
+      });
+    }
+  });
+  // the random words of all steps at once: lane i computes the block of step i (a destination
+  // takes at most one step per link, DEG <= 64), instead of one scalar block per step; word 1
+  // is reduced modulo every possible number of holders 1 .. DEG here (divisions by constants),
+  // four bits each
+  u32 rw0, rw1;
+  philox4x32_10_words01(d, event, phase2, (u32)lane, seed_lo, seed_hi, rw0, rw1);
+  static_assert(DEG <= 8, "the packed remainders of word 1 take four bits per holder count");
+  u32 rmods = 0;
+  static_for<1, DEG + 1>([&](auto M) {
+    constexpr u32 m = (u32)decltype(M)::value;
+    rmods |= (rw1 % m) << (4u * (m - 1u));
+  });
+  for (u32 step = 0; free_links; ++step) {
+    // serv = need & (OR of the planes), with the running in-lane candidate counts
+    typename RT::A sa;
+    typename RT::B sb;
+    u32 pre[NW];
+    u32 cnt = 0;
+    static_for<0, NP>([&](auto I) {
+      constexpr int i = decltype(I)::value;
+      const uint4 nd = need_lds[i * 64 + lane];
+      u32 o[4] = {0, 0, 0, 0};
+      static_for<0, DEG>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        o[0] |= RT::template get<4 * i>(pa[j], pb[j]);
+        o[1] |= RT::template get<4 * i + 1>(pa[j], pb[j]);
+        o[2] |= RT::template get<4 * i + 2>(pa[j], pb[j]);
+        o[3] |= RT::template get<4 * i + 3>(pa[j], pb[j]);
+      });
+      const u32 c0 = o[0] & nd.x, c1 = o[1] & nd.y, c2 = o[2] & nd.z, c3 = o[3] & nd.w;
+      RT::template set<4 * i>(sa, sb, c0); RT::template set<4 * i + 1>(sa, sb, c1);
+      RT::template set<4 * i + 2>(sa, sb, c2); RT::template set<4 * i + 3>(sa, sb, c3);
+      cnt = popc_acc(c0, cnt);
+      cnt = popc_acc(c1, cnt);
+      pre[2 * i] = cnt;
+      cnt = popc_acc(c2, cnt);
+      cnt = popc_acc(c3, cnt);
+      pre[2 * i + 1] = cnt;
+    });
+    const u32 incl = wave_inclusive_scan(cnt);
+    const u32 pop = read_lane(incl, 63);
+    if (pop == 0) break;  // no free link can serve any missing chunk
+    const u32 k = read_lane(rw0, step) % pop;
+    const u64 above = __ballot(incl > k);
+    const u32 ln = (u32)__ffsll((long long)above) - 1u;
+    // Every lane looks for rank k - (candidates in the lanes below it) among its own words with
+    // vector compares; only the owning lane's answer is read.  (With three wavefronts per SIMD
+    // the scalar unit's work does not hide behind the vector unit's: a walk driven by readlane
+    // costs six scalar instructions per word.)
+    const u32 kl = k - (incl - cnt);
+    u32 idxv = 0, befv = 0;
+#pragma unroll
+    for (int i = 0; i < NW - 1; ++i) {
+      const bool le = pre[i] <= kl;
+      idxv += le ? 1u : 0u;
+      befv = le ? pre[i] : befv;
+    }
+    const u32 idx = read_lane(idxv, ln);
+    const u32 k2 = read_lane(kl - befv, ln);
+    const u32 lo = read_lane(RT::at(sa, sb, 2u * idx), ln);
+    const u32 hi = read_lane(RT::at(sa, sb, 2u * idx + 1u), ln);
+    const u32 bit = kth_set_bit_wave(lo, hi, k2);
+    const u32 chunk = ((ln * (u32)NW + idx) << 6) + bit;
+    // holders: the planes (free links) that have the chunk's bit; every lane forms the mask from
+    // its own dword dw of every plane, the owning lane's is read
+    const u32 dw = 2u * idx + (bit >> 5);
+    u32 hv = 0;
+    static_for<0, DEG>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      hv |= ((RT::at(pa[j], pb[j], dw) >> (bit & 31u)) & 1u) << j;
+    });
+    const u32 holders = read_lane(hv, ln);
+    u32 pick;
+    if (first_holder) pick = (u32)__ffs((int)holders) - 1u;
+    else {
+      u32 m = holders;
+      const u32 q0 = (read_lane(rmods, step) >> (4u * ((u32)__popc(holders) - 1u))) & 15u;
+      for (u32 q = q0; q; --q) m &= m - 1u;  // drop the q lowest holders
+      pick = (u32)__ffs((int)m) - 1u;
+    }
+    if ((u32)lane == pick) res = chunk;
+    free_links &= ~(1ull << pick);
+    static_for<0, DEG>([&](auto J) {  // a used link serves nothing more
+      constexpr int j = decltype(J)::value;
+      if (pick == (u32)j) {
+        asm volatile("" ::: "memory");  // keeps this a (wave-uniform) branch: one plane is cleared, not all selected
+        pa[j] = typename RT::A{};
+        pb[j] = typename RT::B{};
+      }
+    });
+    if (lane == 0) {  // now in flight to d
+      u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(idx >> 1) * 64u + ln]) + ((idx & 1u) * 2u + (bit >> 5));
+      *ptr &= ~(1u << (bit & 31u));
+    }
+  }
+  return res;
+}
+
+// The postcondition-centric matching of destination d at span `event` (time t): set-up of the
+// need row, one of the two cores above, and the link state of the matched links.  Returns (per
+// lane) the end time of the transfer on the lane's link, for the next-event reduction.
+template <int NP, int DEG>
 __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, u32 jb, u32 je, u32 event, u64 t,
                                                        u32 *__restrict__ sched_row, int lane, uint4 *need_lds,
                                                        bool first_holder)
 {
   constexpr int NW = 2 * NP;
-  constexpr int NDW = 4 * NP;
-  typedef RowRegs<NDW> RT;
   Ctl *ctl = p.ctl;
   u64 my_min = kInf;
   const bool valid = jb + lane < je;
@@ -558,7 +782,7 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
     cr = p.carry[j];
     l = rec.x; s = rec.y; cs = ((u64)rec.w << 32) | rec.z;
   }
-  u64 free_links = __ballot(valid && cr == kNone);
+  const u64 free_links = __ballot(valid && cr == kNone);
   u32 res = kNone;
 
   if (free_links) {
@@ -581,82 +805,13 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
       u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(iw >> 1) * 64u + ln]) + ((iw & 1u) * 2u + ((cr >> 5) & 1u));
       atomicAnd(ptr, ~(1u << (cr & 31u)));
     }
-    for (u32 step = 0; free_links; ++step) {
-      // serv = need & (OR of the rows of the free links), in registers
-      typename RT::A acc_a = {};
-      typename RT::B acc_b = {};
-      u64 todo = free_links;
-      while (todo) {
-        const u32 b = (u32)__ffsll((long long)todo) - 1u;
-        todo &= todo - 1ull;
-        const u32 src = read_lane(s, b);
-        const uint4 *sp = reinterpret_cast<const uint4 *>(p.held + (u64)src * p.row_words) + lane;
-        static_for<0, NP>([&](auto I) {
-          constexpr int i = decltype(I)::value;
-          const uint4 v = sp[i * 64];
-          RT::template set<4 * i>(acc_a, acc_b, RT::template get<4 * i>(acc_a, acc_b) | v.x);
-          RT::template set<4 * i + 1>(acc_a, acc_b, RT::template get<4 * i + 1>(acc_a, acc_b) | v.y);
-          RT::template set<4 * i + 2>(acc_a, acc_b, RT::template get<4 * i + 2>(acc_a, acc_b) | v.z);
-          RT::template set<4 * i + 3>(acc_a, acc_b, RT::template get<4 * i + 3>(acc_a, acc_b) | v.w);
-        });
-      }
-      u32 pre[NW];
-      u32 cnt = 0;
-      static_for<0, NP>([&](auto I) {
-        constexpr int i = decltype(I)::value;
-        const uint4 nd = need_lds[i * 64 + lane];
-        const u32 c0 = RT::template get<4 * i>(acc_a, acc_b) & nd.x;
-        const u32 c1 = RT::template get<4 * i + 1>(acc_a, acc_b) & nd.y;
-        const u32 c2 = RT::template get<4 * i + 2>(acc_a, acc_b) & nd.z;
-        const u32 c3 = RT::template get<4 * i + 3>(acc_a, acc_b) & nd.w;
-        RT::template set<4 * i>(acc_a, acc_b, c0); RT::template set<4 * i + 1>(acc_a, acc_b, c1);
-        RT::template set<4 * i + 2>(acc_a, acc_b, c2); RT::template set<4 * i + 3>(acc_a, acc_b, c3);
-        cnt = popc_acc(c0, cnt);
-        cnt = popc_acc(c1, cnt);
-        pre[2 * i] = cnt;
-        cnt = popc_acc(c2, cnt);
-        cnt = popc_acc(c3, cnt);
-        pre[2 * i + 1] = cnt;
-      });
-      const u32 incl = wave_inclusive_scan(cnt);
-      const u32 pop = read_lane(incl, 63);
-      if (pop == 0) break;  // no free link can serve any missing chunk
-      u32 r0, r1;
-      philox4x32_10_words01(d, event, p.phase + 2u, step, p.seed_lo, p.seed_hi, r0, r1);
-      u32 k = r0 % pop;
-      const u64 above = __ballot(incl > k);
-      const u32 ln = (u32)__ffsll((long long)above) - 1u;
-      k -= read_lane(incl - cnt, ln);
-      u32 idx = 0, before = 0;
-#pragma unroll
-      for (int i = 0; i < NW - 1; ++i) {
-        const u32 pi = read_lane(pre[i], ln);
-        const u32 le = ((k - pi) >> 31) ^ 1u;
-        idx += le;
-        const u32 cand_before = pi * le;
-        before = cand_before > before ? cand_before : before;
-      }
-      const u32 lo = read_lane(RT::at(acc_a, acc_b, 2u * idx), ln);
-      const u32 hi = read_lane(RT::at(acc_a, acc_b, 2u * idx + 1u), ln);
-      const u32 bit = kth_set_bit_wave(lo, hi, k - before);
-      const u32 chunk = ((ln * (u32)NW + idx) << 6) + bit;
-      // which free links' sources hold the chunk: lane j tests its own source's dword
-      const u32 dword = ((idx >> 1) * 128u + ln * 2u + (idx & 1u)) * 2u + (bit >> 5);
-      bool holds = false;
-      if ((free_links >> lane) & 1ull) {
-        const u32 wv = reinterpret_cast<const u32 *>(p.held + (u64)s * p.row_words)[dword];
-        holds = (wv >> (bit & 31u)) & 1u;
-      }
-      const u64 holders = __ballot(holds);
-      u32 pick;
-      if (first_holder) pick = (u32)__ffsll((long long)holders) - 1u;
-      else pick = kth_set_bit_wave((u32)holders, (u32)(holders >> 32), r1 % (u32)__popcll(holders));
-      if ((u32)lane == pick) res = chunk;
-      free_links &= ~(1ull << pick);
-      if (lane == 0) {  // now in flight to d
-        u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(idx >> 1) * 64u + ln]) + ((idx & 1u) * 2u + (bit >> 5));
-        *ptr &= ~(1u << (bit & 31u));
-      }
+    if (need_any) {
+      if (DEG > 0 && je - jb <= (u32)(DEG > 0 ? DEG : 1))
+        res = draw_pairs_planes<NP, (DEG > 0 ? DEG : 1)>(p.held, p.row_words, s, free_links, d, event, p.phase + 2u,
+                                                         p.seed_lo, p.seed_hi, first_holder, need_lds, lane);
+      else
+        res = draw_pairs_streamed<NP>(p.held, p.row_words, s, free_links, d, event, p.phase + 2u, p.seed_lo,
+                                      p.seed_hi, first_holder, need_lds, lane);
     }
   }
   if (valid) {
@@ -687,8 +842,11 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
 // (Five-piece rows, the 40,960-NPU workloads: the register allocator lands two registers
 // above the 80 that allow 6 wavefronts per SIMD; asking for 6 costs no spill and is 7 %
 // faster.  7 or 8 wavefronts per SIMD spill and are slower.)
-template <int NP, int MODE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NP == 5 && MODE == 0 ? 6 : 1)))
+// DEG (postcondition-centric modes): in-degrees up to DEG keep the rows of a destination's free
+// links in registers (draw_pairs_planes); 0 = always re-stream them.
+template <int NP, int MODE, int DEG>
+__global__ __launch_bounds__(256)
+__attribute__((amdgpu_waves_per_eu(MODE == 0 ? (NP == 5 ? 6 : 1) : (4 * NP * DEG >= 96 ? 3 : 1))))
 void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
 {
   const int lane = threadIdx.x & 63;
@@ -709,7 +867,7 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
   u64 my_min;
   if constexpr (MODE == 0) my_min = match_destination<NP, false>(p, d, jb, je, event, t, sched_row, lane, my_need);
-  else my_min = match_destination_pairs<NP>(p, d, jb, je, event, t, sched_row, lane, my_need, MODE == 2);
+  else my_min = match_destination_pairs<NP, DEG>(p, d, jb, je, event, t, sched_row, lane, my_need, MODE == 2);
 
   // a8: next span = earliest end of a transfer in flight (min over all destinations)
   const u64 m = wave_min64(my_min);
@@ -1184,8 +1342,8 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
         (void)match_destination<NP, true>(q, d, jb, je, e, t, p.reversed ? nullptr : row, lane,
                                           s_need + wave * NP * 64);
       else
-        (void)match_destination_pairs<NP>(q, d, jb, je, e, t, p.reversed ? nullptr : row, lane,
-                                          s_need + wave * NP * 64, MODE == 2);
+        (void)match_destination_pairs<NP, 8>(q, d, jb, je, e, t, p.reversed ? nullptr : row, lane,
+                                             s_need + wave * NP * 64, MODE == 2);
     }
     lds_barrier();
     // ---- next span = earliest end of a transfer in flight (a8), reduced in LDS
@@ -1428,21 +1586,41 @@ void launch_arrive(const PassDev &p, u32 event, u64 *event_time_slot, u32 *sched
                      event_time_slot, sched_row);
 }
 
-template <int MODE> static void launch_match_mode(const PassDev &p, u32 event, u32 *sched_row, hipStream_t s)
+// Shapes whose register planes fit without spilling at three or more wavefronts per SIMD
+// (a lane's share of a row is 4*NP dwords per plane): measured from the compiler's register
+// counts; the other shapes re-stream the rows.
+constexpr bool planes_fit(int np, int deg) { return (deg == 4 && np <= 6) || (deg == 6 && np <= 5) || (deg == 8 && np <= 4); }
+
+template <int MODE, int DEG> static void launch_match_mode(const PassDev &p, u32 event, u32 *sched_row, hipStream_t s)
 {
   const u32 n_wg = (p.n_slots + 3u) / 4u;
   const dim3 grid(8u * ((n_wg + 7u) / 8u + (n_wg == 0u)), 1, 1), block(256);
+#define TACOS_MATCH(NP_)                                                                               \
+  if constexpr (planes_fit(NP_, DEG))                                                                  \
+    hipLaunchKernelGGL((match_kernel<NP_, MODE, DEG>), grid, block, 0, s, p, event, sched_row);        \
+  else                                                                                                 \
+    hipLaunchKernelGGL((match_kernel<NP_, MODE, 0>), grid, block, 0, s, p, event, sched_row)
   switch (p.NP) {
-    case 1: hipLaunchKernelGGL((match_kernel<1, MODE>), grid, block, 0, s, p, event, sched_row); break;
-    case 2: hipLaunchKernelGGL((match_kernel<2, MODE>), grid, block, 0, s, p, event, sched_row); break;
-    case 3: hipLaunchKernelGGL((match_kernel<3, MODE>), grid, block, 0, s, p, event, sched_row); break;
-    case 4: hipLaunchKernelGGL((match_kernel<4, MODE>), grid, block, 0, s, p, event, sched_row); break;
-    case 5: hipLaunchKernelGGL((match_kernel<5, MODE>), grid, block, 0, s, p, event, sched_row); break;
-    case 6: hipLaunchKernelGGL((match_kernel<6, MODE>), grid, block, 0, s, p, event, sched_row); break;
-    case 7: hipLaunchKernelGGL((match_kernel<7, MODE>), grid, block, 0, s, p, event, sched_row); break;
-    case 8: hipLaunchKernelGGL((match_kernel<8, MODE>), grid, block, 0, s, p, event, sched_row); break;
+    case 1: TACOS_MATCH(1); break;
+    case 2: TACOS_MATCH(2); break;
+    case 3: TACOS_MATCH(3); break;
+    case 4: TACOS_MATCH(4); break;
+    case 5: TACOS_MATCH(5); break;
+    case 6: TACOS_MATCH(6); break;
+    case 7: TACOS_MATCH(7); break;
+    case 8: TACOS_MATCH(8); break;
     default: break;  // rejected by the host before any launch
   }
+#undef TACOS_MATCH
+}
+
+// postcondition-centric: the register-plane variant that covers the largest in-degree of the pass
+template <int MODE> static void launch_match_pairs(const PassDev &p, u32 event, u32 *sched_row, hipStream_t s)
+{
+  if (p.max_deg <= 4) launch_match_mode<MODE, 4>(p, event, sched_row, s);
+  else if (p.max_deg <= 6) launch_match_mode<MODE, 6>(p, event, sched_row, s);
+  else if (p.max_deg <= 8) launch_match_mode<MODE, 8>(p, event, sched_row, s);
+  else launch_match_mode<MODE, 0>(p, event, sched_row, s);
 }
 
 void launch_match(const PassDev &p, u32 event, u32 *sched_row, u32 mode, hipStream_t s)
@@ -1457,9 +1635,9 @@ void launch_match(const PassDev &p, u32 event, u32 *sched_row, u32 mode, hipStre
     hipLaunchKernelGGL(match_kernel_streamed, grid, block, lds, s, p, event, sched_row);
     return;
   }
-  if (mode == 0) launch_match_mode<0>(p, event, sched_row, s);
-  else if (mode == 1) launch_match_mode<1>(p, event, sched_row, s);
-  else launch_match_mode<2>(p, event, sched_row, s);
+  if (mode == 0) launch_match_mode<0, 0>(p, event, sched_row, s);
+  else if (mode == 1) launch_match_pairs<1>(p, event, sched_row, s);
+  else launch_match_pairs<2>(p, event, sched_row, s);
 }
 
 void launch_uniform_init(const PassDev &p, const UniformDev &u, uint32_t mode, hipStream_t s)
