@@ -43,6 +43,7 @@ def library_source_hash():
     import hashlib
     h = hashlib.sha256()
     for rel in ("paper_2304_05301_amd/csrc/tacos_kernels.hip", "paper_2304_05301_amd/csrc/tacos_api.cpp",
+                "paper_2304_05301_amd/csrc/tacos_report.hip",
                 "paper_2304_05301_amd/csrc/tacos_internal.h"):
         with open(os.path.join(ROOT, rel), "rb") as f:
             h.update(f.read())
@@ -175,11 +176,11 @@ def report_all(binding, T, stream, with_cpu):
         wall = time.perf_counter() - t0
         alg = algorithmic_bytes(r.num_xfers, topo.n_npus, topo.n_links, n_chunks)
         k_s = r.kernel_ms * 1e-3
-        # the paper's Ideal, bandwidth term only (collective size over the ingress bandwidth of the
-        # worst-connected NPU; the latency diameter is left out): efficiency = Ideal / collective time
-        from paper_2304_05301_amd import metrics
-        ideal = metrics.ideal_time_ps(topo.n_npus, w.chunks_per_npu, w.chunk_bytes, w.collective, topo.link_src,
-                                      topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B, with_diameter=False)
+        # the paper's Ideal, bandwidth term only (collective size over the bandwidth of the worst-
+        # connected NPU; the latency diameter is left out): efficiency = Ideal / collective time
+        ideal = binding.tacos_ideal_bound(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B,
+                                          w.chunks_per_npu, w.chunk_bytes, w.collective,
+                                          with_diameter=False)["bandwidth_term_ps"]
         row = {"idx": idx, "name": w.name, "npus": topo.n_npus, "links": topo.n_links, "spans": r.num_events,
                "eff": ideal / r.collective_time_ps,
                "matches": r.num_xfers, "T_ps": r.collective_time_ps, "wall_s": wall, "kernel_s": k_s,

@@ -23,6 +23,7 @@ import sys
 ROOT = os.path.dirname(os.path.abspath(__file__))
 PROFILES = os.path.join(ROOT, "profiles")
 LIB_SOURCES = ["paper_2304_05301_amd/csrc/tacos_kernels.hip", "paper_2304_05301_amd/csrc/tacos_api.cpp",
+                "paper_2304_05301_amd/csrc/tacos_report.hip",
                "paper_2304_05301_amd/csrc/tacos_internal.h"]
 
 
@@ -82,8 +83,13 @@ def main():
     ap.add_argument("--matching", type=int, default=0)
     ap.add_argument("--dir", default="gpurun_out", help="where the rocprofv3 output folders are")
     ap.add_argument("--commands", action="store_true", help="print the rocprofv3 commands and exit")
+    ap.add_argument("--out-dir", default=None,
+                    help="where to write the summaries (default: profiles/; on a box from which only one "
+                         "folder comes back, write there and copy the files into profiles/)")
     args = ap.parse_args()
     cmds = commands(args.workload, args.matching, args.dir)
+    out_dir = args.out_dir or PROFILES
+    os.makedirs(out_dir, exist_ok=True)
     if args.commands:
         for c in cmds.values():
             print(c)
@@ -174,12 +180,12 @@ def main():
                        f"{req / len(work) * 128 / 1e6:.1f} MB asked of L2, hit rate {100 * hit / (hit + miss):.1f} %")
             vals["l2_request_bytes_per_launch"] = f"{req / len(work) * 128:.0f}"
             vals["l2_hit_rate"] = f"{hit / (hit + miss):.4f}"
-        with open(os.path.join(PROFILES, f"{kernel}_{w.name}{variant}_traffic.txt"), "w") as f:
+        with open(os.path.join(out_dir, f"{kernel}_{w.name}{variant}_traffic.txt"), "w") as f:
             f.write(f"# per working launch of {kernel}: bytes beyond L2 (FETCH_SIZE + WRITE_SIZE, each scaled by a plain 1 GiB copy)\n"
                     f"# and bytes asked of L2 (TCC_REQ_sum x 128 B); written by bench_profile.py, see {kernel}_{w.name}{variant}.txt\n")
             for k, v in vals.items():
                 f.write(f"{k} = {v}\n")
-    path = os.path.join(PROFILES, f"{kernel}_{w.name}{variant}.txt")
+    path = os.path.join(out_dir, f"{kernel}_{w.name}{variant}.txt")
     with open(path, "w") as f:
         f.write("\n".join(out) + "\n")
     print("\n".join(out))

@@ -267,6 +267,58 @@ const char *tacos_last_error(void);
 int tacos_link_costs(const tacos_topology_t *topo, uint64_t chunk_bytes, uint64_t *cost_ps);
 
 /*
+ * Link busy times of pass `pass`: busy_ps[l] = (transfers link l carries) * cost[l] (host,
+ * [n_links], caller-owned, may be NULL), and their sum, minimum and maximum over the links
+ * (each may be NULL), computed on the device from the schedule.  The paper's link
+ * utilisation (section "Analysis of TACOS-Synthesized Algorithms") is the exact ratio
+ * busy_ps[l] / tacos_result_pass_time_ps(pass); the mean over the links is
+ * sum / (n_links * pass time).  TACOS_E_OVERFLOW if the sum does not fit 64 bits.
+ */
+int tacos_result_link_busy(const tacos_result_t *r, uint32_t pass, uint64_t *busy_ps, uint64_t *sum_ps,
+                           uint64_t *min_ps, uint64_t *max_ps);
+
+/*
+ * Switch unwinding (paper, section "TACOS for Switch-based Networks"): an n_npus-port switch
+ * whose ports have latency alpha_ps and reciprocal bandwidth beta_fs_per_B becomes, with
+ * degree d, the point-to-point topology in which NPU i has the d outgoing links to NPUs
+ * i+1 .. i+d (mod n_npus), each with the same alpha and with beta multiplied by d (the port
+ * bandwidth is shared).  Outputs (host, caller-owned): row_ptr [n_npus + 1], col_idx,
+ * alpha_out, beta_out [n_npus * degree each], in the library's CSR convention (rows by
+ * source, ascending destination inside a row), ready for tacos_topology_t.  Computed on the
+ * device.  TACOS_E_INVAL unless n_npus >= 2 and 1 <= degree <= n_npus - 1;
+ * TACOS_E_OVERFLOW if beta * degree does not fit 64 bits.
+ */
+int tacos_unwind_switch(uint32_t n_npus, uint32_t degree, uint64_t alpha_ps, uint64_t beta_fs_per_B,
+                        uint32_t *row_ptr, uint32_t *col_idx, uint64_t *alpha_out, uint64_t *beta_out);
+
+/*
+ * The paper's theoretically ideal collective time (section "Baseline Collective Algorithms
+ * and Synthesizers"):  Ideal = CollectiveSize * 2(n-1)/n / min_NPU(BW_NPU) + Diameter, in
+ * integer picoseconds.  CollectiveSize = n_npus * chunks_per_npu * chunk_bytes.  An
+ * All-Gather has every NPU receive CollectiveSize * (n-1)/n bytes: its bandwidth term is
+ * that over the smallest INGRESS bandwidth of an NPU (sum of 1/beta over its incoming
+ * links, kept as an exact fraction), rounded up to a picosecond; a Reduce-Scatter has every
+ * NPU send as much: the same over the smallest EGRESS bandwidth; an All-Reduce is the sum of
+ * the two (the paper's factor 2).  Diameter = the largest, over ordered pairs of NPUs, of the
+ * smallest sum of alpha along a path (computed if with_diameter != 0; needs n_npus <=
+ * TACOS_IDEAL_MAX_DIAMETER_NPUS, else TACOS_E_INVAL).  pass_*: per pass in schedule order
+ * (All-Reduce: Reduce-Scatter, All-Gather); bottleneck = the worst-connected NPU, lowest id
+ * on ties.  TACOS_E_UNREACHABLE if an NPU has no link on the side needed or is not reached;
+ * TACOS_E_OVERFLOW if a value does not fit 64 bits; TACOS_E_INVAL for rooted collectives.
+ */
+#define TACOS_IDEAL_MAX_DIAMETER_NPUS 8192u
+typedef struct {
+  uint64_t collective_bytes;
+  uint64_t bandwidth_term_ps;          /* sum over the passes                  */
+  uint64_t diameter_ps;                /* 0 if with_diameter == 0              */
+  uint64_t ideal_ps;                   /* bandwidth_term_ps + diameter_ps      */
+  uint64_t pass_bandwidth_term_ps[2];
+  uint32_t pass_bottleneck_npu[2];
+} tacos_ideal_t;
+int tacos_ideal_bound(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint64_t chunk_bytes,
+                      tacos_collective_t coll, uint32_t with_diameter, tacos_ideal_t *out);
+
+/*
  * tacos_link_costs for callers that cannot allocate device memory: code that runs where
  * hipMalloc is not allowed (while a HIP graph is being captured elsewhere in the process,
  * tight serving loops, harnesses that forbid allocation).  Same arguments, same results

@@ -36,6 +36,7 @@ EXPORTS = [
     "tacos_result_link_counts", "tacos_result_digest", "tacos_result_kernel_ms", "tacos_result_kernel_launches",
     "tacos_result_wall_ms", "tacos_result_device_bytes", "tacos_result_free",
     "tacos_strerror", "tacos_last_error", "tacos_link_costs", "tacos_link_costs_static", "tacos_version",
+    "tacos_result_link_busy", "tacos_unwind_switch", "tacos_ideal_bound",
 ]
 
 
@@ -50,6 +51,12 @@ class _Options(ctypes.Structure):
                 ("time_kernels", ctypes.c_uint32), ("launch_mode", ctypes.c_uint32),
                 ("link_order", ctypes.c_uint32), ("matching", ctypes.c_uint32),
                 ("root", ctypes.c_uint32)]
+
+
+class _Ideal(ctypes.Structure):
+    _fields_ = [("collective_bytes", ctypes.c_uint64), ("bandwidth_term_ps", ctypes.c_uint64),
+                ("diameter_ps", ctypes.c_uint64), ("ideal_ps", ctypes.c_uint64),
+                ("pass_bandwidth_term_ps", ctypes.c_uint64 * 2), ("pass_bottleneck_npu", ctypes.c_uint32 * 2)]
 
 
 class TacosError(RuntimeError):
@@ -95,6 +102,12 @@ def load() -> ctypes.CDLL:
     L.tacos_strerror.restype, L.tacos_strerror.argtypes = ctypes.c_char_p, [i32]
     L.tacos_last_error.restype, L.tacos_last_error.argtypes = ctypes.c_char_p, []
     L.tacos_link_costs.restype, L.tacos_link_costs.argtypes = i32, [ctypes.POINTER(_Topology), u64, vp]
+    L.tacos_result_link_busy.restype = i32
+    L.tacos_result_link_busy.argtypes = [vp, u32, vp, ctypes.POINTER(u64), ctypes.POINTER(u64), ctypes.POINTER(u64)]
+    L.tacos_unwind_switch.restype = i32
+    L.tacos_unwind_switch.argtypes = [u32, u32, u64, u64, vp, vp, vp, vp]
+    L.tacos_ideal_bound.restype = i32
+    L.tacos_ideal_bound.argtypes = [ctypes.POINTER(_Topology), u32, u64, i32, u32, ctypes.POINTER(_Ideal)]
     L.tacos_link_costs_static.restype = i32
     L.tacos_link_costs_static.argtypes = [ctypes.POINTER(_Topology), u64, vp]
     L.tacos_version.restype, L.tacos_version.argtypes = ctypes.c_char_p, []
@@ -197,6 +210,16 @@ class TacosResult:
             _raise(rc)
         return out
 
+    def link_busy(self, pass_index: int, n_links: int):
+        """tacos_result_link_busy: (busy_ps[n_links], sum, min, max) of one pass, python ints."""
+        out = np.zeros(int(n_links), dtype=np.uint64)
+        s, mn, mx = ctypes.c_uint64(0), ctypes.c_uint64(0), ctypes.c_uint64(0)
+        rc = load().tacos_result_link_busy(self._req(), pass_index, out.ctypes.data, ctypes.byref(s),
+                                           ctypes.byref(mn), ctypes.byref(mx))
+        if rc != TACOS_OK:
+            _raise(rc)
+        return out, int(s.value), int(mn.value), int(mx.value)
+
     def free(self):
         if self._h:
             load().tacos_result_free(self._h)
@@ -276,6 +299,38 @@ def tacos_link_costs_static(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, c
     if rc != TACOS_OK:
         _raise(rc)
     return out
+
+
+def tacos_unwind_switch(n_npus: int, degree: int, alpha_ps: int, beta_fs_per_B: int):
+    """tacos_unwind_switch of include/tacos.h: (row_ptr, col_idx, alpha_ps, beta_fs_per_B) arrays."""
+    n, d = int(n_npus), int(degree)
+    n_links = max(0, n * d) if n >= 2 and 1 <= d <= n - 1 else 1
+    row_ptr = np.zeros(max(n, 0) + 1, dtype=np.uint32)
+    col = np.zeros(n_links, dtype=np.uint32)
+    al = np.zeros(n_links, dtype=np.uint64)
+    be = np.zeros(n_links, dtype=np.uint64)
+    rc = load().tacos_unwind_switch(n, d, int(alpha_ps), int(beta_fs_per_B), row_ptr.ctypes.data, col.ctypes.data,
+                                    al.ctypes.data, be.ctypes.data)
+    if rc != TACOS_OK:
+        _raise(rc)
+    return row_ptr, col, al, be
+
+
+def tacos_ideal_bound(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B, chunks_per_npu, chunk_bytes, collective,
+                      with_diameter: bool = True) -> dict:
+    """tacos_ideal_bound of include/tacos.h as a dict of python ints."""
+    topo, keep = _topology_struct(n_npus, row_ptr, col_idx, alpha_ps, beta_fs_per_B)
+    out = _Ideal()
+    rc = load().tacos_ideal_bound(ctypes.byref(topo), int(chunks_per_npu), int(chunk_bytes), int(collective),
+                                  1 if with_diameter else 0, ctypes.byref(out))
+    del keep
+    if rc != TACOS_OK:
+        _raise(rc)
+    n_pass = 2 if collective == TACOS_ALL_REDUCE else 1
+    return {"collective_bytes": int(out.collective_bytes), "bandwidth_term_ps": int(out.bandwidth_term_ps),
+            "diameter_ps": int(out.diameter_ps), "ideal_ps": int(out.ideal_ps),
+            "pass_bandwidth_term_ps": [int(out.pass_bandwidth_term_ps[i]) for i in range(n_pass)],
+            "pass_bottleneck_npu": [int(out.pass_bottleneck_npu[i]) for i in range(n_pass)]}
 
 
 def tacos_version() -> str:

@@ -6,7 +6,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["tacos_kernels.hip", "tacos_api.cpp"]
+SOURCES = ["tacos_kernels.hip", "tacos_report.hip", "tacos_api.cpp"]
 OUT = os.path.join(HERE, "libtacos_hip.so")
 
 HIPCC_FLAGS = [

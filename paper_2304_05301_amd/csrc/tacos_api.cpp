@@ -1059,6 +1059,177 @@ int tacos_result_link_counts(const tacos_result_t *r, uint32_t pass, uint64_t *l
   return TACOS_OK;
 }
 
+int tacos_result_link_busy(const tacos_result_t *r, uint32_t pass, uint64_t *busy_ps, uint64_t *sum_ps,
+                           uint64_t *min_ps, uint64_t *max_ps)
+{
+  g_last_error.clear();
+  if (!r || pass >= r->passes.size()) return TACOS_E_INVAL;
+  const Pass &ps = r->passes[pass];
+  if (r->L == 0 || ps.segs.empty()) {
+    if (busy_ps) std::fill(busy_ps, busy_ps + r->L, 0ull);
+    if (sum_ps) *sum_ps = 0;
+    if (min_ps) *min_ps = 0;
+    if (max_ps) *max_ps = 0;
+    return TACOS_OK;
+  }
+  try {
+    int prev = 0;
+    HIP_TRY(hipGetDevice(&prev));
+    if (prev != r->device) HIP_TRY(hipSetDevice(r->device));
+    DevBuf d_counts((size_t)r->L * 8), d_busy((size_t)r->L * 8), d_out(3 * 8), d_flags(4);
+    HIP_TRY(hipMemset(d_counts.p, 0, (size_t)r->L * 8));
+    HIP_TRY(hipMemset(d_flags.p, 0, 4));
+    for (size_t k = 0; k < ps.segs.size(); ++k) {
+      const uint64_t first = (uint64_t)k * ps.rows_per_seg;
+      if (first >= ps.n_rows) break;
+      const uint32_t n = (uint32_t)std::min<uint64_t>(ps.rows_per_seg, ps.n_rows - first);
+      tacos::launch_link_counts(ps.segs[k].rows.as<uint32_t>(), n, ps.L, d_counts.as<unsigned long long>(), nullptr);
+    }
+    tacos::launch_link_busy(r->L, d_counts.as<unsigned long long>(), r->d_cost.as<unsigned long long>(),
+                            d_busy.as<unsigned long long>(), d_out.as<unsigned long long>(), d_flags.as<uint32_t>(),
+                            nullptr);
+    HIP_TRY(hipGetLastError());
+    uint64_t out3[3] = {0, 0, 0};
+    uint32_t flags = 0;
+    HIP_TRY(hipMemcpy(out3, d_out.p, sizeof out3, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(&flags, d_flags.p, 4, hipMemcpyDeviceToHost));
+    if (busy_ps) HIP_TRY(hipMemcpy(busy_ps, d_busy.p, (size_t)r->L * 8, hipMemcpyDeviceToHost));
+    if (prev != r->device) HIP_TRY(hipSetDevice(prev));
+    if (flags & tacos::kRepOverflow) return TACOS_E_OVERFLOW;
+    if (sum_ps) *sum_ps = out3[0];
+    if (min_ps) *min_ps = out3[1];
+    if (max_ps) *max_ps = out3[2];
+  } catch (const HipFail &f) {
+    return f.code;
+  } catch (const std::bad_alloc &) {
+    return TACOS_E_NOMEM;
+  }
+  return TACOS_OK;
+}
+
+int tacos_unwind_switch(uint32_t n_npus, uint32_t degree, uint64_t alpha_ps, uint64_t beta_fs_per_B,
+                        uint32_t *row_ptr, uint32_t *col_idx, uint64_t *alpha_out, uint64_t *beta_out)
+{
+  g_last_error.clear();
+  if (!row_ptr || !col_idx || !alpha_out || !beta_out || n_npus < 2 || degree < 1 || degree > n_npus - 1)
+    return TACOS_E_INVAL;
+  const uint64_t n_links = (uint64_t)n_npus * degree;
+  if (n_links > 0xFFFFFFFEull) return TACOS_E_INVAL;
+  if (beta_fs_per_B != 0 && degree > ~0ull / beta_fs_per_B) return TACOS_E_OVERFLOW;
+  int dev = 0;
+  const int rc = require_device(&dev);
+  if (rc != TACOS_OK) return rc;
+  try {
+    DevBuf d_ptr(((size_t)n_npus + 1) * 4), d_col(n_links * 4), d_alpha(n_links * 8), d_beta(n_links * 8);
+    tacos::launch_unwind_switch(n_npus, degree, alpha_ps, beta_fs_per_B * degree, d_ptr.as<uint32_t>(),
+                                d_col.as<uint32_t>(), d_alpha.as<unsigned long long>(),
+                                d_beta.as<unsigned long long>(), nullptr);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpy(row_ptr, d_ptr.p, ((size_t)n_npus + 1) * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(col_idx, d_col.p, n_links * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(alpha_out, d_alpha.p, n_links * 8, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(beta_out, d_beta.p, n_links * 8, hipMemcpyDeviceToHost));
+  } catch (const HipFail &f) {
+    return f.code;
+  } catch (const std::bad_alloc &) {
+    return TACOS_E_NOMEM;
+  }
+  return TACOS_OK;
+}
+
+int tacos_ideal_bound(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint64_t chunk_bytes,
+                      tacos_collective_t coll, uint32_t with_diameter, tacos_ideal_t *out)
+{
+  g_last_error.clear();
+  if (!out) return TACOS_E_INVAL;
+  int rc = validate(topo, chunks_per_npu, chunk_bytes, (int)coll, nullptr);
+  if (rc != TACOS_OK) return rc;
+  if (is_rooted((int)coll)) return TACOS_E_INVAL;
+  const uint32_t N = topo->n_npus, L = topo->n_links;
+  if (with_diameter && N > TACOS_IDEAL_MAX_DIAMETER_NPUS) {
+    g_last_error = "tacos_ideal_bound: the latency diameter is computed for at most TACOS_IDEAL_MAX_DIAMETER_NPUS NPUs";
+    return TACOS_E_INVAL;
+  }
+  // CollectiveSize and the bytes every NPU receives (sends): (n - 1) * chunks_per_npu * chunk_bytes
+  const unsigned __int128 size = (unsigned __int128)N * chunks_per_npu * chunk_bytes;
+  const unsigned __int128 moved = (unsigned __int128)(N - 1) * chunks_per_npu * chunk_bytes;
+  if (size >> 64) return TACOS_E_OVERFLOW;
+  tacos_ideal_t res{};
+  res.collective_bytes = (uint64_t)size;
+  if (N == 1) { *out = res; return TACOS_OK; }
+  if (L == 0) return TACOS_E_UNREACHABLE;
+  int dev = 0;
+  rc = require_device(&dev);
+  if (rc != TACOS_OK) return rc;
+  try {
+    // the links by destination (in-lists) next to the CSR by source: input marshalling
+    std::vector<uint32_t> src(L), in_ptr(N + 1, 0);
+    std::vector<uint64_t> in_beta(L);
+    for (uint32_t i = 0; i < N; ++i)
+      for (uint32_t l = topo->row_ptr[i]; l < topo->row_ptr[i + 1]; ++l) { src[l] = i; in_ptr[topo->col_idx[l] + 1]++; }
+    for (uint32_t d = 0; d < N; ++d) in_ptr[d + 1] += in_ptr[d];
+    {
+      std::vector<uint32_t> fill(in_ptr.begin(), in_ptr.end() - 1);
+      for (uint32_t l = 0; l < L; ++l) in_beta[fill[topo->col_idx[l]]++] = topo->beta_fs_per_B[l];
+    }
+    DevBuf d_in_ptr, d_in_beta, d_out_ptr, d_out_beta, d_P((size_t)N * 8), d_Q((size_t)N * 8), d_res(4 * 8), d_flags(4);
+    upload(d_in_ptr, in_ptr.data(), in_ptr.size(), nullptr);
+    upload(d_in_beta, reinterpret_cast<const unsigned long long *>(in_beta.data()), in_beta.size(), nullptr);
+    upload(d_out_ptr, topo->row_ptr, (size_t)N + 1, nullptr);
+    upload(d_out_beta, reinterpret_cast<const unsigned long long *>(topo->beta_fs_per_B), (size_t)L, nullptr);
+    HIP_TRY(hipMemset(d_flags.p, 0, 4));
+    HIP_TRY(hipMemset(d_res.p, 0, 4 * 8));
+    const bool rs = has_reversed_pass((int)coll), ag = has_forward_pass((int)coll);
+    int n_pass = 0;
+    unsigned long long *res_dev = d_res.as<unsigned long long>();
+    if (rs) {  // every NPU sends: egress side
+      tacos::launch_bandwidth_term(N, d_out_ptr.as<uint32_t>(), d_out_beta.as<unsigned long long>(), (uint64_t)moved,
+                                   d_P.as<unsigned long long>(), d_Q.as<unsigned long long>(), res_dev + 2 * n_pass,
+                                   d_flags.as<uint32_t>(), nullptr);
+      n_pass++;
+    }
+    if (ag) {  // every NPU receives: ingress side
+      tacos::launch_bandwidth_term(N, d_in_ptr.as<uint32_t>(), d_in_beta.as<unsigned long long>(), (uint64_t)moved,
+                                   d_P.as<unsigned long long>(), d_Q.as<unsigned long long>(), res_dev + 2 * n_pass,
+                                   d_flags.as<uint32_t>(), nullptr);
+      n_pass++;
+    }
+    HIP_TRY(hipGetLastError());
+    DevBuf d_src, d_dst, d_alpha, d_diam(8);
+    HIP_TRY(hipMemset(d_diam.p, 0, 8));
+    if (with_diameter) {
+      upload(d_src, src.data(), src.size(), nullptr);
+      upload(d_dst, topo->col_idx, (size_t)L, nullptr);
+      upload(d_alpha, reinterpret_cast<const unsigned long long *>(topo->alpha_ps), (size_t)L, nullptr);
+      HIP_TRY(tacos::launch_latency_diameter(N, L, d_src.as<uint32_t>(), d_dst.as<uint32_t>(),
+                                             d_alpha.as<unsigned long long>(), d_diam.as<unsigned long long>(),
+                                             d_flags.as<uint32_t>(), nullptr));
+    }
+    uint64_t host_res[4] = {0, 0, 0, 0}, diam = 0;
+    uint32_t flags = 0;
+    HIP_TRY(hipMemcpy(host_res, d_res.p, sizeof host_res, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(&diam, d_diam.p, 8, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(&flags, d_flags.p, 4, hipMemcpyDeviceToHost));
+    if (flags & tacos::kRepNoLink) return TACOS_E_UNREACHABLE;
+    if (flags & tacos::kRepOverflow) return TACOS_E_OVERFLOW;
+    for (int i = 0; i < n_pass; ++i) {
+      res.pass_bandwidth_term_ps[i] = host_res[2 * i];
+      res.pass_bottleneck_npu[i] = (uint32_t)host_res[2 * i + 1];
+      if (res.bandwidth_term_ps + host_res[2 * i] < res.bandwidth_term_ps) return TACOS_E_OVERFLOW;
+      res.bandwidth_term_ps += host_res[2 * i];
+    }
+    res.diameter_ps = diam;
+    if (res.bandwidth_term_ps + diam < diam) return TACOS_E_OVERFLOW;
+    res.ideal_ps = res.bandwidth_term_ps + diam;
+  } catch (const HipFail &f) {
+    return f.code;
+  } catch (const std::bad_alloc &) {
+    return TACOS_E_NOMEM;
+  }
+  *out = res;
+  return TACOS_OK;
+}
+
 void tacos_result_free(tacos_result_t *r)
 {
   if (!r) return;

@@ -168,4 +168,27 @@ void launch_start_span_counts(const uint32_t *rows, uint32_t first_row, uint32_t
 void launch_link_counts(const uint32_t *rows, uint32_t n_rows, uint32_t L, unsigned long long *counts,
                         hipStream_t s);
 
+// ---- reporting and input pre-processing (tacos_report.hip)
+// flags the kernels below OR into *flags
+constexpr uint32_t kRepOverflow = 1;  // a value does not fit 64 bits
+constexpr uint32_t kRepNoLink = 2;    // an NPU without a link on the side asked for / not reached
+// switch unwinding: CSR of the degree-d unwinding of an n-NPU switch (device pointers)
+void launch_unwind_switch(uint32_t n, uint32_t d, unsigned long long alpha, unsigned long long beta_d,
+                          uint32_t *row_ptr, uint32_t *col_idx, unsigned long long *alpha_out,
+                          unsigned long long *beta_out, hipStream_t s);
+// bandwidth term of the Ideal on one side (ptr/beta: every NPU's incoming or outgoing links):
+// out[0] = ceil(bytes / bandwidth of the worst-connected NPU) in ps, out[1] = that NPU;
+// P, Q: [N] scratch (the NPU bandwidths as fractions)
+void launch_bandwidth_term(uint32_t N, const uint32_t *ptr, const unsigned long long *beta, unsigned long long bytes,
+                           unsigned long long *P, unsigned long long *Q, unsigned long long *out, uint32_t *flags,
+                           hipStream_t s);
+// latency diameter: *diameter = max over ordered pairs of the smallest alpha sum of a path
+// (N * 8 + 16 bytes of LDS per workgroup: N <= 8192)
+hipError_t launch_latency_diameter(uint32_t N, uint32_t L, const uint32_t *src, const uint32_t *dst,
+                                   const unsigned long long *alpha, unsigned long long *diameter, uint32_t *flags,
+                                   hipStream_t s);
+// busy[l] = counts[l] * cost[l] (busy may be null); out[0..2] = sum, min, max over the links
+void launch_link_busy(uint32_t L, const unsigned long long *counts, const unsigned long long *cost,
+                      unsigned long long *busy, unsigned long long *out, uint32_t *flags, hipStream_t s);
+
 }  // namespace tacos
