@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.orc_max_threads.restype = ctypes.c_int
         L.orc_set_progress.restype = None
         L.orc_set_progress.argtypes = [ctypes.c_uint64]
+        L.orc_set_keep_windows.restype = None
+        L.orc_set_keep_windows.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
         _lib = L
     return _lib
 
@@ -120,6 +122,12 @@ def link_cost(alpha_ps: int, beta_fs_per_B: int, chunk_bytes: int):
 def set_progress(every: int) -> None:
     """Print a line on stderr every `every` matching sweeps (0 = silent)."""
     lib().orc_set_progress(int(every))
+
+
+def set_keep_windows(stride: int, block: int) -> None:
+    """Forward pass: store the blocks of `block` records starting at keep_first + k * stride
+    instead of one window (stride 0 = one window again)."""
+    lib().orc_set_keep_windows(int(stride), int(block))
 
 
 def max_threads() -> int:

@@ -167,11 +167,19 @@ typedef struct {
   uint64_t digest;
 } pass_out_t;
 
+/* Which records of a forward pass are stored (all are counted and digested): by default the
+ * window [keep_first, keep_first + keep_limit); with orc_set_keep_windows(stride, block),
+ * stride > 0, the blocks of `block` records that start at keep_first + k * stride, k = 0, 1, ...
+ * (samples spread over a run whose records do not fit memory). */
+static uint64_t g_keep_stride = 0, g_keep_block = 0;
+void orc_set_keep_windows(uint64_t stride, uint64_t block) { g_keep_stride = stride; g_keep_block = block; }
+
 static int push_rec(pass_out_t *o, uint64_t t, uint32_t link, uint32_t chunk)
 {
   o->n_total++;
   if (o->fwd) o->digest += orc_mix(t + o->t_off, link, chunk);
   if (o->n_total - 1 < o->keep_first || o->n >= o->keep_limit) return 1;
+  if (o->fwd && g_keep_stride && (o->n_total - 1 - o->keep_first) % g_keep_stride >= g_keep_block) return 1;
   if (o->n == o->cap) {
     uint64_t nc = o->cap ? o->cap * 2 : 1024;
     pass_rec_t *p = (pass_rec_t *)realloc(o->rec, nc * sizeof(pass_rec_t));

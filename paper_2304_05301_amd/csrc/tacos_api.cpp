@@ -112,6 +112,15 @@ struct Pass {
   uint32_t L = 0;
   uint32_t rows_per_seg = 1;
   std::vector<Segment> segs;
+  // Compact schedule (single-workgroup kernel): (link, chunk) records in span order instead of
+  // one row of L entries per span; while the pass runs, a segment's `rows` holds one u32 per
+  // span, the index of the span's first record.  After the pass: first / d_first
+  // [n_rows + 1] and d_time [n_rows] are the whole pass's, the segments are released.
+  bool compact = false;
+  DevBuf recs, d_first, d_time;
+  uint64_t n_rec = 0;
+  std::vector<uint32_t> first;
+  uint32_t row_stride() const { return compact ? 1u : L; }
   uint64_t T = 0;         // pass time
   uint64_t n_events = 0;  // matching sweeps
   uint64_t n_rows = 0;    // schedule rows that may hold records
@@ -374,22 +383,30 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   EventPool pool;
   auto row_slot = [&](uint64_t e, uint32_t **row, unsigned long long **tslot) {
     const uint64_t k = e / pass.rows_per_seg;
+    const size_t stride = pass.row_stride();
     while (pass.segs.size() <= k) {
       Segment s;
-      s.rows.alloc((size_t)pass.rows_per_seg * L * 4);
+      s.rows.alloc((size_t)pass.rows_per_seg * stride * 4);
       s.row_time.alloc((size_t)pass.rows_per_seg * 8);
       if (pass.prefill) HIP_TRY(hipMemsetAsync(s.rows.p, 0xFF, s.rows.bytes, stream));  // TACOS_NO_CHUNK
-      res.device_bytes += s.rows.bytes + s.row_time.bytes;
       pass.segs.push_back(std::move(s));
     }
     const uint64_t i = e - k * pass.rows_per_seg;
-    *row = pass.segs[k].rows.as<uint32_t>() + i * L;
+    *row = pass.segs[k].rows.as<uint32_t>() + i * stride;
     *tslot = pass.segs[k].row_time.as<unsigned long long>() + i;
   };
 
   uint64_t e = 0;
   bool stopped = false;  // prefix run reached max_events
-  pass.prefill = true;  // the kernels write matches (a reversed pass: arrivals) only
+  pass.prefill = !small;  // dense rows: the kernels write matches (a reversed pass: arrivals) only
+  if (small) {
+    // compact records: exactly one per unsatisfied postcondition of the pass
+    pass.compact = true;
+    pass.rows_per_seg = 1u << 20;
+    const uint64_t cap = (uint64_t)N * C - C;
+    if (cap > 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 transfers in a pass of the single-workgroup kernel"; return TACOS_E_INVAL; }
+    pass.recs.alloc((size_t)std::max<uint64_t>(cap, 1) * 8);
+  }
   DevBuf d_rnd, d_prev;
   if (!small && match_mode == 0) {
     d_rnd.alloc((size_t)L * 4 * (uniform ? 2 : 1));
@@ -427,7 +444,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
         HIP_TRY(hipEventRecord(ev0, stream));
       }
       HIP_TRY(tacos::launch_small_sweep(p, g.out_ptr.as<uint32_t>(), g.out_dst.as<uint32_t>(), (uint32_t)e,
-                                        (uint32_t)n, stop_event, row, tslot, match_mode, stream));
+                                        (uint32_t)n, stop_event, pass.recs.as<uint2>(), row, tslot, match_mode, stream));
       if (time_kernels) HIP_TRY(hipEventRecord(ev1, stream));
       HIP_TRY(hipMemcpyAsync(host_ctl.p, p.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, stream));
       HIP_TRY(hipStreamSynchronize(stream));
@@ -522,12 +539,10 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
     pass.n_events = max_events;
   }
   pass.n_rows = reversed ? pass.n_events + 1 : pass.n_events;
+  pass.n_rec = c.n_rec;
   // drop segments past the end (batches run ahead of the terminating span)
   const uint64_t used_segs = (pass.n_rows + pass.rows_per_seg - 1) / pass.rows_per_seg;
-  while (pass.segs.size() > used_segs) {
-    res.device_bytes -= pass.segs.back().rows.bytes + pass.segs.back().row_time.bytes;
-    pass.segs.pop_back();
-  }
+  while (pass.segs.size() > used_segs) pass.segs.pop_back();
   return TACOS_OK;
 }
 
@@ -541,6 +556,28 @@ void finish_pass(Pass &pass, uint64_t t_off, uint64_t *digest, hipStream_t strea
   DevBuf d_digest(digest_bytes);
   HIP_TRY(hipMemsetAsync(d_digest.p, 0, digest_bytes, stream));
   const uint64_t t_base = pass.reversed ? pass.T : t_off;
+  if (pass.compact) {
+    // gather the spans' first-record indices and times, order every span's records by link
+    // and digest them; the per-span segments are not needed afterwards
+    pass.first.assign(pass.n_rows + 1, 0);
+    for (size_t k = 0; k < pass.segs.size(); ++k) {
+      const uint64_t first = (uint64_t)k * pass.rows_per_seg;
+      if (first >= pass.n_rows) break;
+      const size_t n = (size_t)std::min<uint64_t>(pass.rows_per_seg, pass.n_rows - first);
+      HIP_TRY(hipMemcpyAsync(pass.first.data() + first, pass.segs[k].rows.p, n * 4, hipMemcpyDeviceToHost, stream));
+      HIP_TRY(hipMemcpyAsync(pass.row_time.data() + first, pass.segs[k].row_time.p, n * 8, hipMemcpyDeviceToHost, stream));
+    }
+    HIP_TRY(hipStreamSynchronize(stream));
+    pass.first[pass.n_rows] = (uint32_t)pass.n_rec;
+    pass.segs.clear();
+    upload(pass.d_first, pass.first.data(), pass.first.size(), stream);
+    upload(pass.d_time, reinterpret_cast<const unsigned long long *>(pass.row_time.data()), pass.row_time.size(), stream);
+    tacos::launch_compact_epilogue(pass.recs.as<uint2>(), pass.d_first.as<uint32_t>(), (uint32_t)pass.n_rows, pass.L,
+                                   pass.d_time.as<unsigned long long>(), t_base, pass.reversed ? 1u : 0u,
+                                   d_digest.as<unsigned long long>(), stream);
+    HIP_TRY(hipGetLastError());
+    for (uint64_t k = 0; k < pass.n_rows; ++k) pass.row_count[k] = pass.first[k + 1] - pass.first[k];
+  }
   for (size_t k = 0; k < pass.segs.size(); ++k) {
     const uint64_t first = (uint64_t)k * pass.rows_per_seg;
     const uint32_t n = (uint32_t)std::min<uint64_t>(pass.rows_per_seg, pass.n_rows - first);
@@ -742,6 +779,8 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       res->collective_time += ps.T;
       res->n_events += ps.n_events;
       res->n_xfers += ps.n_xfers;
+      res->device_bytes += ps.recs.bytes + ps.d_first.bytes + ps.d_time.bytes;
+      for (const Segment &sg : ps.segs) res->device_bytes += sg.rows.bytes + sg.row_time.bytes;
     }
   } catch (const HipFail &f) {
     return f.code;
@@ -930,6 +969,12 @@ int tacos_result_event_trace(const tacos_result_t *r, uint32_t pass, uint64_t *e
       DevBuf d_time((size_t)ps.n_rows * 8), d_counts((size_t)ps.n_rows * 4);
       HIP_TRY(hipMemcpy(d_time.p, ps.row_time.data(), (size_t)ps.n_rows * 8, hipMemcpyHostToDevice));
       HIP_TRY(hipMemset(d_counts.p, 0, (size_t)ps.n_rows * 4));
+      if (ps.compact) {
+        tacos::launch_compact_start_span_counts(ps.recs.as<uint2>(), ps.d_first.as<uint32_t>(), (uint32_t)ps.n_rows,
+                                                d_time.as<unsigned long long>(), r->d_cost.as<unsigned long long>(),
+                                                d_counts.as<uint32_t>(), nullptr);
+        HIP_TRY(hipGetLastError());
+      }
       for (size_t k = 0; k < ps.segs.size(); ++k) {
         const uint64_t first = (uint64_t)k * ps.rows_per_seg;
         if (first >= ps.n_rows) break;
@@ -980,6 +1025,29 @@ int tacos_result_read(const tacos_result_t *r, uint64_t first, uint64_t count, t
         // last canonical row (exclusive) that holds a record below lend
         const uint64_t k_end = (uint64_t)(std::lower_bound(ps.canon_base.begin(), ps.canon_base.end(), lend) -
                                           ps.canon_base.begin());
+        if (ps.compact) {
+          // the spans of canonical rows [k, k_end) are consecutive (descending for a reversed
+          // pass), so their records are one range of the record array
+          const uint64_t e_a = ps.event_of(k), e_b = ps.event_of(k_end - 1);
+          const uint64_t e_lo = std::min(e_a, e_b), e_hi = std::max(e_a, e_b) + 1;
+          const uint32_t r_lo = ps.first[e_lo], r_hi = ps.first[e_hi];
+          std::vector<uint2> recs_host((size_t)(r_hi - r_lo));
+          if (r_hi > r_lo)
+            HIP_TRY(hipMemcpy(recs_host.data(), ps.recs.as<uint2>() + r_lo, (size_t)(r_hi - r_lo) * 8, hipMemcpyDeviceToHost));
+          for (uint64_t kk = k; kk < k_end; ++kk) {
+            const uint64_t ee = ps.event_of(kk);
+            const uint64_t t = ps.time_of_event(ee);
+            uint64_t idx = ps.canon_base[kk];
+            for (uint32_t i = ps.first[ee]; i < ps.first[ee + 1] && idx < lend; ++i, ++idx) {
+              if (idx < lfirst) continue;
+              const uint2 rc = recs_host[i - r_lo];
+              tacos_xfer_t &x = host_out[written++];
+              x.t_ps = t; x.src = r->link_src[rc.x]; x.dst = r->link_dst[rc.x]; x.chunk = rc.y; x.link = rc.x;
+            }
+          }
+          pass_base += ps.n_xfers;
+          continue;
+        }
         const uint64_t block_rows = std::max<uint64_t>(1, (64ull << 20) / ((uint64_t)ps.L * 4));
         while (k < k_end) {
           // a block of canonical rows that is contiguous in one segment
@@ -1041,6 +1109,7 @@ int tacos_result_link_counts(const tacos_result_t *r, uint32_t pass, uint64_t *l
     if (prev != r->device) HIP_TRY(hipSetDevice(r->device));
     DevBuf d_counts((size_t)r->L * 8);
     HIP_TRY(hipMemset(d_counts.p, 0, (size_t)r->L * 8));
+    if (ps.compact) tacos::launch_compact_link_counts(ps.recs.as<uint2>(), (uint32_t)ps.n_rec, d_counts.as<unsigned long long>(), nullptr);
     for (size_t k = 0; k < ps.segs.size(); ++k) {
       const uint64_t first = (uint64_t)k * ps.rows_per_seg;
       if (first >= ps.n_rows) break;
@@ -1065,7 +1134,7 @@ int tacos_result_link_busy(const tacos_result_t *r, uint32_t pass, uint64_t *bus
   g_last_error.clear();
   if (!r || pass >= r->passes.size()) return TACOS_E_INVAL;
   const Pass &ps = r->passes[pass];
-  if (r->L == 0 || ps.segs.empty()) {
+  if (r->L == 0 || (ps.segs.empty() && !ps.compact)) {
     if (busy_ps) std::fill(busy_ps, busy_ps + r->L, 0ull);
     if (sum_ps) *sum_ps = 0;
     if (min_ps) *min_ps = 0;
@@ -1079,6 +1148,7 @@ int tacos_result_link_busy(const tacos_result_t *r, uint32_t pass, uint64_t *bus
     DevBuf d_counts((size_t)r->L * 8), d_busy((size_t)r->L * 8), d_out(3 * 8), d_flags(4);
     HIP_TRY(hipMemset(d_counts.p, 0, (size_t)r->L * 8));
     HIP_TRY(hipMemset(d_flags.p, 0, 4));
+    if (ps.compact) tacos::launch_compact_link_counts(ps.recs.as<uint2>(), (uint32_t)ps.n_rec, d_counts.as<unsigned long long>(), nullptr);
     for (size_t k = 0; k < ps.segs.size(); ++k) {
       const uint64_t first = (uint64_t)k * ps.rows_per_seg;
       if (first >= ps.n_rows) break;

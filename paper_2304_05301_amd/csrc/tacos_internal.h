@@ -29,7 +29,7 @@ struct Ctl {
   uint32_t done;
   uint32_t status;
   uint32_t n_events;             // matching sweeps run, valid once done
-  uint32_t pad;
+  uint32_t n_rec;                // single-workgroup kernel: schedule records written so far
   // Set by the matching of span e if a destination with an idle incoming link still misses a
   // chunk, read by the launch that follows, cleared one span ahead.  Two launches per span:
   // index e & 1 (set by match_kernel, read and cleared by arrive_kernel); homogeneous-TEN path:
@@ -130,12 +130,14 @@ void launch_match(const PassDev &p, uint32_t event, uint32_t *sched_row, uint32_
 // first_event+n_events) with the per-link state in LDS (arrivals, termination test,
 // matching of the destinations something changed for, next-event min-reduction) and
 // returns early when the pass ends.  mode: as launch_match.  stop_event: the span at which only the arrivals are
-// applied (prefix runs), or 0xFFFFFFFF.  sched_rows / event_times point at the slots of
-// first_event; the rows must be pre-filled with kNone.  out_ptr/out_dst: out-neighbour
-// lists of the pass orientation.  Needs small_sweep_lds_bytes(...) of dynamic LDS.
+// applied (prefix runs), or 0xFFFFFFFF.  The schedule is written as compact records: recs
+// (the whole pass's (link, chunk) pairs, appended in span order; within a span in no
+// particular order) and, per span from first_event on, span_first (index of the span's first
+// record) and event_times.  A forward pass records matches, a reversed pass arrivals.
+// out_ptr/out_dst: out-neighbour lists of the pass orientation.
 hipError_t launch_small_sweep(const PassDev &p, const uint32_t *out_ptr, const uint32_t *out_dst,
                               uint32_t first_event, uint32_t n_events, uint32_t stop_event,
-                              uint32_t *sched_rows, unsigned long long *event_times, uint32_t mode,
+                              uint2 *recs, uint32_t *span_first, unsigned long long *event_times, uint32_t mode,
                               hipStream_t s);
 // The same sweep for n_jobs independent passes of one shape at once, one workgroup each
 // (jobs: device array); collective times only, no schedule rows.  p0: any of the jobs'
@@ -156,6 +158,20 @@ void launch_row_stats(const uint32_t *rows, uint32_t n_rows, uint32_t L,
                       const unsigned long long *row_time, unsigned long long t_base,
                       uint32_t reversed, uint32_t *row_count, unsigned long long *digest,
                       hipStream_t s);
+
+// ---- compact schedules (single-workgroup kernel): n_rec records (link, chunk), the records of
+// span e are [span_first[e], span_first[e + 1]), span_first has n_spans + 1 entries.
+// epilogue: orders the records of every span by link id (workgroups of 256 threads, L * 4 bytes
+// of LDS) and adds the schedule digest of all records into the kDigestSlots partial sums
+void launch_compact_epilogue(uint2 *recs, const uint32_t *span_first, uint32_t n_spans, uint32_t L,
+                             const unsigned long long *span_time, unsigned long long t_base, uint32_t reversed,
+                             unsigned long long *digest, hipStream_t s);
+// counts[l] += records on link l
+void launch_compact_link_counts(const uint2 *recs, uint32_t n_rec, unsigned long long *counts, hipStream_t s);
+// reversed pass: counts[k] += records that STARTED in span k (arrival span's time minus the link's cost)
+void launch_compact_start_span_counts(const uint2 *recs, const uint32_t *span_first, uint32_t n_spans,
+                                      const unsigned long long *span_time, const unsigned long long *cost,
+                                      uint32_t *counts, hipStream_t s);
 
 // reporting, reversed pass (rows keyed by arrival span): counts[k] += number of transfers of
 // the block of rows [first_row, first_row + n_rows) that STARTED in span k, i.e. whose arrival

@@ -172,7 +172,7 @@ __global__ void init_links_kernel(PassDev p)
     c->done = 0u;
     c->status = 0u;
     c->n_events = 0u;
-    c->pad = 0u;
+    c->n_rec = 0u;
     c->now = 0ull;
     for (int i = 0; i < 4; ++i) { c->need_flag[i] = 0u; c->match_flag[i] = 0u; }
   }
@@ -294,6 +294,25 @@ __device__ __forceinline__ u32 kth_set_bit_wave(u32 lo, u32 hi, u32 k)
   return (u32)__ffsll((long long)hit) - 1u;
 }
 
+// Compact schedule records of the single-workgroup kernel: (link, chunk) pairs appended in the
+// order the spans are swept, at a record counter that lives in LDS.  Null in the other kernels.
+struct RecOut {
+  uint2 *recs = nullptr;
+  u32 *counter = nullptr;
+};
+
+// appends the lanes' records (lanes with has == true) behind one another
+__device__ __forceinline__ void append_records(const RecOut &rec, bool has, u32 link, u32 chunk, int lane)
+{
+  const u64 m = __ballot(has);
+  if (m == 0ull) return;
+  const u32 first = (u32)__ffsll((long long)m) - 1u;
+  u32 base = 0;
+  if ((u32)lane == first) base = atomicAdd(rec.counter, (u32)__popcll(m));
+  base = read_lane(base, first);
+  if (has) rec.recs[base + (u32)__popcll(m & ((1ull << lane) - 1ull))] = make_uint2(link, chunk);
+}
+
 // The link-centric draws of ONE destination for up to 64 of its incoming links (one per
 // lane): for every link whose bit is set in `idle`, in ascending lane order,
 //   cand = held[source] & need;  p = |cand|;  nothing if p == 0;
@@ -399,7 +418,8 @@ __device__ __forceinline__ u32 draw_chunks(const u64 *__restrict__ held, u32 row
 // is decided; the candidate set is formed in place in the buffer.
 template <int NP, bool LATENCY_BOUND>
 __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb, u32 je, u32 event, u64 t,
-                                                     u32 *__restrict__ sched_row, int lane, uint4 *need_lds)
+                                                     u32 *__restrict__ sched_row, int lane, uint4 *need_lds,
+                                                     const RecOut rec = RecOut())
 {
   constexpr int NW = 2 * NP;
   Ctl *ctl = p.ctl;
@@ -489,6 +509,7 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb
       else if (valid) r = p.rnd[j];
       res = draw_chunks<NP>(p.held, p.row_words, s, r, idle, need_lds, lane);
     }
+    if (rec.recs) append_records(rec, valid && res != kNone, l, res, lane);
     if (valid) {
       if (sched_row && res != kNone) sched_row[l] = res;  // rows are pre-filled with kNone
       if (res != kNone) {
@@ -768,7 +789,7 @@ __device__ __forceinline__ u32 draw_pairs_planes(const u64 *__restrict__ held, u
 template <int NP, int DEG>
 __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, u32 jb, u32 je, u32 event, u64 t,
                                                        u32 *__restrict__ sched_row, int lane, uint4 *need_lds,
-                                                       bool first_holder)
+                                                       bool first_holder, const RecOut rec = RecOut())
 {
   constexpr int NW = 2 * NP;
   Ctl *ctl = p.ctl;
@@ -814,6 +835,7 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
                                       p.seed_hi, first_holder, need_lds, lane);
     }
   }
+  if (rec.recs) append_records(rec, valid && res != kNone, l, res, lane);
   if (valid) {
     if (sched_row && res != kNone) sched_row[l] = res;  // rows are pre-filled with kNone
     if (res != kNone) {
@@ -1231,8 +1253,9 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 template <int NP, int MODE>
 __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__restrict__ out_ptr,
                                                  const u32 *__restrict__ out_dst, u32 first_event,
-                                                 u32 n_events, u32 stop_event, u32 *__restrict__ sched_rows,
-                                                 u64 *__restrict__ event_times, u32 dst_in_lds)
+                                                 u32 n_events, u32 stop_event, uint2 *__restrict__ recs,
+                                                 u32 *__restrict__ span_first, u64 *__restrict__ event_times,
+                                                 u32 dst_in_lds)
 {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const u32 Lp = (p.L + 1u) & ~1u;
@@ -1243,7 +1266,8 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   u32 *s_work = reinterpret_cast<u32 *>(cur); cur += ((size_t)p.N * 4 + 15) & ~(size_t)15;
   uint4 *s_need = reinterpret_cast<uint4 *>(cur); cur += (size_t)16 * NP * 1024;
   u64 *s_next = reinterpret_cast<u64 *>(cur); cur += 2 * 8;  // next event time, one slot per span parity
-  // [0] = destinations appended as out-neighbours, [1] = arrivals, [3] = NPUs arrived at
+  // [0] = destinations appended as out-neighbours, [1] = arrivals, [2] = schedule records
+  // written so far in the pass, [3] = NPUs arrived at
   u32 *s_cnt = reinterpret_cast<u32 *>(cur); cur += 16;
   Ctl *s_ctl = reinterpret_cast<Ctl *>(cur); cur += (sizeof(Ctl) + 15) & ~(size_t)15;  // status / done of the matching code
   u32 *s_dst = reinterpret_cast<u32 *>(cur);
@@ -1261,9 +1285,11 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   for (u32 n = tid; n < p.N; n += 1024u) s_stamp[n] = kNone;
   if (tid == 0) {
     s_cnt[0] = 0u; s_cnt[1] = 0u; s_cnt[3] = 0u;
+    s_cnt[2] = ctl->n_rec;
     s_ctl->status = 0u; s_ctl->done = 0u;
     s_next[0] = kInf; s_next[1] = kInf;
   }
+  const RecOut rec_fwd = (recs && !p.reversed) ? RecOut{recs, &s_cnt[2]} : RecOut();
   const u32 *pos_dst = p.pos_dst;
   if (dst_in_lds) {
     for (u32 l = tid; l < p.L; l += 1024u) s_dst[l] = p.pos_dst[l];
@@ -1292,8 +1318,8 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   u64 lm = own_min();
 
   for (; e < first_event + n_events; ++e) {
-    u32 *row = sched_rows ? sched_rows + (u64)(e - first_event) * p.L : nullptr;  // null: times only
-    if (tid == 0 && event_times) event_times[e - first_event] = t;
+    // the span's records (a forward pass: its matches; a reversed one: its arrivals) begin here
+    if (tid == 0 && event_times) { event_times[e - first_event] = t; span_first[e - first_event] = s_cnt[2]; }
     // ---- arrivals at t (a3): the NPUs a chunk arrived at start the work list
     if (lm == t) {
       for (u32 l2 = tid * 2u; l2 < Lp; l2 += 2048u) {
@@ -1307,7 +1333,7 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
           s_carry[l] = kNone;
           s_free[l] = kInf;
           atomicAdd(&s_cnt[1], 1u);
-          if (p.reversed && row) row[p.in_link[l]] = c;
+          if (p.reversed && recs) recs[atomicAdd(&s_cnt[2], 1u)] = make_uint2(p.in_link[l], c);
           if (atomicExch(&s_stamp[d], e) != e) s_work[atomicAdd(&s_cnt[3], 1u)] = d;
         }
       }
@@ -1339,11 +1365,10 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
       const u32 d = uniform((e == 0u) ? i : s_work[i]);
       const u32 jb = p.in_ptr[d], je = p.in_ptr[d + 1];
       if constexpr (MODE == 0)
-        (void)match_destination<NP, true>(q, d, jb, je, e, t, p.reversed ? nullptr : row, lane,
-                                          s_need + wave * NP * 64);
+        (void)match_destination<NP, true>(q, d, jb, je, e, t, nullptr, lane, s_need + wave * NP * 64, rec_fwd);
       else
-        (void)match_destination_pairs<NP, 8>(q, d, jb, je, e, t, p.reversed ? nullptr : row, lane,
-                                             s_need + wave * NP * 64, MODE == 2);
+        (void)match_destination_pairs<NP, 8>(q, d, jb, je, e, t, nullptr, lane, s_need + wave * NP * 64, MODE == 2,
+                                             rec_fwd);
     }
     lds_barrier();
     // ---- next span = earliest end of a transfer in flight (a8), reduced in LDS
@@ -1369,17 +1394,17 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   __syncthreads();
   for (u32 l = tid; l < p.L; l += 1024u) { p.free_at[l] = s_free[l]; p.carry[l] = s_carry[l]; }
   if (tid == 0 && !finished) ctl->next_t[e & 1u] = t;
-  if (tid == 0) ctl->remaining = remaining;
+  if (tid == 0) { ctl->remaining = remaining; ctl->n_rec = s_cnt[2]; }
 }
 
 template <int NP, int MODE>
 __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 *__restrict__ out_ptr,
                                                            const u32 *__restrict__ out_dst, u32 first_event,
                                                            u32 n_events, u32 stop_event,
-                                                           u32 *__restrict__ sched_rows,
+                                                           uint2 *__restrict__ recs, u32 *__restrict__ span_first,
                                                            u64 *__restrict__ event_times, u32 dst_in_lds)
 {
-  small_sweep_body<NP, MODE>(p, out_ptr, out_dst, first_event, n_events, stop_event, sched_rows, event_times,
+  small_sweep_body<NP, MODE>(p, out_ptr, out_dst, first_event, n_events, stop_event, recs, span_first, event_times,
                              dst_in_lds);
 }
 
@@ -1390,7 +1415,7 @@ __global__ __launch_bounds__(1024) void small_sweep_batch_kernel(const SmallJob 
                                                                  u32 n_events, u32 dst_in_lds)
 {
   const SmallJob &j = jobs[blockIdx.x];
-  small_sweep_body<NP, MODE>(j.p, j.out_ptr, j.out_dst, first_event, n_events, 0xFFFFFFFFu, nullptr, nullptr,
+  small_sweep_body<NP, MODE>(j.p, j.out_ptr, j.out_dst, first_event, n_events, 0xFFFFFFFFu, nullptr, nullptr, nullptr,
                              dst_in_lds);
 }
 
@@ -1448,6 +1473,97 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const u32 *__restrict__ 
       atomicAdd(&row_count[row], nb);
       atomicAdd(&digest[(blockIdx.x % kDigestSlots) * 16u], s_dg[0] + s_dg[1] + s_dg[2] + s_dg[3]);
     }
+  }
+}
+
+// ---- compact schedules of the single-workgroup kernel
+
+// One workgroup per span: brings the span's records into ascending link id (a link starts at
+// most one transfer per span, so the records scatter into a row of L entries in LDS and are
+// read back in order) and adds their digest contributions.  t = the span's time (forward
+// pass, offset t_base) or t_base minus it (reversed pass: the records are arrivals).
+__global__ __launch_bounds__(256) void compact_epilogue_kernel(uint2 *__restrict__ recs,
+                                                               const u32 *__restrict__ span_first, u32 L,
+                                                               const u64 *__restrict__ span_time, u64 t_base,
+                                                               u32 reversed, u64 *__restrict__ digest)
+{
+  extern __shared__ __align__(16) unsigned char compact_lds[];
+  u32 *row = reinterpret_cast<u32 *>(compact_lds);  // [L]
+  __shared__ u32 s_off[257];
+  __shared__ u64 s_dg[4];
+  const u32 e = blockIdx.x;
+  const u32 b0 = span_first[e], n = span_first[e + 1] - b0;
+  if (n == 0) return;
+  const u64 rt = span_time[e];
+  const u64 t = reversed ? t_base - rt : rt + t_base;
+  u64 dg = 0;
+  for (u32 i = threadIdx.x; i < n; i += 256u) {
+    const uint2 r = recs[b0 + i];
+    dg += mix_record(t, r.x, r.y);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const u32 lo = (u32)__shfl_xor((int)(u32)dg, off, 64);
+    const u32 hi = (u32)__shfl_xor((int)(u32)(dg >> 32), off, 64);
+    dg += ((u64)hi << 32) | lo;
+  }
+  if ((threadIdx.x & 63u) == 0) s_dg[threadIdx.x >> 6] = dg;
+  if (n > 1) {  // uniform over the workgroup
+    for (u32 l = threadIdx.x; l < L; l += 256u) row[l] = kNone;
+    __syncthreads();
+    for (u32 i = threadIdx.x; i < n; i += 256u) {
+      const uint2 r = recs[b0 + i];
+      row[r.x] = r.y;
+    }
+    __syncthreads();
+    // thread k owns links [k*per, (k+1)*per): count, exclusive prefix over the threads, write back
+    const u32 per = (L + 255u) / 256u;
+    const u32 l0 = threadIdx.x * per, l1 = l0 + per < L ? l0 + per : L;
+    u32 cnt = 0;
+    for (u32 l = l0; l < l1; ++l) cnt += row[l] != kNone ? 1u : 0u;
+    s_off[threadIdx.x + 1] = cnt;
+    if (threadIdx.x == 0) s_off[0] = 0u;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      for (u32 k = 1; k <= 256u; ++k) s_off[k] += s_off[k - 1];
+    __syncthreads();
+    u32 w = b0 + s_off[threadIdx.x];
+    for (u32 l = l0; l < l1; ++l) {
+      const u32 c = row[l];
+      if (c != kNone) recs[w++] = make_uint2(l, c);
+    }
+  } else {
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) atomicAdd(&digest[(blockIdx.x % kDigestSlots) * 16u], s_dg[0] + s_dg[1] + s_dg[2] + s_dg[3]);
+}
+
+__global__ __launch_bounds__(256) void compact_link_count_kernel(const uint2 *__restrict__ recs, u32 n_rec,
+                                                                 u64 *__restrict__ counts)
+{
+  const u32 i = blockIdx.x * 256u + threadIdx.x;
+  if (i < n_rec) atomicAdd(&counts[recs[i].x], 1ull);
+}
+
+// One workgroup per span of a reversed pass: every record arrived in this span; it started in
+// the span whose time is the arrival time minus the link's cost.
+__global__ __launch_bounds__(256) void compact_start_span_kernel(const uint2 *__restrict__ recs,
+                                                                 const u32 *__restrict__ span_first,
+                                                                 const u64 *__restrict__ span_time,
+                                                                 const u64 *__restrict__ cost, u32 *__restrict__ counts)
+{
+  const u32 e = blockIdx.x;
+  const u32 b0 = span_first[e], n = span_first[e + 1] - b0;
+  const u64 t_arr = span_time[e];
+  for (u32 i = threadIdx.x; i < n; i += 256u) {
+    const u64 t_start = t_arr - cost[recs[b0 + i].x];
+    u32 lo = 0, hi = e;  // the first span with time >= t_start
+    while (lo < hi) {
+      const u32 mid = (lo + hi) >> 1;
+      if (span_time[mid] < t_start) lo = mid + 1u;
+      else hi = mid;
+    }
+    atomicAdd(&counts[lo], 1u);
   }
 }
 
@@ -1690,7 +1806,8 @@ static size_t small_launch_lds(const PassDev &p, u32 *dst_in_lds)
 
 template <int NP, int MODE>
 static hipError_t launch_small_np(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
-                                  u32 n_events, u32 stop_event, u32 *sched_rows, u64 *event_times, hipStream_t s)
+                                  u32 n_events, u32 stop_event, uint2 *recs, u32 *span_first, u64 *event_times,
+                                  hipStream_t s)
 {
   u32 dst_in_lds = 0;
   const size_t lds = small_launch_lds(p, &dst_in_lds);
@@ -1698,7 +1815,7 @@ static hipError_t launch_small_np(const PassDev &p, const u32 *out_ptr, const u3
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((small_sweep_kernel<NP, MODE>), dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst, first_event,
-                     n_events, stop_event, sched_rows, event_times, dst_in_lds);
+                     n_events, stop_event, recs, span_first, event_times, dst_in_lds);
   return hipGetLastError();
 }
 
@@ -1717,11 +1834,11 @@ static hipError_t launch_batch_np(const SmallJob *jobs, u32 n_jobs, const PassDe
 }
 
 hipError_t launch_small_sweep(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
-                              u32 n_events, u32 stop_event, u32 *sched_rows, u64 *event_times, u32 mode,
+                              u32 n_events, u32 stop_event, uint2 *recs, u32 *span_first, u64 *event_times, u32 mode,
                               hipStream_t s)
 {
 #define TACOS_SMALL(NP_, M_) \
-  return launch_small_np<NP_, M_>(p, out_ptr, out_dst, first_event, n_events, stop_event, sched_rows, event_times, s)
+  return launch_small_np<NP_, M_>(p, out_ptr, out_dst, first_event, n_events, stop_event, recs, span_first, event_times, s)
   if (mode > 2) return hipErrorInvalidValue;
   switch (p.NP * 4 + mode) {
     case 4: TACOS_SMALL(1, 0);
@@ -1753,6 +1870,28 @@ hipError_t launch_small_sweep_batch(const SmallJob *jobs, u32 n_jobs, const Pass
 }
 
 size_t small_sweep_lds_bytes(u32 N, u32 L, u32 NP) { return NP <= 2 ? small_lds_bytes(N, L, NP) : (size_t)-1; }
+
+void launch_compact_epilogue(uint2 *recs, const u32 *span_first, u32 n_spans, u32 L, const u64 *span_time, u64 t_base,
+                             u32 reversed, u64 *digest, hipStream_t s)
+{
+  if (n_spans == 0) return;
+  hipLaunchKernelGGL(compact_epilogue_kernel, dim3(n_spans), dim3(256), (size_t)L * 4, s, recs, span_first, L, span_time,
+                     t_base, reversed, digest);
+}
+
+void launch_compact_link_counts(const uint2 *recs, u32 n_rec, u64 *counts, hipStream_t s)
+{
+  if (n_rec == 0) return;
+  hipLaunchKernelGGL(compact_link_count_kernel, dim3((n_rec + 255) / 256), dim3(256), 0, s, recs, n_rec, counts);
+}
+
+void launch_compact_start_span_counts(const uint2 *recs, const u32 *span_first, u32 n_spans, const u64 *span_time,
+                                      const u64 *cost, u32 *counts, hipStream_t s)
+{
+  if (n_spans == 0) return;
+  hipLaunchKernelGGL(compact_start_span_kernel, dim3(n_spans), dim3(256), 0, s, recs, span_first, span_time, cost,
+                     counts);
+}
 
 void launch_start_span_counts(const u32 *rows, u32 first_row, u32 n_rows, u32 L, const u64 *row_time,
                               const u64 *cost, u32 *counts, hipStream_t s)

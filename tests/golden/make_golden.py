@@ -10,7 +10,8 @@ t_ps:u64, src:u32, dst:u32, chunk:u32, link:u32).  Workload 4 takes about a minu
 
 additionally runs the 40,960-NPU workload 5 to completion (OpenMP over destinations;
 minutes) and stores its time, sweeps, records, digest and the SHA-256 of the per-sweep
-(time, match count) trace in workload5_oracle.json.  Its 1.68e9 records are not kept.
+(time, match count) trace in workload5_oracle.json.  Of its 1.68e9 records the first 4096 and
+16 windows of 65,536 spread over the whole schedule (the last one ends it) are hashed.
 
     python tests/golden/make_golden.py --scalability 6 [--threads 8]      (or 7)
 
@@ -35,12 +36,27 @@ import oracle  # noqa: E402
 from paper_2304_05301_amd import topologies as T  # noqa: E402
 
 
+W5_XFERS = 40_960 * 40_959          # records of the 40,960-NPU All-Gather
+W5_BLOCK = 65_536                   # records per sampled window
+W5_STRIDE = 104_857_600             # distance between windows: 16 of them, the last one ends the schedule
+
+
 def workload5(threads):
     w = T.workload(5)
     oracle.set_progress(500)
+    first = (W5_XFERS - W5_BLOCK) % W5_STRIDE
+    # one run keeps the first 4096 records; a second one the windows spread over the schedule
     r = oracle.synthesize_workload(w, keep_first=0, keep_xfers=4096, n_threads=threads)
+    oracle.set_keep_windows(W5_STRIDE, W5_BLOCK)
+    try:
+        rw = oracle.synthesize_workload(w, keep_first=first, n_threads=threads)
+    finally:
+        oracle.set_keep_windows(0, 0)
+    assert rw.digest == r.digest and rw.n_xfers == r.n_xfers == W5_XFERS and len(rw.xfers) % W5_BLOCK == 0
+    windows = [hashlib.sha256(rw.xfers[i:i + W5_BLOCK].tobytes()).hexdigest() for i in range(0, len(rw.xfers), W5_BLOCK)]
     trace = hashlib.sha256(r.event_times.tobytes() + r.event_matches.tobytes()).hexdigest()
     out = {
+        "windows": {"first": first, "stride": W5_STRIDE, "block": W5_BLOCK, "sha256": windows},
         "name": w.name,
         "topology": w.topo.name,
         "collective_time_ps": r.collective_time_ps,

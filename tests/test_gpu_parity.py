@@ -366,6 +366,13 @@ def test_workload_5_full_run_against_stored_oracle_result(stream):
         # the last record of the canonical order ends exactly at the collective time
         last = r.read(r.num_xfers - 1, 1)[0]
         assert int(last["t_ps"]) + 10_985_760 == g["collective_time_ps"]
+        # records, not only their digest: 16 windows of 65,536 records spread over the whole
+        # schedule (the last one ends it), each against the SHA-256 of the oracle's records
+        win = g["windows"]
+        assert win["first"] + (len(win["sha256"]) - 1) * win["stride"] + win["block"] == r.num_xfers
+        for k, want in enumerate(win["sha256"]):
+            got = r.read(win["first"] + k * win["stride"], win["block"])
+            assert hashlib.sha256(got.tobytes()).hexdigest() == want, f"window {k}"
 
 
 @pytest.mark.parametrize("idx", [6, 7])

@@ -283,6 +283,14 @@ def test_prefix_and_window_runs():
     win = run(topo, seed=1, keep_first=100, keep_xfers=50)
     assert np.array_equal(win.xfers, full.xfers[100:150])
     assert win.digest == full.digest and win.n_xfers == full.n_xfers
+    # sampled windows: blocks of 7 records every 100, from record 13 on
+    oracle.set_keep_windows(100, 7)
+    try:
+        samp = run(topo, seed=1, keep_first=13)
+    finally:
+        oracle.set_keep_windows(0, 0)
+    want = np.concatenate([full.xfers[13 + k * 100:13 + k * 100 + 7] for k in range((len(full.xfers) - 13 + 99) // 100)])
+    assert np.array_equal(samp.xfers, want) and samp.digest == full.digest and samp.n_xfers == full.n_xfers
 
 
 # ------------------------------------------------------------------ brute force, N <= 4
