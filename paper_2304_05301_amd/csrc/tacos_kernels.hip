@@ -294,6 +294,48 @@ __device__ __forceinline__ u32 kth_set_bit_wave(u32 lo, u32 hi, u32 k)
   return (u32)__ffsll((long long)hit) - 1u;
 }
 
+// Where the matching reads the held rows from.
+// RowsHbm: the table in device memory, swizzled rows of NP KiB (see PassDev).
+struct RowsHbm {
+  const u64 *held;
+  u32 row_words;
+  __device__ __forceinline__ uint4 load(u32 npu, int piece, int lane) const
+  {
+    return reinterpret_cast<const uint4 *>(held + (u64)npu * row_words)[piece * 64 + lane];
+  }
+  __device__ __forceinline__ u32 dword(u32 npu, u32 dw) const  // dw: dword index inside the row
+  {
+    return reinterpret_cast<const u32 *>(held + (u64)npu * row_words)[dw];
+  }
+};
+// RowsLds: a copy of the table in LDS (single-workgroup kernel, small chunk counts) without
+// the lanes that own no chunk id below C: a row is NP pieces of `lanes` 16-byte shares; the
+// shares left out are all ones ("held", never a candidate) and are synthesized on load.
+struct RowsLds {
+  uint4 *base;
+  u32 lanes;   // lanes of a wavefront that own a chunk id < C
+  u32 row_u4;  // NP * lanes
+  __device__ __forceinline__ uint4 load(u32 npu, int piece, int lane) const
+  {
+    uint4 v = make_uint4(~0u, ~0u, ~0u, ~0u);
+    if ((u32)lane < lanes) v = base[npu * row_u4 + (u32)piece * lanes + (u32)lane];
+    return v;
+  }
+  __device__ __forceinline__ u32 dword(u32 npu, u32 dw) const
+  {
+    const u32 share = dw >> 2, piece = share >> 6, ln = share & 63u;
+    if (ln >= lanes) return ~0u;
+    return reinterpret_cast<const u32 *>(&base[npu * row_u4 + piece * lanes + ln])[dw & 3u];
+  }
+  // the 64-bit word that holds chunk c in row npu (c < C)
+  __device__ __forceinline__ u64 *word_of(u32 npu, u32 c, u32 NP) const
+  {
+    const u32 w = c >> 6, nw = 2u * NP;
+    const u32 ln = w / nw, iw = w - ln * nw;
+    return reinterpret_cast<u64 *>(&base[npu * row_u4 + (iw >> 1) * lanes + ln]) + (iw & 1u);
+  }
+};
+
 // Compact schedule records of the single-workgroup kernel: (link, chunk) pairs appended in the
 // order the spans are swept, at a record counter that lives in LDS.  Null in the other kernels.
 struct RecOut {
@@ -322,9 +364,8 @@ __device__ __forceinline__ void append_records(const RecOut &rec, bool has, u32 
 // kNone.  Source rows land in two register buffers used in turn, so that the next link's
 // row is in flight while the current link is decided; the candidate set is formed in place
 // in the buffer.
-template <int NP>
-__device__ __forceinline__ u32 draw_chunks(const u64 *__restrict__ held, u32 row_words, u32 s, u32 r, u64 idle,
-                                           uint4 *need_lds, int lane)
+template <int NP, class Rows>
+__device__ __forceinline__ u32 draw_chunks(const Rows &rows, u32 s, u32 r, u64 idle, uint4 *need_lds, int lane)
 {
   constexpr int NW = 2 * NP;
   constexpr int NDW = 4 * NP;
@@ -334,10 +375,9 @@ __device__ __forceinline__ u32 draw_chunks(const u64 *__restrict__ held, u32 row
   typename RT::B buf0_b, buf1_b;
   auto fetch = [&](typename RT::A &ba, typename RT::B &bb, u64 pending) {
     const u32 src = read_lane(s, (u32)__ffsll((long long)pending) - 1u);
-    const uint4 *sp = reinterpret_cast<const uint4 *>(held + (u64)src * row_words) + lane;
     static_for<0, NP>([&](auto I) {
       constexpr int i = decltype(I)::value;
-      const uint4 v = sp[i * 64];
+      const uint4 v = rows.load(src, i, lane);
       RT::template set<4 * i>(ba, bb, v.x); RT::template set<4 * i + 1>(ba, bb, v.y);
       RT::template set<4 * i + 2>(ba, bb, v.z); RT::template set<4 * i + 3>(ba, bb, v.w);
     });
@@ -416,9 +456,9 @@ __device__ __forceinline__ u32 draw_chunks(const u64 *__restrict__ held, u32 row
 // points at this wavefront's private NP*64 uint4.  Source rows land in two register
 // buffers used in turn, so that the next link's row is in flight while the current link
 // is decided; the candidate set is formed in place in the buffer.
-template <int NP, bool LATENCY_BOUND>
-__device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb, u32 je, u32 event, u64 t,
-                                                     u32 *__restrict__ sched_row, int lane, uint4 *need_lds,
+template <int NP, bool LATENCY_BOUND, class Rows>
+__device__ __forceinline__ u64 match_destination(const PassDev &p, const Rows &rows, u32 d, u32 jb, u32 je, u32 event,
+                                                     u64 t, u32 *__restrict__ sched_row, int lane, uint4 *need_lds,
                                                      const RecOut rec = RecOut())
 {
   constexpr int NW = 2 * NP;
@@ -431,11 +471,10 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb
   // links' random words are computed here.  Otherwise (one wavefront per destination of a
   // large topology, VALU- and bandwidth-bound) the random words were computed for all links
   // of the span by arrive_kernel, with every lane busy, and are read from p.rnd.
-  const uint4 *hp = reinterpret_cast<const uint4 *>(p.held + (u64)d * p.row_words) + lane;
   uint4 own[NP];
   if constexpr (LATENCY_BOUND) {
 #pragma unroll
-    for (int i = 0; i < NP; ++i) own[i] = hp[i * 64];
+    for (int i = 0; i < NP; ++i) own[i] = rows.load(d, i, lane);
   }
 
   u32 l0 = 0, s0 = 0, cr0 = kNone;
@@ -460,7 +499,7 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb
     for (int i = 0; i < NP; ++i) {
       uint4 v;
       if constexpr (LATENCY_BOUND) v = own[i];
-      else v = hp[i * 64];
+      else v = rows.load(d, i, lane);
       v.x = ~v.x; v.y = ~v.y; v.z = ~v.z; v.w = ~v.w;
       need_lds[i * 64 + lane] = v;
       acc |= v.x | v.y | v.z | v.w;
@@ -507,7 +546,7 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, u32 d, u32 jb
       u32 r = 0;
       if constexpr (LATENCY_BOUND) r = philox4x32_10_word0(l, event, p.phase, 0u, p.seed_lo, p.seed_hi);
       else if (valid) r = p.rnd[j];
-      res = draw_chunks<NP>(p.held, p.row_words, s, r, idle, need_lds, lane);
+      res = draw_chunks<NP>(rows, s, r, idle, need_lds, lane);
     }
     if (rec.recs) append_records(rec, valid && res != kNone, l, res, lane);
     if (valid) {
@@ -567,10 +606,10 @@ __device__ __forceinline__ void philox4x32_10_words01(u32 c0, u32 c1, u32 c2, u3
 // the chunk the lane's link carries or kNone.
 
 // Any in-degree up to 64: the rows of the free links are re-streamed (from L2) in every step.
-template <int NP>
-__device__ __forceinline__ u32 draw_pairs_streamed(const u64 *__restrict__ held, u32 row_words, u32 s, u64 free_links,
-                                                   u32 d, u32 event, u32 phase2, u32 seed_lo, u32 seed_hi,
-                                                   bool first_holder, uint4 *need_lds, int lane)
+template <int NP, class Rows>
+__device__ __forceinline__ u32 draw_pairs_streamed(const Rows &rows, u32 s, u64 free_links, u32 d, u32 event, u32 phase2,
+                                                   u32 seed_lo, u32 seed_hi, bool first_holder, uint4 *need_lds,
+                                                   int lane)
 {
   constexpr int NW = 2 * NP;
   constexpr int NDW = 4 * NP;
@@ -585,10 +624,9 @@ __device__ __forceinline__ u32 draw_pairs_streamed(const u64 *__restrict__ held,
       const u32 b = (u32)__ffsll((long long)todo) - 1u;
       todo &= todo - 1ull;
       const u32 src = read_lane(s, b);
-      const uint4 *sp = reinterpret_cast<const uint4 *>(held + (u64)src * row_words) + lane;
       static_for<0, NP>([&](auto I) {
         constexpr int i = decltype(I)::value;
-        const uint4 v = sp[i * 64];
+        const uint4 v = rows.load(src, i, lane);
         RT::template set<4 * i>(acc_a, acc_b, RT::template get<4 * i>(acc_a, acc_b) | v.x);
         RT::template set<4 * i + 1>(acc_a, acc_b, RT::template get<4 * i + 1>(acc_a, acc_b) | v.y);
         RT::template set<4 * i + 2>(acc_a, acc_b, RT::template get<4 * i + 2>(acc_a, acc_b) | v.z);
@@ -639,7 +677,7 @@ __device__ __forceinline__ u32 draw_pairs_streamed(const u64 *__restrict__ held,
     const u32 dword = ((idx >> 1) * 128u + ln * 2u + (idx & 1u)) * 2u + (bit >> 5);
     bool holds = false;
     if ((free_links >> lane) & 1ull) {
-      const u32 wv = reinterpret_cast<const u32 *>(held + (u64)s * row_words)[dword];
+      const u32 wv = rows.dword(s, dword);
       holds = (wv >> (bit & 31u)) & 1u;
     }
     const u64 holders = __ballot(holds);
@@ -660,10 +698,9 @@ __device__ __forceinline__ u32 draw_pairs_streamed(const u64 *__restrict__ held,
 // ONCE and stay in registers (DEG planes of a lane's share of a row), so that a step is
 // register and LDS work only: OR of the planes & need, selection, and the holders of the chosen
 // chunk from one dword of every plane; the plane of the link that was used is cleared.
-template <int NP, int DEG>
-__device__ __forceinline__ u32 draw_pairs_planes(const u64 *__restrict__ held, u32 row_words, u32 s, u64 free_links,
-                                                 u32 d, u32 event, u32 phase2, u32 seed_lo, u32 seed_hi,
-                                                 bool first_holder, uint4 *need_lds, int lane)
+template <int NP, int DEG, class Rows>
+__device__ __forceinline__ u32 draw_pairs_planes(const Rows &rows, u32 s, u64 free_links, u32 d, u32 event, u32 phase2,
+                                                 u32 seed_lo, u32 seed_hi, bool first_holder, uint4 *need_lds, int lane)
 {
   constexpr int NW = 2 * NP;
   constexpr int NDW = 4 * NP;
@@ -676,10 +713,10 @@ __device__ __forceinline__ u32 draw_pairs_planes(const u64 *__restrict__ held, u
     pa[j] = typename RT::A{};
     pb[j] = typename RT::B{};
     if ((free_links >> j) & 1ull) {
-      const uint4 *sp = reinterpret_cast<const uint4 *>(held + (u64)read_lane(s, (u32)j) * row_words) + lane;
+      const u32 src = read_lane(s, (u32)j);
       static_for<0, NP>([&](auto I) {
         constexpr int i = decltype(I)::value;
-        const uint4 v = sp[i * 64];
+        const uint4 v = rows.load(src, i, lane);
         RT::template set<4 * i>(pa[j], pb[j], v.x); RT::template set<4 * i + 1>(pa[j], pb[j], v.y);
         RT::template set<4 * i + 2>(pa[j], pb[j], v.z); RT::template set<4 * i + 3>(pa[j], pb[j], v.w);
       });
@@ -786,10 +823,10 @@ __device__ __forceinline__ u32 draw_pairs_planes(const u64 *__restrict__ held, u
 // The postcondition-centric matching of destination d at span `event` (time t): set-up of the
 // need row, one of the two cores above, and the link state of the matched links.  Returns (per
 // lane) the end time of the transfer on the lane's link, for the next-event reduction.
-template <int NP, int DEG>
-__device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, u32 jb, u32 je, u32 event, u64 t,
-                                                       u32 *__restrict__ sched_row, int lane, uint4 *need_lds,
-                                                       bool first_holder, const RecOut rec = RecOut())
+template <int NP, int DEG, class Rows>
+__device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, const Rows &rows, u32 d, u32 jb, u32 je,
+                                                       u32 event, u64 t, u32 *__restrict__ sched_row, int lane,
+                                                       uint4 *need_lds, bool first_holder, const RecOut rec = RecOut())
 {
   constexpr int NW = 2 * NP;
   Ctl *ctl = p.ctl;
@@ -807,11 +844,10 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
   u32 res = kNone;
 
   if (free_links) {
-    const uint4 *hp = reinterpret_cast<const uint4 *>(p.held + (u64)d * p.row_words) + lane;
     u32 acc = 0;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-      uint4 v = hp[i * 64];
+      uint4 v = rows.load(d, i, lane);
       v.x = ~v.x; v.y = ~v.y; v.z = ~v.z; v.w = ~v.w;
       need_lds[i * 64 + lane] = v;
       acc |= v.x | v.y | v.z | v.w;
@@ -828,11 +864,11 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, u32 d, 
     }
     if (need_any) {
       if (DEG > 0 && je - jb <= (u32)(DEG > 0 ? DEG : 1))
-        res = draw_pairs_planes<NP, (DEG > 0 ? DEG : 1)>(p.held, p.row_words, s, free_links, d, event, p.phase + 2u,
-                                                         p.seed_lo, p.seed_hi, first_holder, need_lds, lane);
+        res = draw_pairs_planes<NP, (DEG > 0 ? DEG : 1)>(rows, s, free_links, d, event, p.phase + 2u, p.seed_lo,
+                                                         p.seed_hi, first_holder, need_lds, lane);
       else
-        res = draw_pairs_streamed<NP>(p.held, p.row_words, s, free_links, d, event, p.phase + 2u, p.seed_lo,
-                                      p.seed_hi, first_holder, need_lds, lane);
+        res = draw_pairs_streamed<NP>(rows, s, free_links, d, event, p.phase + 2u, p.seed_lo, p.seed_hi, first_holder,
+                                      need_lds, lane);
     }
   }
   if (rec.recs) append_records(rec, valid && res != kNone, l, res, lane);
@@ -888,8 +924,9 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   __shared__ uint4 need_lds[4 * NP * 64];
   uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
   u64 my_min;
-  if constexpr (MODE == 0) my_min = match_destination<NP, false>(p, d, jb, je, event, t, sched_row, lane, my_need);
-  else my_min = match_destination_pairs<NP, DEG>(p, d, jb, je, event, t, sched_row, lane, my_need, MODE == 2);
+  const RowsHbm rows{p.held, p.row_words};
+  if constexpr (MODE == 0) my_min = match_destination<NP, false>(p, rows, d, jb, je, event, t, sched_row, lane, my_need);
+  else my_min = match_destination_pairs<NP, DEG>(p, rows, d, jb, je, event, t, sched_row, lane, my_need, MODE == 2);
 
   // a8: next span = earliest end of a transfer in flight (min over all destinations)
   const u64 m = wave_min64(my_min);
@@ -964,7 +1001,7 @@ __device__ __forceinline__ bool match_destination_uniform(const PassDev &p, cons
       l = rec.x; s = rec.y;
       r = rnd[j];
     }
-    const u32 res = draw_chunks<NP>(H, p.row_words, s, r, __ballot(valid), need_lds, lane);
+    const u32 res = draw_chunks<NP>(RowsHbm{H, p.row_words}, s, r, __ballot(valid), need_lds, lane);
     if (valid) {
       prev_out[j] = res;
       if (res != kNone) {
@@ -1232,7 +1269,10 @@ __global__ __launch_bounds__(256) void match_kernel_streamed(PassDev p, u32 even
 //
 // LDS layout (dynamic): u64 free_at[L rounded up to even] | u32 carry[L] | u32 stamp[N] |
 // u32 work[N] | uint4 need[16][NP][64] | u64 next[2] | u32 counters[4] | Ctl shadow |
-// (if it still fits) u32 pos_dst[L].  Link state is indexed by in-list position, as in HBM.
+// and, each while it still fits: u32 pos_dst[L] | the held table without its padding lanes
+// (RowsLds: N * ceil(C / 128) * 16 bytes when NP = 1) | uint4 in_rec[L], u32 in_ptr[N + 1].
+// Link state is indexed by in-list position, as in HBM.  With the held table in LDS a span of
+// a small topology touches device memory only to append schedule records.
 __host__ __device__ inline size_t small_lds_bytes(u32 N, u32 L, u32 NP)
 {
   size_t b = (((size_t)L + 1) & ~(size_t)1) * 8;
@@ -1250,12 +1290,12 @@ constexpr size_t kLdsPerWorkgroup = 160 * 1024;  // gfx950
 // stores and atomics are not waited for.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int NP, int MODE>
+template <int NP, int MODE, bool HELD_LDS>
 __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__restrict__ out_ptr,
                                                  const u32 *__restrict__ out_dst, u32 first_event,
                                                  u32 n_events, u32 stop_event, uint2 *__restrict__ recs,
                                                  u32 *__restrict__ span_first, u64 *__restrict__ event_times,
-                                                 u32 dst_in_lds)
+                                                 u32 dst_in_lds, u32 held_lanes, u32 rec_in_lds)
 {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const u32 Lp = (p.L + 1u) & ~1u;
@@ -1271,6 +1311,15 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   u32 *s_cnt = reinterpret_cast<u32 *>(cur); cur += 16;
   Ctl *s_ctl = reinterpret_cast<Ctl *>(cur); cur += (sizeof(Ctl) + 15) & ~(size_t)15;  // status / done of the matching code
   u32 *s_dst = reinterpret_cast<u32 *>(cur);
+  if (dst_in_lds) cur += ((size_t)p.L * 4 + 15) & ~(size_t)15;
+  // HELD_LDS: the held table itself, without the lanes that own no chunk (RowsLds)
+  const RowsLds lrows{reinterpret_cast<uint4 *>(cur), held_lanes, (u32)NP * held_lanes};
+  const RowsHbm grows{p.held, p.row_words};
+  if constexpr (HELD_LDS) cur += (size_t)p.N * NP * held_lanes * 16;
+  // rec_in_lds: the in-list records and the in-list offsets, so that setting up a destination
+  // costs no memory round trip
+  uint4 *s_rec = reinterpret_cast<uint4 *>(cur); cur += rec_in_lds ? (size_t)p.L * 16 : 0;
+  u32 *s_inptr = reinterpret_cast<u32 *>(cur);
 
   const u32 tid = threadIdx.x;
   const int lane = tid & 63;
@@ -1289,6 +1338,14 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
     s_ctl->status = 0u; s_ctl->done = 0u;
     s_next[0] = kInf; s_next[1] = kInf;
   }
+  if constexpr (HELD_LDS) {
+    const uint4 *g = reinterpret_cast<const uint4 *>(p.held);
+    for (u32 i = tid; i < p.N * lrows.row_u4; i += 1024u) {
+      const u32 npu = i / lrows.row_u4, rem = i - npu * lrows.row_u4;
+      const u32 piece = rem / held_lanes, ln = rem - piece * held_lanes;
+      lrows.base[i] = g[(u64)npu * (p.row_words / 2u) + piece * 64u + ln];
+    }
+  }
   const RecOut rec_fwd = (recs && !p.reversed) ? RecOut{recs, &s_cnt[2]} : RecOut();
   const u32 *pos_dst = p.pos_dst;
   if (dst_in_lds) {
@@ -1299,6 +1356,13 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   q.carry = s_carry;
   q.free_at = s_free;
   q.ctl = s_ctl;
+  const u32 *in_ptr = p.in_ptr;
+  if (rec_in_lds) {
+    for (u32 l = tid; l < p.L; l += 1024u) s_rec[l] = p.in_rec[l];
+    for (u32 n = tid; n <= p.N; n += 1024u) s_inptr[n] = p.in_ptr[n];
+    q.in_rec = s_rec;
+    in_ptr = s_inptr;
+  }
   u64 t = ctl->next_t[first_event & 1u];
   u64 remaining = ctl->remaining;
   u32 e = first_event;
@@ -1329,7 +1393,8 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
           if (s_free[l] != t) continue;
           const u32 c = s_carry[l];
           const u32 d = pos_dst[l];
-          atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
+          if constexpr (HELD_LDS) atomicOr(lrows.word_of(d, c, (u32)NP), 1ull << (c & 63u));
+          else atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
           s_carry[l] = kNone;
           s_free[l] = kInf;
           atomicAdd(&s_cnt[1], 1u);
@@ -1363,12 +1428,17 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
     const u32 n_work = (e == 0u) ? p.N : n_arr + s_cnt[0];
     for (u32 i = wave; i < n_work; i += 16u) {
       const u32 d = uniform((e == 0u) ? i : s_work[i]);
-      const u32 jb = p.in_ptr[d], je = p.in_ptr[d + 1];
-      if constexpr (MODE == 0)
-        (void)match_destination<NP, true>(q, d, jb, je, e, t, nullptr, lane, s_need + wave * NP * 64, rec_fwd);
-      else
-        (void)match_destination_pairs<NP, 8>(q, d, jb, je, e, t, nullptr, lane, s_need + wave * NP * 64, MODE == 2,
-                                             rec_fwd);
+      const u32 jb = in_ptr[d], je = in_ptr[d + 1];
+      uint4 *my_need = s_need + wave * NP * 64;
+      if constexpr (MODE == 0) {
+        if constexpr (HELD_LDS) (void)match_destination<NP, true>(q, lrows, d, jb, je, e, t, nullptr, lane, my_need, rec_fwd);
+        else (void)match_destination<NP, true>(q, grows, d, jb, je, e, t, nullptr, lane, my_need, rec_fwd);
+      } else {
+        if constexpr (HELD_LDS)
+          (void)match_destination_pairs<NP, 8>(q, lrows, d, jb, je, e, t, nullptr, lane, my_need, MODE == 2, rec_fwd);
+        else
+          (void)match_destination_pairs<NP, 8>(q, grows, d, jb, je, e, t, nullptr, lane, my_need, MODE == 2, rec_fwd);
+      }
     }
     lds_barrier();
     // ---- next span = earliest end of a transfer in flight (a8), reduced in LDS
@@ -1393,30 +1463,40 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   // ---- hand the state back for the next launch
   __syncthreads();
   for (u32 l = tid; l < p.L; l += 1024u) { p.free_at[l] = s_free[l]; p.carry[l] = s_carry[l]; }
+  if constexpr (HELD_LDS) {
+    uint4 *g = reinterpret_cast<uint4 *>(p.held);
+    for (u32 i = tid; i < p.N * lrows.row_u4; i += 1024u) {
+      const u32 npu = i / lrows.row_u4, rem = i - npu * lrows.row_u4;
+      const u32 piece = rem / held_lanes, ln = rem - piece * held_lanes;
+      g[(u64)npu * (p.row_words / 2u) + piece * 64u + ln] = lrows.base[i];
+    }
+  }
   if (tid == 0 && !finished) ctl->next_t[e & 1u] = t;
   if (tid == 0) { ctl->remaining = remaining; ctl->n_rec = s_cnt[2]; }
 }
 
-template <int NP, int MODE>
+template <int NP, int MODE, bool HELD_LDS>
 __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 *__restrict__ out_ptr,
                                                            const u32 *__restrict__ out_dst, u32 first_event,
                                                            u32 n_events, u32 stop_event,
                                                            uint2 *__restrict__ recs, u32 *__restrict__ span_first,
-                                                           u64 *__restrict__ event_times, u32 dst_in_lds)
+                                                           u64 *__restrict__ event_times, u32 dst_in_lds, u32 held_lanes,
+                                                           u32 rec_in_lds)
 {
-  small_sweep_body<NP, MODE>(p, out_ptr, out_dst, first_event, n_events, stop_event, recs, span_first, event_times,
-                             dst_in_lds);
+  small_sweep_body<NP, MODE, HELD_LDS>(p, out_ptr, out_dst, first_event, n_events, stop_event, recs, span_first,
+                                       event_times, dst_in_lds, held_lanes, rec_in_lds);
 }
 
 // Many independent passes at once (one per workgroup, each with its own seed, rows, link
 // state and control block): only the collective times are wanted, no schedule is kept.
-template <int NP, int MODE>
+template <int NP, int MODE, bool HELD_LDS>
 __global__ __launch_bounds__(1024) void small_sweep_batch_kernel(const SmallJob *__restrict__ jobs, u32 first_event,
-                                                                 u32 n_events, u32 dst_in_lds)
+                                                                 u32 n_events, u32 dst_in_lds, u32 held_lanes,
+                                                                 u32 rec_in_lds)
 {
   const SmallJob &j = jobs[blockIdx.x];
-  small_sweep_body<NP, MODE>(j.p, j.out_ptr, j.out_dst, first_event, n_events, 0xFFFFFFFFu, nullptr, nullptr, nullptr,
-                             dst_in_lds);
+  small_sweep_body<NP, MODE, HELD_LDS>(j.p, j.out_ptr, j.out_dst, first_event, n_events, 0xFFFFFFFFu, nullptr, nullptr,
+                                       nullptr, dst_in_lds, held_lanes, rec_in_lds);
 }
 
 // ---------------------------------------------------------------- epilogue
@@ -1795,12 +1875,23 @@ static size_t lds_limit()
   return (size_t)v < kLdsPerWorkgroup ? (size_t)v : kLdsPerWorkgroup;
 }
 
-static size_t small_launch_lds(const PassDev &p, u32 *dst_in_lds)
+// LDS of one single-workgroup launch: the link state, and while they still fit the held table
+// (without its padding lanes) and the link destinations.
+static size_t small_launch_lds(const PassDev &p, u32 *dst_in_lds, u32 *held_lanes, u32 *rec_in_lds)
 {
   size_t lds = small_lds_bytes(p.N, p.L, p.NP);
+  const size_t limit = lds_limit();
+  const u32 lanes = (p.C + 128u * p.NP - 1u) / (128u * p.NP);
+  const size_t held_bytes = (size_t)p.N * p.NP * lanes * 16;
   const size_t dst_bytes = ((size_t)p.L * 4 + 15) & ~(size_t)15;
-  *dst_in_lds = lds + dst_bytes <= lds_limit() ? 1u : 0u;
+  const size_t rec_bytes = (size_t)p.L * 16 + (((size_t)p.N + 1) * 4 + 15 & ~(size_t)15);
+  // in the order the kernel lays them out: link destinations, held table, in-list records
+  *dst_in_lds = lds + dst_bytes <= limit ? 1u : 0u;
   if (*dst_in_lds) lds += dst_bytes;
+  *held_lanes = lds + held_bytes <= limit ? lanes : 0u;
+  if (*held_lanes) lds += held_bytes;
+  *rec_in_lds = lds + rec_bytes <= limit ? 1u : 0u;
+  if (*rec_in_lds) lds += rec_bytes;
   return lds;
 }
 
@@ -1809,13 +1900,18 @@ static hipError_t launch_small_np(const PassDev &p, const u32 *out_ptr, const u3
                                   u32 n_events, u32 stop_event, uint2 *recs, u32 *span_first, u64 *event_times,
                                   hipStream_t s)
 {
-  u32 dst_in_lds = 0;
-  const size_t lds = small_launch_lds(p, &dst_in_lds);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&small_sweep_kernel<NP, MODE>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  u32 dst_in_lds = 0, held_lanes = 0, rec_in_lds = 0;
+  const size_t lds = small_launch_lds(p, &dst_in_lds, &held_lanes, &rec_in_lds);
+  const void *fn = held_lanes ? reinterpret_cast<const void *>(&small_sweep_kernel<NP, MODE, true>)
+                              : reinterpret_cast<const void *>(&small_sweep_kernel<NP, MODE, false>);
+  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((small_sweep_kernel<NP, MODE>), dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst, first_event,
-                     n_events, stop_event, recs, span_first, event_times, dst_in_lds);
+  if (held_lanes)
+    hipLaunchKernelGGL((small_sweep_kernel<NP, MODE, true>), dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst,
+                       first_event, n_events, stop_event, recs, span_first, event_times, dst_in_lds, held_lanes, rec_in_lds);
+  else
+    hipLaunchKernelGGL((small_sweep_kernel<NP, MODE, false>), dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst,
+                       first_event, n_events, stop_event, recs, span_first, event_times, dst_in_lds, held_lanes, rec_in_lds);
   return hipGetLastError();
 }
 
@@ -1823,13 +1919,18 @@ template <int NP, int MODE>
 static hipError_t launch_batch_np(const SmallJob *jobs, u32 n_jobs, const PassDev &p0, u32 first_event,
                                   u32 n_events, hipStream_t s)
 {
-  u32 dst_in_lds = 0;
-  const size_t lds = small_launch_lds(p0, &dst_in_lds);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&small_sweep_batch_kernel<NP, MODE>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  u32 dst_in_lds = 0, held_lanes = 0, rec_in_lds = 0;
+  const size_t lds = small_launch_lds(p0, &dst_in_lds, &held_lanes, &rec_in_lds);
+  const void *fn = held_lanes ? reinterpret_cast<const void *>(&small_sweep_batch_kernel<NP, MODE, true>)
+                              : reinterpret_cast<const void *>(&small_sweep_batch_kernel<NP, MODE, false>);
+  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((small_sweep_batch_kernel<NP, MODE>), dim3(n_jobs), dim3(1024), lds, s, jobs, first_event,
-                     n_events, dst_in_lds);
+  if (held_lanes)
+    hipLaunchKernelGGL((small_sweep_batch_kernel<NP, MODE, true>), dim3(n_jobs), dim3(1024), lds, s, jobs, first_event,
+                       n_events, dst_in_lds, held_lanes, rec_in_lds);
+  else
+    hipLaunchKernelGGL((small_sweep_batch_kernel<NP, MODE, false>), dim3(n_jobs), dim3(1024), lds, s, jobs, first_event,
+                       n_events, dst_in_lds, held_lanes, rec_in_lds);
   return hipGetLastError();
 }
 
