@@ -1246,6 +1246,108 @@ __global__ __launch_bounds__(256) void match_kernel_streamed(PassDev p, u32 even
   }
 }
 
+// ---------------------------------------------------------------- few chunks: a lane per destination
+
+// Position of the k-th (0-based) set bit of x, k < popcount(x): binary search on popcounts.
+__device__ __forceinline__ u32 kth_set_bit64(u64 x, u32 k)
+{
+  u32 pos = 0;
+  u32 c = (u32)__popc((u32)x);
+  u32 w = (u32)x;
+  if (k >= c) { k -= c; pos = 32; w = (u32)(x >> 32); }
+#pragma unroll
+  for (u32 width = 16; width >= 1; width >>= 1) {
+    const u32 lowbits = w & ((1u << width) - 1u);
+    c = (u32)__popc(lowbits);
+    if (k >= c) { k -= c; pos += width; w >>= width; }
+    else w = lowbits;
+  }
+  return pos;
+}
+
+// Link-centric matching (Algorithm 1, as match_destination) when a bitset row is at most W
+// 64-bit words (W * 64 chunks): ONE LANE per destination instead of one wavefront, every lane
+// walking its own destination's idle incoming links in list order with its need row in
+// registers, so that a wavefront matches 64 destinations at once.  Rows, in-list records and
+// offsets and the link state are in LDS (single-workgroup kernel).  active: the lane has a
+// destination d; all lanes of the wavefront must call this together.
+template <int W>
+__device__ __forceinline__ void match_destinations_by_lane(const PassDev &q, const RowsLds &rows, const u32 *in_ptr, u32 d,
+                                                           bool active, u32 event, u64 t, const RecOut rec, int lane)
+{
+  Ctl *ctl = q.ctl;
+  const u32 nw = 2u * rows.lanes;  // words of a row that hold chunk ids (NP = 1: lane j owns words 2j, 2j + 1)
+  u32 jb = 0, deg = 0;
+  if (active) { jb = in_ptr[d]; deg = in_ptr[d + 1] - jb; }
+  u64 need[W];
+  {
+    const u64 *own = reinterpret_cast<const u64 *>(rows.base + d * rows.row_u4);
+#pragma unroll
+    for (int w = 0; w < W; ++w) need[w] = (active && (u32)w < nw) ? ~own[w] : 0ull;
+  }
+  bool any_idle = false;
+  for (u32 jr = 0; jr < deg; ++jr) {  // chunks in flight to d are not needed
+    const u32 c = q.carry[jb + jr];
+    if (c == kNone) { any_idle = true; continue; }
+#pragma unroll
+    for (int w = 0; w < W; ++w)
+      if ((c >> 6) == (u32)w) need[w] &= ~(1ull << (c & 63u));
+  }
+  u64 any = 0;
+#pragma unroll
+  for (int w = 0; w < W; ++w) any |= need[w];
+  if (any_idle && any != 0ull) ctl->need_flag[event & 1u] = 1u;
+  for (u32 jr = 0; __ballot(jr < deg) != 0ull; ++jr) {
+    bool has = false;
+    u32 link = 0, chunk = kNone;
+    const u32 j = jb + jr;
+    if (jr < deg && any != 0ull && q.carry[j] == kNone) {
+      const uint4 ir = q.in_rec[j];  // (link, source, cost lo, cost hi)
+      const u64 *srow = reinterpret_cast<const u64 *>(rows.base + ir.y * rows.row_u4);
+      u64 cand[W];
+      u32 p = 0;
+#pragma unroll
+      for (int w = 0; w < W; ++w) {
+        cand[w] = (u32)w < nw ? srow[w] & need[w] : 0ull;
+        p += (u32)__popcll(cand[w]);
+      }
+      if (p != 0u) {
+        u32 k = philox4x32_10_word0(ir.x, event, q.phase, 0u, q.seed_lo, q.seed_hi) % p;
+        u32 wsel = 0;
+        u64 word = 0;
+        bool found = false;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+          const u32 c = (u32)__popcll(cand[w]);
+          if (!found) {
+            if (k < c) { found = true; wsel = (u32)w; word = cand[w]; }
+            else k -= c;
+          }
+        }
+        const u32 bit = kth_set_bit64(word, k);
+        chunk = (wsel << 6) + bit;
+#pragma unroll
+        for (int w = 0; w < W; ++w)
+          if (wsel == (u32)w) need[w] &= ~(1ull << bit);
+        const u64 cs = ((u64)ir.w << 32) | ir.z;
+        if (chunk >= q.C) {
+          ctl->status = kStInternal;
+          ctl->done = 1u;
+        } else if (cs > kInf - 1ull - t) {
+          ctl->status = kStOverflow;
+          ctl->done = 1u;
+        } else {
+          q.carry[j] = chunk;
+          q.free_at[j] = t + cs;
+          has = true;
+          link = ir.x;
+        }
+      }
+    }
+    if (rec.recs) append_records(rec, has, link, chunk, lane);
+  }
+}
+
 // ---------------------------------------------------------------- small topologies
 
 // One workgroup of 16 wavefronts sweeps many TEN spans without leaving the chip: the
@@ -1290,7 +1392,9 @@ constexpr size_t kLdsPerWorkgroup = 160 * 1024;  // gfx950
 // stores and atomics are not waited for.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int NP, int MODE, bool HELD_LDS>
+// TW > 0 (link-centric matching, NP = 1, rows of at most TW 64-bit words, held table and in-list
+// records in LDS): destinations are matched one per LANE (match_destinations_by_lane).
+template <int NP, int MODE, bool HELD_LDS, int TW>
 __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__restrict__ out_ptr,
                                                  const u32 *__restrict__ out_dst, u32 first_event,
                                                  u32 n_events, u32 stop_event, uint2 *__restrict__ recs,
@@ -1426,6 +1530,14 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
     if (e == stop_event) break;  // prefix run: time reached is next_t[e & 1]
     // ---- matching (a5-a7) for the destinations on the work list (all of them at span 0)
     const u32 n_work = (e == 0u) ? p.N : n_arr + s_cnt[0];
+    if constexpr (TW > 0) {
+      for (u32 i0 = wave * 64u; i0 < n_work; i0 += 1024u) {
+        const u32 i = i0 + (u32)lane;
+        const bool active = i < n_work;
+        const u32 d = active ? ((e == 0u) ? i : s_work[i]) : 0u;
+        match_destinations_by_lane<(TW > 0 ? TW : 1)>(q, lrows, in_ptr, d, active, e, t, rec_fwd, lane);
+      }
+    } else
     for (u32 i = wave; i < n_work; i += 16u) {
       const u32 d = uniform((e == 0u) ? i : s_work[i]);
       const u32 jb = in_ptr[d], je = in_ptr[d + 1];
@@ -1475,7 +1587,7 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   if (tid == 0) { ctl->remaining = remaining; ctl->n_rec = s_cnt[2]; }
 }
 
-template <int NP, int MODE, bool HELD_LDS>
+template <int NP, int MODE, bool HELD_LDS, int TW>
 __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 *__restrict__ out_ptr,
                                                            const u32 *__restrict__ out_dst, u32 first_event,
                                                            u32 n_events, u32 stop_event,
@@ -1483,20 +1595,20 @@ __global__ __launch_bounds__(1024) void small_sweep_kernel(PassDev p, const u32 
                                                            u64 *__restrict__ event_times, u32 dst_in_lds, u32 held_lanes,
                                                            u32 rec_in_lds)
 {
-  small_sweep_body<NP, MODE, HELD_LDS>(p, out_ptr, out_dst, first_event, n_events, stop_event, recs, span_first,
-                                       event_times, dst_in_lds, held_lanes, rec_in_lds);
+  small_sweep_body<NP, MODE, HELD_LDS, TW>(p, out_ptr, out_dst, first_event, n_events, stop_event, recs, span_first,
+                                           event_times, dst_in_lds, held_lanes, rec_in_lds);
 }
 
 // Many independent passes at once (one per workgroup, each with its own seed, rows, link
 // state and control block): only the collective times are wanted, no schedule is kept.
-template <int NP, int MODE, bool HELD_LDS>
+template <int NP, int MODE, bool HELD_LDS, int TW>
 __global__ __launch_bounds__(1024) void small_sweep_batch_kernel(const SmallJob *__restrict__ jobs, u32 first_event,
                                                                  u32 n_events, u32 dst_in_lds, u32 held_lanes,
                                                                  u32 rec_in_lds)
 {
   const SmallJob &j = jobs[blockIdx.x];
-  small_sweep_body<NP, MODE, HELD_LDS>(j.p, j.out_ptr, j.out_dst, first_event, n_events, 0xFFFFFFFFu, nullptr, nullptr,
-                                       nullptr, dst_in_lds, held_lanes, rec_in_lds);
+  small_sweep_body<NP, MODE, HELD_LDS, TW>(j.p, j.out_ptr, j.out_dst, first_event, n_events, 0xFFFFFFFFu, nullptr,
+                                           nullptr, nullptr, dst_in_lds, held_lanes, rec_in_lds);
 }
 
 // ---------------------------------------------------------------- epilogue
@@ -1895,6 +2007,26 @@ static size_t small_launch_lds(const PassDev &p, u32 *dst_in_lds, u32 *held_lane
   return lds;
 }
 
+// Words per row (2, 4, 8, 16) of the lane-per-destination variant that takes this launch, or 0.
+template <int NP, int MODE> static int tiny_words(u32 held_lanes, u32 rec_in_lds)
+{
+  if (NP != 1 || MODE != 0 || held_lanes == 0 || held_lanes > 8 || !rec_in_lds) return 0;
+  return held_lanes == 1 ? 2 : held_lanes == 2 ? 4 : held_lanes <= 4 ? 8 : 16;
+}
+
+template <int NP, int MODE, bool HELD_LDS, int TW>
+static hipError_t launch_small_variant(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
+                                       u32 n_events, u32 stop_event, uint2 *recs, u32 *span_first, u64 *event_times,
+                                       size_t lds, u32 dst_in_lds, u32 held_lanes, u32 rec_in_lds, hipStream_t s)
+{
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&small_sweep_kernel<NP, MODE, HELD_LDS, TW>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((small_sweep_kernel<NP, MODE, HELD_LDS, TW>), dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst,
+                     first_event, n_events, stop_event, recs, span_first, event_times, dst_in_lds, held_lanes, rec_in_lds);
+  return hipGetLastError();
+}
+
 template <int NP, int MODE>
 static hipError_t launch_small_np(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
                                   u32 n_events, u32 stop_event, uint2 *recs, u32 *span_first, u64 *event_times,
@@ -1902,16 +2034,32 @@ static hipError_t launch_small_np(const PassDev &p, const u32 *out_ptr, const u3
 {
   u32 dst_in_lds = 0, held_lanes = 0, rec_in_lds = 0;
   const size_t lds = small_launch_lds(p, &dst_in_lds, &held_lanes, &rec_in_lds);
-  const void *fn = held_lanes ? reinterpret_cast<const void *>(&small_sweep_kernel<NP, MODE, true>)
-                              : reinterpret_cast<const void *>(&small_sweep_kernel<NP, MODE, false>);
-  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+#define TACOS_VARIANT(H_, T_)                                                                                         \
+  return launch_small_variant<NP, MODE, H_, T_>(p, out_ptr, out_dst, first_event, n_events, stop_event, recs, span_first, \
+                                                event_times, lds, dst_in_lds, held_lanes, rec_in_lds, s)
+  if constexpr (NP == 1 && MODE == 0) {
+    switch (tiny_words<NP, MODE>(held_lanes, rec_in_lds)) {
+      case 2: TACOS_VARIANT(true, 2);
+      case 4: TACOS_VARIANT(true, 4);
+      case 8: TACOS_VARIANT(true, 8);
+      case 16: TACOS_VARIANT(true, 16);
+      default: break;
+    }
+  }
+  if (held_lanes) TACOS_VARIANT(true, 0);
+  TACOS_VARIANT(false, 0);
+#undef TACOS_VARIANT
+}
+
+template <int NP, int MODE, bool HELD_LDS, int TW>
+static hipError_t launch_batch_variant(const SmallJob *jobs, u32 n_jobs, u32 first_event, u32 n_events, size_t lds,
+                                       u32 dst_in_lds, u32 held_lanes, u32 rec_in_lds, hipStream_t s)
+{
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&small_sweep_batch_kernel<NP, MODE, HELD_LDS, TW>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  if (held_lanes)
-    hipLaunchKernelGGL((small_sweep_kernel<NP, MODE, true>), dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst,
-                       first_event, n_events, stop_event, recs, span_first, event_times, dst_in_lds, held_lanes, rec_in_lds);
-  else
-    hipLaunchKernelGGL((small_sweep_kernel<NP, MODE, false>), dim3(1), dim3(1024), lds, s, p, out_ptr, out_dst,
-                       first_event, n_events, stop_event, recs, span_first, event_times, dst_in_lds, held_lanes, rec_in_lds);
+  hipLaunchKernelGGL((small_sweep_batch_kernel<NP, MODE, HELD_LDS, TW>), dim3(n_jobs), dim3(1024), lds, s, jobs,
+                     first_event, n_events, dst_in_lds, held_lanes, rec_in_lds);
   return hipGetLastError();
 }
 
@@ -1921,17 +2069,20 @@ static hipError_t launch_batch_np(const SmallJob *jobs, u32 n_jobs, const PassDe
 {
   u32 dst_in_lds = 0, held_lanes = 0, rec_in_lds = 0;
   const size_t lds = small_launch_lds(p0, &dst_in_lds, &held_lanes, &rec_in_lds);
-  const void *fn = held_lanes ? reinterpret_cast<const void *>(&small_sweep_batch_kernel<NP, MODE, true>)
-                              : reinterpret_cast<const void *>(&small_sweep_batch_kernel<NP, MODE, false>);
-  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
-  if (held_lanes)
-    hipLaunchKernelGGL((small_sweep_batch_kernel<NP, MODE, true>), dim3(n_jobs), dim3(1024), lds, s, jobs, first_event,
-                       n_events, dst_in_lds, held_lanes, rec_in_lds);
-  else
-    hipLaunchKernelGGL((small_sweep_batch_kernel<NP, MODE, false>), dim3(n_jobs), dim3(1024), lds, s, jobs, first_event,
-                       n_events, dst_in_lds, held_lanes, rec_in_lds);
-  return hipGetLastError();
+#define TACOS_VARIANT(H_, T_) \
+  return launch_batch_variant<NP, MODE, H_, T_>(jobs, n_jobs, first_event, n_events, lds, dst_in_lds, held_lanes, rec_in_lds, s)
+  if constexpr (NP == 1 && MODE == 0) {
+    switch (tiny_words<NP, MODE>(held_lanes, rec_in_lds)) {
+      case 2: TACOS_VARIANT(true, 2);
+      case 4: TACOS_VARIANT(true, 4);
+      case 8: TACOS_VARIANT(true, 8);
+      case 16: TACOS_VARIANT(true, 16);
+      default: break;
+    }
+  }
+  if (held_lanes) TACOS_VARIANT(true, 0);
+  TACOS_VARIANT(false, 0);
+#undef TACOS_VARIANT
 }
 
 hipError_t launch_small_sweep(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
