@@ -1420,9 +1420,9 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   const RowsLds lrows{reinterpret_cast<uint4 *>(cur), held_lanes, (u32)NP * held_lanes};
   const RowsHbm grows{p.held, p.row_words};
   if constexpr (HELD_LDS) cur += (size_t)p.N * NP * held_lanes * 16;
-  // rec_in_lds: the in-list records and the in-list offsets, so that setting up a destination
-  // costs no memory round trip
-  uint4 *s_rec = reinterpret_cast<uint4 *>(cur); cur += rec_in_lds ? (size_t)p.L * 16 : 0;
+  // rec_in_lds bit 0: the in-list records, bit 1: the in-list offsets, so that setting up a
+  // destination costs one memory round trip less each
+  uint4 *s_rec = reinterpret_cast<uint4 *>(cur); cur += (rec_in_lds & 1u) ? (size_t)p.L * 16 : 0;
   u32 *s_inptr = reinterpret_cast<u32 *>(cur);
 
   const u32 tid = threadIdx.x;
@@ -1461,10 +1461,12 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   q.free_at = s_free;
   q.ctl = s_ctl;
   const u32 *in_ptr = p.in_ptr;
-  if (rec_in_lds) {
+  if (rec_in_lds & 1u) {
     for (u32 l = tid; l < p.L; l += 1024u) s_rec[l] = p.in_rec[l];
-    for (u32 n = tid; n <= p.N; n += 1024u) s_inptr[n] = p.in_ptr[n];
     q.in_rec = s_rec;
+  }
+  if (rec_in_lds & 2u) {
+    for (u32 n = tid; n <= p.N; n += 1024u) s_inptr[n] = p.in_ptr[n];
     in_ptr = s_inptr;
   }
   u64 t = ctl->next_t[first_event & 1u];
@@ -1996,21 +1998,23 @@ static size_t small_launch_lds(const PassDev &p, u32 *dst_in_lds, u32 *held_lane
   const u32 lanes = (p.C + 128u * p.NP - 1u) / (128u * p.NP);
   const size_t held_bytes = (size_t)p.N * p.NP * lanes * 16;
   const size_t dst_bytes = ((size_t)p.L * 4 + 15) & ~(size_t)15;
-  const size_t rec_bytes = (size_t)p.L * 16 + (((size_t)p.N + 1) * 4 + 15 & ~(size_t)15);
+  const size_t ptr_bytes = ((size_t)p.N + 1) * 4 + 15 & ~(size_t)15;
+  const size_t rec_bytes = (size_t)p.L * 16;
   // in the order the kernel lays them out: link destinations, held table, in-list records
   *dst_in_lds = lds + dst_bytes <= limit ? 1u : 0u;
   if (*dst_in_lds) lds += dst_bytes;
   *held_lanes = lds + held_bytes <= limit ? lanes : 0u;
   if (*held_lanes) lds += held_bytes;
-  *rec_in_lds = lds + rec_bytes <= limit ? 1u : 0u;
-  if (*rec_in_lds) lds += rec_bytes;
+  *rec_in_lds = 0u;
+  if (lds + ptr_bytes <= limit) { *rec_in_lds |= 2u; lds += ptr_bytes; }  // offsets first: they are small
+  if (lds + rec_bytes <= limit) { *rec_in_lds |= 1u; lds += rec_bytes; }
   return lds;
 }
 
 // Words per row (2, 4, 8, 16) of the lane-per-destination variant that takes this launch, or 0.
 template <int NP, int MODE> static int tiny_words(u32 held_lanes, u32 rec_in_lds)
 {
-  if (NP != 1 || MODE != 0 || held_lanes == 0 || held_lanes > 8 || !rec_in_lds) return 0;
+  if (NP != 1 || MODE != 0 || held_lanes == 0 || held_lanes > 8 || rec_in_lds != 3u) return 0;
   return held_lanes == 1 ? 2 : held_lanes == 2 ? 4 : held_lanes <= 4 ? 8 : 16;
 }
 
