@@ -13,6 +13,10 @@ minutes) and stores its time, sweeps, records, digest and the SHA-256 of the per
 (time, match count) trace in workload5_oracle.json.  Of its 1.68e9 records the first 4096 and
 16 windows of 65,536 spread over the whole schedule (the last one ends it) are hashed.
 
+    python tests/golden/make_golden.py --with-5 --matching1 [--threads 8]
+
+the same workload with the postcondition-centric matching order (workload5_matching1_oracle.json).
+
     python tests/golden/make_golden.py --scalability 6 [--threads 8]      (or 7)
 
 runs the paper's scalability workload (6: All-Reduce on the 200x200 mesh, 7: on the
@@ -39,6 +43,24 @@ from paper_2304_05301_amd import topologies as T  # noqa: E402
 W5_XFERS = 40_960 * 40_959          # records of the 40,960-NPU All-Gather
 W5_BLOCK = 65_536                   # records per sampled window
 W5_STRIDE = 104_857_600             # distance between windows: 16 of them, the last one ends the schedule
+
+
+def workload5_matching1(threads):
+    """Workload 5 with Algorithm 1's own (postcondition-centric) order: digest, trace and the
+    first 4096 records."""
+    w = T.workload(5)
+    oracle.set_progress(500)
+    r = oracle.synthesize_workload(w, keep_first=0, keep_xfers=4096, n_threads=threads, matching=1)
+    out = {
+        "name": w.name, "topology": w.topo.name, "matching": 1,
+        "collective_time_ps": r.collective_time_ps, "n_events": r.n_events, "n_xfers": r.n_xfers, "digest": r.digest,
+        "sha256_event_trace": hashlib.sha256(r.event_times.tobytes() + r.event_matches.tobytes()).hexdigest(),
+        "sha256_first_4096_xfers": hashlib.sha256(r.xfers.tobytes()).hexdigest(),
+    }
+    print("5 matching 1", out, flush=True)
+    with open(os.path.join(HERE, "workload5_matching1_oracle.json"), "w") as f:
+        json.dump(out, f, indent=1, sort_keys=True)
+        f.write("\n")
 
 
 def workload5(threads):
@@ -121,7 +143,10 @@ def main():
         return
     if "--with-5" in sys.argv:
         threads = int(sys.argv[sys.argv.index("--threads") + 1]) if "--threads" in sys.argv else 8
-        workload5(threads)
+        if "--matching1" in sys.argv:
+            workload5_matching1(threads)
+        else:
+            workload5(threads)
         return
     out = {}
     for idx in (1, 2, 3, 4):

@@ -332,8 +332,8 @@ def test_five_piece_rows_full_run(stream):
 
 def test_workload_5_prefix_bit_exact(stream):
     """40,960-NPU torus in the launch configuration bench.py times: the first 48 TEN spans
-    (11.8 M transfers) record by record.  The complete run is compared by
-    tests/full_size_parity.py (minutes of oracle time)."""
+    (11.8 M transfers) record by record.  The complete run is compared with the oracle's stored
+    result by the next test."""
     w = T.workload(5)
     n_ev = 48
     ref = oracle.synthesize_workload(w, max_events=n_ev, n_threads=min(16, oracle.max_threads()))
@@ -373,6 +373,23 @@ def test_workload_5_full_run_against_stored_oracle_result(stream):
         for k, want in enumerate(win["sha256"]):
             got = r.read(win["first"] + k * win["stride"], win["block"])
             assert hashlib.sha256(got.tobytes()).hexdigest() == want, f"window {k}"
+
+
+def test_workload_5_full_run_postcondition_centric_against_stored_oracle_result(stream):
+    """The complete 40,960-NPU All-Gather in Algorithm 1's own order (matching = 1, rows of the
+    free links in register planes) against tests/golden/workload5_matching1_oracle.json
+    (make_golden.py --with-5 --matching1): time, spans, transfers, digest over every transfer,
+    per-span trace and the first 4096 records.  The time equals the ingress lower bound."""
+    with open(os.path.join(os.path.dirname(GOLDEN), "workload5_matching1_oracle.json")) as f:
+        g = json.load(f)
+    w = T.workload(5)
+    with binding.synthesize_workload(w, stream=stream, matching=1) as r:
+        assert r.collective_time_ps == g["collective_time_ps"] == 6_827 * 10_985_760
+        assert r.num_events == g["n_events"] and r.num_xfers == g["n_xfers"]
+        assert r.digest == g["digest"]
+        t, m = r.event_trace(0)
+        assert hashlib.sha256(t.tobytes() + m.tobytes()).hexdigest() == g["sha256_event_trace"]
+        assert hashlib.sha256(r.read(0, 4096).tobytes()).hexdigest() == g["sha256_first_4096_xfers"]
 
 
 @pytest.mark.parametrize("idx", [6, 7])
