@@ -63,6 +63,9 @@ struct PassDev {
   const uint32_t *in_ptr;          // [N+1]
   const uint32_t *in_link;         // [L] incoming links of each NPU, ascending link id
   const uint32_t *in_src;          // [L] their source NPUs (pass orientation)
+  const unsigned short *in_src16;  // [L] the same as 16-bit values in LDS (single-workgroup kernel, when the
+                                   //     in-list records themselves do not fit there), else null
+  uint32_t in_rec_in_lds;          // single-workgroup kernel: in_rec points into LDS
   uint4 *in_rec;                   // [L] the in-lists as one record per entry: (link, source, cost lo, cost hi),
                                    //     written by the set-up kernel from in_link / in_src / cost
   const uint32_t *pos_dst;         // [L] destination NPU of in-list position j (pass orientation)

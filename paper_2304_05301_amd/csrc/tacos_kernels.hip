@@ -26,6 +26,49 @@ namespace {
 typedef unsigned long long u64;
 typedef uint32_t u32;
 
+// Loads and stores with the address space spelled out.  The single-workgroup kernel keeps
+// some arrays either in LDS or in device memory, decided at launch; through a generic
+// pointer such an access becomes a FLAT instruction, and on gfx9 every wait for a flat load
+// is s_waitcnt vmcnt(0) lgkmcnt(0): it also waits for all global loads, stores and atomics
+// in flight, which is exactly what that kernel avoids.  With these, an LDS access is a ds_
+// instruction and a device-memory access a global_ one.
+#define TACOS_LDS __attribute__((address_space(3)))
+#define TACOS_GLB __attribute__((address_space(1)))
+typedef u32 u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32 lds_ld(const u32 *p) { return *(const TACOS_LDS u32 *)p; }
+__device__ __forceinline__ u32 lds_ld(const unsigned short *p) { return *(const TACOS_LDS unsigned short *)p; }
+__device__ __forceinline__ unsigned long long lds_ld(const unsigned long long *p)
+{
+  return *(const TACOS_LDS unsigned long long *)p;
+}
+__device__ __forceinline__ uint4 lds_ld(const uint4 *p)
+{
+  const u32x4_t v = *(const TACOS_LDS u32x4_t *)p;
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void lds_st(u32 *p, u32 v) { *(TACOS_LDS u32 *)p = v; }
+__device__ __forceinline__ void lds_st(unsigned long long *p, unsigned long long v)
+{
+  *(TACOS_LDS unsigned long long *)p = v;
+}
+__device__ __forceinline__ u32 glb_ld(const u32 *p) { return *(const TACOS_GLB u32 *)p; }
+__device__ __forceinline__ uint4 glb_ld(const uint4 *p)
+{
+  const u32x4_t v = *(const TACOS_GLB u32x4_t *)p;
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+// link state and control block: in LDS for the single-workgroup kernel (IN_LDS), else in device memory
+template <bool IN_LDS, class T> __device__ __forceinline__ auto state_ld(const T *p)
+{
+  if constexpr (IN_LDS) return lds_ld(p);
+  else return *p;
+}
+template <bool IN_LDS, class T, class V> __device__ __forceinline__ void state_st(T *p, V v)
+{
+  if constexpr (IN_LDS) lds_st(p, (T)v);
+  else *p = (T)v;
+}
+
 // ---------------------------------------------------------------- small helpers
 
 __device__ __forceinline__ u32 uniform(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
@@ -364,8 +407,14 @@ __device__ __forceinline__ void append_records(const RecOut &rec, bool has, u32 
 // kNone.  Source rows land in two register buffers used in turn, so that the next link's
 // row is in flight while the current link is decided; the candidate set is formed in place
 // in the buffer.
-template <int NP, class Rows>
-__device__ __forceinline__ u32 draw_chunks(const Rows &rows, u32 s, u32 r, u64 idle, uint4 *need_lds, int lane)
+// pre(): called once, after the first link's row has been asked for and before anything is
+// decided (r is read only after it); returns false (wave-uniform) if nothing is to be drawn.
+struct DrawNow {
+  __device__ __forceinline__ bool operator()() const { return true; }
+};
+template <int NP, class Rows, class Pre = DrawNow>
+__device__ __forceinline__ u32 draw_chunks(const Rows &rows, u32 s, const u32 &r, u64 idle, uint4 *need_lds, int lane,
+                                           Pre &&pre = Pre())
 {
   constexpr int NW = 2 * NP;
   constexpr int NDW = 4 * NP;
@@ -439,6 +488,7 @@ __device__ __forceinline__ u32 draw_chunks(const Rows &rows, u32 s, u32 r, u64 i
     }
   };
   if (idle) fetch(buf0_a, buf0_b, idle);
+  if (!pre()) return kNone;
   while (idle) {
     decide(buf0_a, buf0_b, buf1_a, buf1_b);
     if (!idle) break;
@@ -478,20 +528,40 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, const Rows &r
   }
 
   u32 l0 = 0, s0 = 0, cr0 = kNone;
+  u32 ry0 = 0;  // the record's source field: kept alive with the rest of the record (see below)
   u64 cs0 = 0;
   if (jb + lane < je) {
-    const uint4 rec = p.in_rec[jb + lane];
-    cr0 = p.carry[jb + lane];
-    l0 = rec.x; s0 = rec.y; cs0 = ((u64)rec.w << 32) | rec.z;
+    uint4 rec;
+    if constexpr (LATENCY_BOUND) rec = p.in_rec_in_lds ? lds_ld(p.in_rec + jb + lane) : glb_ld(p.in_rec + jb + lane);
+    else rec = p.in_rec[jb + lane];
+    cr0 = state_ld<LATENCY_BOUND>(&p.carry[jb + lane]);
+    l0 = rec.x; ry0 = rec.y; cs0 = ((u64)rec.w << 32) | rec.z;
+    // LATENCY_BOUND with the sources in LDS: the first source row can be asked for without
+    // waiting for the record, i.e. in the same memory round trip as the record and d's own row.
+    // (The empty asm keeps the two cases in separate branches: as a select, the source would
+    // wait for the record in both.)
+    if constexpr (LATENCY_BOUND) {
+      if (p.in_src16) {
+        s0 = lds_ld(p.in_src16 + jb + lane);
+      } else {
+        u32 y = rec.y;
+        asm volatile("" : "+v"(y));
+        s0 = y;
+      }
+    } else {
+      s0 = rec.y;
+    }
   }
   bool any_idle = __ballot(jb + lane < je && cr0 == kNone) != 0ull;
   for (u32 base = jb + 64; base < je && !any_idle; base += 64) {
     const u32 j = base + lane;
-    any_idle = __ballot(j < je && p.carry[j < je ? j : jb] == kNone) != 0ull;
+    any_idle = __ballot(j < je && state_ld<LATENCY_BOUND>(&p.carry[j < je ? j : jb]) == kNone) != 0ull;
   }
 
   bool need_any = false;
-  if (any_idle) {
+  bool need_ready = false;  // LATENCY_BOUND: the need row is set up behind the first row request
+  auto setup_need = [&]() {
+    need_ready = true;
     // need = ~held[d] & ~inflight[d], written to LDS; inflight[d] = the chunks on d's
     // busy incoming links, cleared by single-lane read-modify-writes
     u32 acc = 0;
@@ -508,12 +578,12 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, const Rows &r
     // d holds every chunk: nothing is or will be in flight to it, its links stay idle for
     // good, and the host may drop it from the processing order
     if (!need_any && p.dest_done && lane == 0) p.dest_done[d] = 1u;
-    if (need_any && lane == 0) ctl->need_flag[event & 1u] = 1u;
+    if (need_any && lane == 0) state_st<LATENCY_BOUND>(&ctl->need_flag[event & 1u], 1u);
     for (u32 base = jb; base < je; base += 64) {
       const u32 j = base + lane;
       u32 cr = kNone;
       if (base == jb) cr = cr0;
-      else if (j < je) cr = p.carry[j];
+      else if (j < je) cr = state_ld<LATENCY_BOUND>(&p.carry[j]);
       const u64 busy = __ballot(cr != kNone);
       if (busy && cr != kNone) {
         // every busy lane clears its own link's chunk (distinct chunks; dword updates
@@ -525,27 +595,39 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, const Rows &r
         atomicAnd(ptr, ~(1u << (cr & 31u)));
       }
     }
+  };
+  if constexpr (!LATENCY_BOUND) {
+    if (any_idle) setup_need();
   }
 
-  for (u32 base = jb; base < je; base += 64) {
+  // one block of up to 64 in-list entries, one per lane: (l, s, cr, cs) = the lane's link id,
+  // source, chunk carried (kNone: idle) and cost
+  auto block = [&](u32 base, u32 l, u32 s, u32 cr, u64 cs) {
     const u32 j = base + lane;
     const bool valid = j < je;
-    u32 l = l0, s = s0, cr = cr0;
-    u64 cs = cs0;
-    if (base != jb) {
-      l = 0; s = 0; cr = kNone; cs = 0;
-      if (valid) {
-        const uint4 rec = p.in_rec[j];
-        cr = p.carry[j];
-        l = rec.x; s = rec.y; cs = ((u64)rec.w << 32) | rec.z;
-      }
-    }
     u32 res = kNone;
-    if (need_any) {
+    if constexpr (LATENCY_BOUND) {
       const u64 idle = __ballot(valid && cr == kNone);
-      u32 r = 0;
-      if constexpr (LATENCY_BOUND) r = philox4x32_10_word0(l, event, p.phase, 0u, p.seed_lo, p.seed_hi);
-      else if (valid) r = p.rnd[j];
+      if (idle != 0ull && (need_any || !need_ready)) {
+        u32 r = 0;
+        res = draw_chunks<NP>(rows, s, r, idle, need_lds, lane, [&]() {
+          if (!need_ready) {
+            // d's own row and the records are first used here, behind the request for the first
+            // source row, so that all three arrive in one memory round trip
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < NP; ++i) asm volatile("" : "+v"(own[i].x), "+v"(own[i].y), "+v"(own[i].z), "+v"(own[i].w));
+            setup_need();
+          }
+          // (an unused register of a load in flight would be reused at once, which waits for the load)
+          asm volatile("" : "+v"(l) : "v"(ry0));
+          r = philox4x32_10_word0(l, event, p.phase, 0u, p.seed_lo, p.seed_hi);
+          return need_any;
+        });
+      }
+    } else if (need_any) {
+      const u64 idle = __ballot(valid && cr == kNone);
+      const u32 r = valid ? p.rnd[j] : 0u;
       res = draw_chunks<NP>(rows, s, r, idle, need_lds, lane);
     }
     if (rec.recs) append_records(rec, valid && res != kNone, l, res, lane);
@@ -553,22 +635,38 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, const Rows &r
       if (sched_row && res != kNone) sched_row[l] = res;  // rows are pre-filled with kNone
       if (res != kNone) {
         if (res >= p.C) {
-          ctl->status = kStInternal;
-          ctl->done = 1u;
+          state_st<LATENCY_BOUND>(&ctl->status, kStInternal);
+          state_st<LATENCY_BOUND>(&ctl->done, 1u);
         } else if (cs > kInf - 1ull - t) {
-          ctl->status = kStOverflow;
-          ctl->done = 1u;
+          state_st<LATENCY_BOUND>(&ctl->status, kStOverflow);
+          state_st<LATENCY_BOUND>(&ctl->done, 1u);
         } else {
           const u64 fa = t + cs;
-          p.carry[j] = res;
-          p.free_at[j] = fa;
+          state_st<LATENCY_BOUND>(&p.carry[j], res);
+          state_st<LATENCY_BOUND>(&p.free_at[j], fa);
           my_min = fa < my_min ? fa : my_min;
         }
       } else if (cr != kNone) {
-        const u64 fa = p.free_at[j];
+        const u64 fa = state_ld<LATENCY_BOUND>(&p.free_at[j]);
         my_min = fa < my_min ? fa : my_min;
       }
     }
+  };
+  // the first block as straight-line code (no in-degree above 64 in practice): the values it
+  // starts from are then not copied into loop variables, which would wait for their loads
+  block(jb, l0, s0, cr0, cs0);
+  for (u32 base = jb + 64; base < je; base += 64) {
+    const u32 j = base + lane;
+    u32 l = 0, s = 0, cr = kNone;
+    u64 cs = 0;
+    if (j < je) {
+      uint4 rec;
+      if constexpr (LATENCY_BOUND) rec = p.in_rec_in_lds ? lds_ld(p.in_rec + j) : glb_ld(p.in_rec + j);
+      else rec = p.in_rec[j];
+      cr = state_ld<LATENCY_BOUND>(&p.carry[j]);
+      l = rec.x; s = rec.y; cs = ((u64)rec.w << 32) | rec.z;
+    }
+    block(base, l, s, cr, cs);
   }
   return my_min;
 }
@@ -1372,7 +1470,8 @@ __device__ __forceinline__ void match_destinations_by_lane(const PassDev &q, con
 // LDS layout (dynamic): u64 free_at[L rounded up to even] | u32 carry[L] | u32 stamp[N] |
 // u32 work[N] | uint4 need[16][NP][64] | u64 next[2] | u32 counters[4] | Ctl shadow |
 // and, each while it still fits: u32 pos_dst[L] | the held table without its padding lanes
-// (RowsLds: N * ceil(C / 128) * 16 bytes when NP = 1) | uint4 in_rec[L], u32 in_ptr[N + 1].
+// (RowsLds: N * ceil(C / 128) * 16 bytes when NP = 1) | uint4 in_rec[L], u32 in_ptr[N + 1] |
+// u16 in_src[L] if in_rec does not fit.
 // Link state is indexed by in-list position, as in HBM.  With the held table in LDS a span of
 // a small topology touches device memory only to append schedule records.
 __host__ __device__ inline size_t small_lds_bytes(u32 N, u32 L, u32 NP)
@@ -1423,7 +1522,10 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
   // rec_in_lds bit 0: the in-list records, bit 1: the in-list offsets, so that setting up a
   // destination costs one memory round trip less each
   uint4 *s_rec = reinterpret_cast<uint4 *>(cur); cur += (rec_in_lds & 1u) ? (size_t)p.L * 16 : 0;
-  u32 *s_inptr = reinterpret_cast<u32 *>(cur);
+  u32 *s_inptr = reinterpret_cast<u32 *>(cur); cur += (rec_in_lds & 2u) ? (((size_t)p.N + 1) * 4 + 15) & ~(size_t)15 : 0;
+  // bit 2 (only without bit 0): the in-list sources alone, 16 bits each, so that a destination's
+  // first source row is asked for together with its records instead of after them
+  unsigned short *s_src16 = reinterpret_cast<unsigned short *>(cur);
 
   const u32 tid = threadIdx.x;
   const int lane = tid & 63;
@@ -1451,23 +1553,27 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
     }
   }
   const RecOut rec_fwd = (recs && !p.reversed) ? RecOut{recs, &s_cnt[2]} : RecOut();
-  const u32 *pos_dst = p.pos_dst;
   if (dst_in_lds) {
     for (u32 l = tid; l < p.L; l += 1024u) s_dst[l] = p.pos_dst[l];
-    pos_dst = s_dst;
   }
+  // (a branch per access rather than one pointer to either copy: see lds_ld)
+  auto dst_of = [&](u32 l) { return dst_in_lds ? lds_ld(s_dst + l) : glb_ld(p.pos_dst + l); };
   PassDev q = p;  // the matching code works on the LDS copy of the link state
   q.carry = s_carry;
   q.free_at = s_free;
   q.ctl = s_ctl;
-  const u32 *in_ptr = p.in_ptr;
   if (rec_in_lds & 1u) {
     for (u32 l = tid; l < p.L; l += 1024u) s_rec[l] = p.in_rec[l];
     q.in_rec = s_rec;
+    q.in_rec_in_lds = 1u;
   }
   if (rec_in_lds & 2u) {
     for (u32 n = tid; n <= p.N; n += 1024u) s_inptr[n] = p.in_ptr[n];
-    in_ptr = s_inptr;
+  }
+  auto in_off = [&](u32 n) { return (rec_in_lds & 2u) ? lds_ld(s_inptr + n) : glb_ld(p.in_ptr + n); };
+  if (rec_in_lds & 4u) {
+    for (u32 l = tid; l < p.L; l += 1024u) s_src16[l] = (unsigned short)p.in_src[l];
+    q.in_src16 = s_src16;
   }
   u64 t = ctl->next_t[first_event & 1u];
   u64 remaining = ctl->remaining;
@@ -1498,7 +1604,7 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
           const u32 l = l2 + k;
           if (s_free[l] != t) continue;
           const u32 c = s_carry[l];
-          const u32 d = pos_dst[l];
+          const u32 d = dst_of(l);
           if constexpr (HELD_LDS) atomicOr(lrows.word_of(d, c, (u32)NP), 1ull << (c & 63u));
           else atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
           s_carry[l] = kNone;
@@ -1537,12 +1643,12 @@ __device__ __forceinline__ void small_sweep_body(const PassDev &p, const u32 *__
         const u32 i = i0 + (u32)lane;
         const bool active = i < n_work;
         const u32 d = active ? ((e == 0u) ? i : s_work[i]) : 0u;
-        match_destinations_by_lane<(TW > 0 ? TW : 1)>(q, lrows, in_ptr, d, active, e, t, rec_fwd, lane);
+        match_destinations_by_lane<(TW > 0 ? TW : 1)>(q, lrows, s_inptr, d, active, e, t, rec_fwd, lane);
       }
     } else
     for (u32 i = wave; i < n_work; i += 16u) {
       const u32 d = uniform((e == 0u) ? i : s_work[i]);
-      const u32 jb = in_ptr[d], je = in_ptr[d + 1];
+      const u32 jb = in_off(d), je = in_off(d + 1u);
       uint4 *my_need = s_need + wave * NP * 64;
       if constexpr (MODE == 0) {
         if constexpr (HELD_LDS) (void)match_destination<NP, true>(q, lrows, d, jb, je, e, t, nullptr, lane, my_need, rec_fwd);
@@ -2000,6 +2106,7 @@ static size_t small_launch_lds(const PassDev &p, u32 *dst_in_lds, u32 *held_lane
   const size_t dst_bytes = ((size_t)p.L * 4 + 15) & ~(size_t)15;
   const size_t ptr_bytes = ((size_t)p.N + 1) * 4 + 15 & ~(size_t)15;
   const size_t rec_bytes = (size_t)p.L * 16;
+  const size_t src16_bytes = ((size_t)p.L * 2 + 15) & ~(size_t)15;
   // in the order the kernel lays them out: link destinations, held table, in-list records
   *dst_in_lds = lds + dst_bytes <= limit ? 1u : 0u;
   if (*dst_in_lds) lds += dst_bytes;
@@ -2008,6 +2115,7 @@ static size_t small_launch_lds(const PassDev &p, u32 *dst_in_lds, u32 *held_lane
   *rec_in_lds = 0u;
   if (lds + ptr_bytes <= limit) { *rec_in_lds |= 2u; lds += ptr_bytes; }  // offsets first: they are small
   if (lds + rec_bytes <= limit) { *rec_in_lds |= 1u; lds += rec_bytes; }
+  else if (p.N <= 65536u && lds + src16_bytes <= limit) { *rec_in_lds |= 4u; lds += src16_bytes; }
   return lds;
 }
 
