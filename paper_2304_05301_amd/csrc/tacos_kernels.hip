@@ -934,7 +934,7 @@ __device__ __forceinline__ u64 match_destination_pairs(const PassDev &p, const R
   u32 l = 0, s = 0, cr = kNone;
   u64 cs = 0;
   if (valid) {
-    const uint4 rec = p.in_rec[j];
+    const uint4 rec = p.in_rec_in_lds ? lds_ld(p.in_rec + j) : glb_ld(p.in_rec + j);
     cr = p.carry[j];
     l = rec.x; s = rec.y; cs = ((u64)rec.w << 32) | rec.z;
   }
@@ -1400,7 +1400,7 @@ __device__ __forceinline__ void match_destinations_by_lane(const PassDev &q, con
     u32 link = 0, chunk = kNone;
     const u32 j = jb + jr;
     if (jr < deg && any != 0ull && q.carry[j] == kNone) {
-      const uint4 ir = q.in_rec[j];  // (link, source, cost lo, cost hi)
+      const uint4 ir = lds_ld(q.in_rec + j);  // (link, source, cost lo, cost hi)
       const u64 *srow = reinterpret_cast<const u64 *>(rows.base + ir.y * rows.row_u4);
       u64 cand[W];
       u32 p = 0;
@@ -1714,6 +1714,8 @@ __global__ __launch_bounds__(1024) void small_sweep_batch_kernel(const SmallJob 
                                                                  u32 n_events, u32 dst_in_lds, u32 held_lanes,
                                                                  u32 rec_in_lds)
 {
+  // (The job's pointers are read from memory, so the compiler cannot tell device memory from
+  // LDS behind them and some of this kernel's accesses stay flat instructions.)
   const SmallJob &j = jobs[blockIdx.x];
   small_sweep_body<NP, MODE, HELD_LDS, TW>(j.p, j.out_ptr, j.out_dst, first_event, n_events, 0xFFFFFFFFu, nullptr,
                                            nullptr, nullptr, dst_in_lds, held_lanes, rec_in_lds);
