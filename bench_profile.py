@@ -6,7 +6,7 @@ runs committed files only), e.g. for the default workload:
 
   python3 bench_profile.py --workload 5 --commands          # prints the four commands
   ... run them (cd /tmp && export TMPDIR=/tmp first; one rocprofv3 run per counter set) ...
-  python3 bench_profile.py --workload 5 --dir gpurun_out    # writes profiles/<kernel>_<workload>[_<variant>].txt
+  python3 bench_profile.py --workload 5 --dir rocprof_out   # writes profiles/<kernel>_<workload>[_<variant>].txt
                                                             # and ..._traffic.txt
 
 The traffic file records the SHA-256 of the library sources it was measured on; bench.py
@@ -81,7 +81,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", type=int, default=5)
     ap.add_argument("--matching", type=int, default=0)
-    ap.add_argument("--dir", default="gpurun_out", help="where the rocprofv3 output folders are")
+    ap.add_argument("--dir", default="rocprof_out", help="where the rocprofv3 output folders are")
     ap.add_argument("--commands", action="store_true", help="print the rocprofv3 commands and exit")
     ap.add_argument("--out-dir", default=None,
                     help="where to write the summaries (default: profiles/; on a box from which only one "
