@@ -269,6 +269,58 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
   if (sched_row && arrived) sched_row[link] = c;  // rows are pre-filled with kNone
 }
 
+// The same for the in-lists of the destinations still in the processing order only: once the
+// host has dropped the complete destinations (nothing is or will be in flight to them, so
+// their links never deliver again), a thread per (slot, position in the in-list), deg
+// positions per slot.  On the meshes of the paper's scalability experiment the last third of
+// a pass has a handful of active destinations among tens of thousands.
+__global__ __launch_bounds__(256) void arrive_slots_kernel(PassDev p, u32 event, u64 *event_time_slot,
+                                                           u32 *__restrict__ sched_row, u32 deg)
+{
+  Ctl *ctl = p.ctl;
+  const u32 q = blockIdx.x * 256u + threadIdx.x;
+  const u32 slot = q / deg, k = q - slot * deg;
+  u32 c = kNone, d = 0, link = 0, j = 0;
+  u64 fa = 0;
+  bool valid = false;
+  if (slot < p.n_slots) {
+    const uint4 sr = p.slot_rec[slot];  // (destination, in-list begin, end)
+    j = sr.y + k;
+    if (j < sr.z) {
+      valid = true;
+      d = sr.x;
+      c = p.carry[j]; fa = p.free_at[j];
+      if (sched_row || p.rnd) link = p.in_link[j];
+    }
+  }
+  if (ctl->done) return;
+  const u64 t = ctl->next_t[event & 1u];
+  if (q == 0) {
+    if (t == kInf) {  // as arrive_kernel
+      if (event != 0u && ctl->need_flag[(event - 1u) & 1u] == 0u) {
+        ctl->T = ctl->now;
+        ctl->n_events = event - 1u;
+      } else {
+        ctl->status = kStUnreachable;
+      }
+      ctl->done = 1u;
+    } else {
+      *event_time_slot = t;
+      ctl->now = t;
+      ctl->next_t[(event + 1u) & 1u] = kInf;
+      ctl->need_flag[event & 1u] = 0u;
+    }
+  }
+  if (t == kInf || !valid) return;
+  if (p.rnd) p.rnd[j] = philox4x32_10_word0(link, event, p.phase, 0u, p.seed_lo, p.seed_hi);
+  const bool arrived = (c != kNone) && (fa == t);
+  if (arrived) {
+    atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
+    p.carry[j] = kNone;
+  }
+  if (sched_row && arrived) sched_row[link] = c;
+}
+
 // ---------------------------------------------------------------- a4-a8: matching
 
 // A lane's share of a bitset row (NDW dwords) held in native vector registers, so that
@@ -2000,6 +2052,14 @@ void launch_init_pass(const PassDev &p, hipStream_t s)
 
 void launch_arrive(const PassDev &p, u32 event, u64 *event_time_slot, u32 *sched_row, hipStream_t s)
 {
+  // few destinations left in the processing order: only their in-lists are looked at
+  const u64 slot_threads = (u64)p.n_slots * p.max_deg;
+  if (p.n_slots < p.N && p.max_deg >= 1u && p.max_deg <= 64u && slot_threads * 2ull <= (u64)p.L) {
+    const u32 blocks = (u32)((slot_threads + 255ull) / 256ull);
+    hipLaunchKernelGGL(arrive_slots_kernel, dim3(blocks ? blocks : 1u), dim3(256), 0, s, p, event, event_time_slot,
+                       sched_row, p.max_deg);
+    return;
+  }
   hipLaunchKernelGGL(arrive_kernel, dim3((p.L + 255) / 256), dim3(256), 0, s, p, event,
                      event_time_slot, sched_row);
 }
