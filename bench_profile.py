@@ -141,14 +141,14 @@ def main():
         g_am, g_ma, arr = [], [], []
         for i in range(1, len(trace) - 1):
             s, e, n = trace[i]
-            if kernel in n and e - s >= thr and "arrive_kernel" in trace[i - 1][2] and "arrive_kernel" in trace[i + 1][2]:
+            if kernel in n and e - s >= thr and trace[i - 1][2].startswith("arrive_") and trace[i + 1][2].startswith("arrive_"):
                 g_am.append(s - trace[i - 1][1])
                 g_ma.append(trace[i + 1][0] - e)
                 arr.append(trace[i - 1][1] - trace[i - 1][0])
         if arr:
             a, g1, g2 = (sum(x) / len(x) / 1e3 for x in (arr, g_am, g_ma))
             span = mean_us + a + g1 + g2
-            out.append(f"per span ({len(arr)} spans): arrive_kernel {a:.2f} us + gap {g1:.2f} us + {kernel} {mean_us:.2f} us + "
+            out.append(f"per span ({len(arr)} spans): arrivals kernel {a:.2f} us + gap {g1:.2f} us + {kernel} {mean_us:.2f} us + "
                        f"gap {g2:.2f} us = {span:.2f} us; outside {kernel}: {100 * (span - mean_us) / span:.1f} %")
     n_chunks = w.topo.n_npus * w.chunks_per_npu
     wb = 8 * ((n_chunks + 63) // 64)
