@@ -447,6 +447,20 @@ def test_scalability_shapes_all_reduce_full(name, mk, stream):
             assert np.array_equal(r.read(first, cnt), ref.xfers[first:first + cnt]), (name, first)
 
 
+@pytest.mark.parametrize("coll", [T.ALL_GATHER, T.REDUCE_SCATTER, T.ALL_REDUCE])
+def test_heterogeneous_mesh_with_few_destinations_left(coll, stream):
+    """A mesh with different link classes per dimension through the per-span launches:
+    the interior completes long before the corners, the host drops complete destinations
+    from the launches, and the arrivals are then looked for in the remaining in-lists
+    only; spans sit on many distinct times, forward and reversed passes.  Record by record."""
+    topo = T.grid([14, 11], False, [300_000, 700_000], [5_000, 20_000])
+    ref = cpu(topo, 2, 96 << 10, coll, 23, n_threads=min(16, oracle.max_threads()))
+    with gpu(topo, 2, 96 << 10, coll, 23, stream, launch_mode=1) as r:
+        assert_same(r, ref, "hetero mesh 14x11")
+        n_pass = 2 if coll == T.ALL_REDUCE else 1
+        assert [r.pass_events(i) for i in range(n_pass)] == list(ref.pass_events)[:n_pass]
+
+
 @pytest.mark.parametrize("idx,n_ev", [(6, 40), (7, 40)])
 def test_scalability_workloads_prefix_bit_exact(idx, n_ev, stream):
     """Full-size shapes of the paper's scalability experiment (40,000-NPU 2D mesh and
