@@ -252,9 +252,12 @@ double   tacos_result_wall_ms(const tacos_result_t *r);
 /* Bytes of device memory the result holds (schedule tables).  A pass run by the per-span
  * launches (launch_mode 1 and 3) keeps one row of n_links 32-bit entries per span, i.e.
  * spans * n_links * 4 bytes, allocated in 256 MiB segments as the spans are reached (6.7 GB for
- * the 40,960-NPU torus; a heterogeneous topology with very many distinct event times can
- * exhaust device memory: TACOS_E_NOMEM).  A pass run by the single-workgroup kernel
- * (launch_mode 2) keeps 8 bytes per transfer and 12 bytes per span. */
+ * the 40,960-NPU torus).  A pass run by the single-workgroup kernel (launch_mode 2) keeps 8
+ * bytes per transfer and 12 bytes per span, and so does launch_mode 1 on a topology whose
+ * links nearly all cost differently (at least 64 distinct costs and at least n_links / 4 of
+ * them: about one transfer starts per span and there are millions of spans) with at most
+ * about 40,000 links.  Beyond that size such a topology keeps dense rows and can exhaust
+ * device memory: TACOS_E_NOMEM. */
 uint64_t tacos_result_device_bytes(const tacos_result_t *r);
 void     tacos_result_free(tacos_result_t *r);
 

@@ -323,7 +323,8 @@ bool fits_small_kernel(uint32_t N, uint32_t L, uint32_t NP)
 int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const std::vector<uint32_t> &pdst,
              const DevBuf &d_cost, uint32_t cpn, uint32_t root, uint64_t seed, uint32_t phase, bool reversed,
              uint64_t max_events, bool time_kernels, uint32_t launch_mode, const std::vector<uint64_t> *order_cost,
-             uint32_t match_mode, uint64_t uniform_cost, hipStream_t stream, tacos_result &res, Pass &pass)
+             uint32_t match_mode, uint64_t uniform_cost, bool many_costs, hipStream_t stream, tacos_result &res,
+             Pass &pass)
 {
   const uint32_t C = total_chunks(N, cpn, root);
   const uint32_t NP = (C + 8191u) / 8192u;
@@ -398,14 +399,20 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
 
   uint64_t e = 0;
   bool stopped = false;  // prefix run reached max_events
-  pass.prefill = !small;  // dense rows: the kernels write matches (a reversed pass: arrivals) only
-  if (small) {
+  // Per-span launches on a topology whose links nearly all cost differently: about one transfer
+  // starts per span, so dense rows (one entry per link and span) would be almost empty and
+  // millions of them long.  Such a pass keeps compact records as the single-workgroup kernel
+  // does, provided the epilogue can order a span's records (one LDS word per link).
+  const uint64_t n_transfers = (uint64_t)N * C - C;
+  const bool compact_spans = !small && !uniform && many_costs && NP <= 8 && L <= tacos::compact_schedule_max_links() &&
+                             n_transfers <= 0xFFFFFFFEull;
+  pass.prefill = !small && !compact_spans;  // dense rows: the kernels write matches (a reversed pass: arrivals) only
+  if (small || compact_spans) {
     // compact records: exactly one per unsatisfied postcondition of the pass
     pass.compact = true;
     pass.rows_per_seg = 1u << 20;
-    const uint64_t cap = (uint64_t)N * C - C;
-    if (cap > 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 transfers in a pass of the single-workgroup kernel"; return TACOS_E_INVAL; }
-    pass.recs.alloc((size_t)std::max<uint64_t>(cap, 1) * 8);
+    if (n_transfers > 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 transfers in a pass of the single-workgroup kernel"; return TACOS_E_INVAL; }
+    pass.recs.alloc((size_t)std::max<uint64_t>(n_transfers, 1) * 8);
   }
   DevBuf d_rnd, d_prev;
   if (!small && match_mode == 0) {
@@ -478,7 +485,22 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
           e++;
           continue;
         }
-        tacos::launch_arrive(p, (uint32_t)e, tslot, reversed ? row : nullptr, stream);
+        if (compact_spans) {
+          // `row` is the span's slot for the index of its first record: a forward pass's arrivals
+          // kernel fills it; in a reversed pass (records = arrivals) the matching of the span before
+          uint32_t *first_next = nullptr;
+          unsigned long long *tslot_next = nullptr;
+          if (reversed) row_slot(e + 1, &first_next, &tslot_next);
+          tacos::launch_arrive(p, (uint32_t)e, tslot, nullptr, reversed ? pass.recs.as<uint2>() : nullptr,
+                               (!reversed || e == 0) ? row : nullptr, stream);
+          if (max_events && e >= max_events) { stopped = true; break; }
+          if (time_kernels) HIP_TRY(hipEventRecord(pool.ev[2 * n_timed], stream));
+          tacos::launch_match_compact(p, (uint32_t)e, pass.recs.as<uint2>(), first_next, match_mode, stream);
+          if (time_kernels) { HIP_TRY(hipEventRecord(pool.ev[2 * n_timed + 1], stream)); n_timed++; }
+          e++;
+          continue;
+        }
+        tacos::launch_arrive(p, (uint32_t)e, tslot, reversed ? row : nullptr, nullptr, nullptr, stream);
         if (max_events && e >= max_events) { stopped = true; break; }
         if (time_kernels) HIP_TRY(hipEventRecord(pool.ev[2 * n_timed], stream));
         tacos::launch_match(p, (uint32_t)e, reversed ? nullptr : row, match_mode, stream);
@@ -755,12 +777,20 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       uint64_t uniform_cost = host_cost[0];
       for (uint32_t l = 1; l < L && uniform_cost; ++l)
         if (host_cost[l] != host_cost[0]) uniform_cost = 0;
+      // nearly every link with a cost of its own: spans then sit on about as many times as there are transfers
+      bool many_costs = false;
+      if (!uniform_cost) {
+        std::vector<uint64_t> sorted(host_cost);
+        std::sort(sorted.begin(), sorted.end());
+        const size_t distinct = (size_t)(std::unique(sorted.begin(), sorted.end()) - sorted.begin());
+        many_costs = distinct >= 64 && distinct * 4 >= (size_t)L;
+      }
       uint64_t t_off = 0;
       if (has_reversed_pass((int)coll)) {
         // reversed pass: every link (s -> d) is used as (d -> s), ids and costs unchanged
         res->passes.emplace_back();
         rc = run_pass(N, L, res->link_dst, res->link_src, d_cost, chunks_per_npu, root, seed, 1u, true, 0,
-                      time_kernels, launch_mode, order_cost, match_mode, uniform_cost, stream, *res,
+                      time_kernels, launch_mode, order_cost, match_mode, uniform_cost, many_costs, stream, *res,
                       res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), 0, &res->digest, stream);
@@ -769,7 +799,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       if (has_forward_pass((int)coll)) {
         res->passes.emplace_back();
         rc = run_pass(N, L, res->link_src, res->link_dst, d_cost, chunks_per_npu, root, seed, 0u, false,
-                      max_events, time_kernels, launch_mode, order_cost, match_mode, uniform_cost,
+                      max_events, time_kernels, launch_mode, order_cost, match_mode, uniform_cost, many_costs,
                       stream, *res, res->passes.back());
         if (rc != TACOS_OK) return rc;
         finish_pass(res->passes.back(), t_off, &res->digest, stream);

@@ -121,14 +121,24 @@ hipError_t link_cost_static(const unsigned long long *h_alpha, const unsigned lo
 void launch_init_pass(const PassDev &p, hipStream_t s);
 // a3 + a8 (consume): arrivals at the event's time; writes event_time_slot and, for a
 // reversed pass, the arrivals into the schedule row of the event (rows are pre-filled with kNone)
+// Compact schedule (recs != null, sched_row == null): a reversed pass appends its arrivals as
+// (link, chunk) records at Ctl::n_rec; first_slot, if not null, receives the index of the
+// span's first record.
 void launch_arrive(const PassDev &p, uint32_t event, unsigned long long *event_time_slot,
-                   uint32_t *sched_row, hipStream_t s);
+                   uint32_t *sched_row, uint2 *recs, uint32_t *first_slot, hipStream_t s);
 // a4-a8 (produce): termination test, matching for all destinations, min-reduction of
 // the next event time; a forward pass writes its matches into the schedule row of the event
 // (pre-filled with kNone).  Only the first p.n_slots processing slots are launched.
 // mode 0: link-centric; 1: postcondition-centric with a random holder link; 2: postcondition-
 // centric with the first holder of the incoming list (in-degree <= 64 for modes 1, 2)
 void launch_match(const PassDev &p, uint32_t event, uint32_t *sched_row, uint32_t mode, hipStream_t s);
+// The same with a compact schedule: a forward pass appends its matches as (link, chunk) records
+// at Ctl::n_rec; first_next, if not null (reversed pass), receives the index at which the records
+// of the next span (its arrivals) start.  Rows of at most 8 pieces.
+void launch_match_compact(const PassDev &p, uint32_t event, uint2 *recs, uint32_t *first_next, uint32_t mode,
+                          hipStream_t s);
+// largest number of links whose compact schedule the epilogue can order (one LDS word per link)
+uint32_t compact_schedule_max_links();
 // a3-a8 fused for small topologies: ONE workgroup sweeps spans [first_event,
 // first_event+n_events) with the per-link state in LDS (arrivals, termination test,
 // matching of the destinations something changed for, next-event min-reduction) and

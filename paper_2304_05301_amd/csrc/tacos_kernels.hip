@@ -221,10 +221,34 @@ __global__ void init_links_kernel(PassDev p)
   }
 }
 
+// Compact schedule records: (link, chunk) pairs appended in the order the spans are swept, at a
+// record counter (in LDS for the single-workgroup kernel, Ctl::n_rec for the per-span launches on
+// topologies whose links nearly all cost differently).  Null where the schedule is dense rows.
+struct RecOut {
+  uint2 *recs = nullptr;
+  u32 *counter = nullptr;
+};
+
+// appends the lanes' records (lanes with has == true) behind one another
+__device__ __forceinline__ void append_records(const RecOut &rec, bool has, u32 link, u32 chunk, int lane)
+{
+  const u64 m = __ballot(has);
+  if (m == 0ull) return;
+  const u32 first = (u32)__ffsll((long long)m) - 1u;
+  u32 base = 0;
+  if ((u32)lane == first) base = atomicAdd(rec.counter, (u32)__popcll(m));
+  base = read_lane(base, first);
+  if (has) rec.recs[base + (u32)__popcll(m & ((1ull << lane) - 1ull))] = make_uint2(link, chunk);
+}
+
 // ---------------------------------------------------------------- a3: arrivals
 
+// Compact schedules (recs != null; see RecOut): a reversed pass appends its arrivals as (link,
+// chunk) records at ctl->n_rec; first_slot, if not null, receives the index of the span's first
+// record (forward pass: the matching kernel appends the span's matches after this launch).
 __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *event_time_slot,
-                                                     u32 *__restrict__ sched_row)
+                                                     u32 *__restrict__ sched_row, uint2 *__restrict__ recs,
+                                                     u32 *__restrict__ first_slot)
 {
   Ctl *ctl = p.ctl;
   // one thread per in-list position (the per-link state is kept in in-list order)
@@ -234,11 +258,12 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
   u64 fa = 0;
   if (l < p.L) {
     c = p.carry[l]; fa = p.free_at[l]; d = p.pos_dst[l];
-    if (sched_row || p.rnd) link = p.in_link[l];
+    if (sched_row || recs || p.rnd) link = p.in_link[l];
   }
   if (ctl->done) return;
   const u64 t = ctl->next_t[event & 1u];
   if (l == 0) {
+    if (first_slot) *first_slot = ctl->n_rec;
     if (t == kInf) {
       // a4 / a8: nothing is in flight after the previous span's matching.  If no destination
       // needed a chunk there, every postcondition is satisfied and the collective ended at
@@ -267,6 +292,7 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
     p.carry[l] = kNone;
   }
   if (sched_row && arrived) sched_row[link] = c;  // rows are pre-filled with kNone
+  if (recs) append_records(RecOut{recs, &ctl->n_rec}, arrived, link, c, (int)(threadIdx.x & 63u));
 }
 
 // The same for the in-lists of the destinations still in the processing order only: once the
@@ -275,7 +301,8 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
 // positions per slot.  On the meshes of the paper's scalability experiment the last third of
 // a pass has a handful of active destinations among tens of thousands.
 __global__ __launch_bounds__(256) void arrive_slots_kernel(PassDev p, u32 event, u64 *event_time_slot,
-                                                           u32 *__restrict__ sched_row, u32 deg)
+                                                           u32 *__restrict__ sched_row, uint2 *__restrict__ recs,
+                                                           u32 *__restrict__ first_slot, u32 deg)
 {
   Ctl *ctl = p.ctl;
   const u32 q = blockIdx.x * 256u + threadIdx.x;
@@ -290,12 +317,13 @@ __global__ __launch_bounds__(256) void arrive_slots_kernel(PassDev p, u32 event,
       valid = true;
       d = sr.x;
       c = p.carry[j]; fa = p.free_at[j];
-      if (sched_row || p.rnd) link = p.in_link[j];
+      if (sched_row || recs || p.rnd) link = p.in_link[j];
     }
   }
   if (ctl->done) return;
   const u64 t = ctl->next_t[event & 1u];
   if (q == 0) {
+    if (first_slot) *first_slot = ctl->n_rec;
     if (t == kInf) {  // as arrive_kernel
       if (event != 0u && ctl->need_flag[(event - 1u) & 1u] == 0u) {
         ctl->T = ctl->now;
@@ -311,14 +339,15 @@ __global__ __launch_bounds__(256) void arrive_slots_kernel(PassDev p, u32 event,
       ctl->need_flag[event & 1u] = 0u;
     }
   }
-  if (t == kInf || !valid) return;
-  if (p.rnd) p.rnd[j] = philox4x32_10_word0(link, event, p.phase, 0u, p.seed_lo, p.seed_hi);
-  const bool arrived = (c != kNone) && (fa == t);
+  if (t == kInf) return;
+  if (p.rnd && valid) p.rnd[j] = philox4x32_10_word0(link, event, p.phase, 0u, p.seed_lo, p.seed_hi);
+  const bool arrived = valid && (c != kNone) && (fa == t);
   if (arrived) {
     atomicOr(&p.held[(u64)d * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
     p.carry[j] = kNone;
   }
   if (sched_row && arrived) sched_row[link] = c;
+  if (recs) append_records(RecOut{recs, &ctl->n_rec}, arrived, link, c, (int)(threadIdx.x & 63u));
 }
 
 // ---------------------------------------------------------------- a4-a8: matching
@@ -430,25 +459,6 @@ struct RowsLds {
     return reinterpret_cast<u64 *>(&base[npu * row_u4 + (iw >> 1) * lanes + ln]) + (iw & 1u);
   }
 };
-
-// Compact schedule records of the single-workgroup kernel: (link, chunk) pairs appended in the
-// order the spans are swept, at a record counter that lives in LDS.  Null in the other kernels.
-struct RecOut {
-  uint2 *recs = nullptr;
-  u32 *counter = nullptr;
-};
-
-// appends the lanes' records (lanes with has == true) behind one another
-__device__ __forceinline__ void append_records(const RecOut &rec, bool has, u32 link, u32 chunk, int lane)
-{
-  const u64 m = __ballot(has);
-  if (m == 0ull) return;
-  const u32 first = (u32)__ffsll((long long)m) - 1u;
-  u32 base = 0;
-  if ((u32)lane == first) base = atomicAdd(rec.counter, (u32)__popcll(m));
-  base = read_lane(base, first);
-  if (has) rec.recs[base + (u32)__popcll(m & ((1ull << lane) - 1ull))] = make_uint2(link, chunk);
-}
 
 // The link-centric draws of ONE destination for up to 64 of its incoming links (one per
 // lane): for every link whose bit is set in `idle`, in ascending lane order,
@@ -1079,6 +1089,40 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   else my_min = match_destination_pairs<NP, DEG>(p, rows, d, jb, je, event, t, sched_row, lane, my_need, MODE == 2);
 
   // a8: next span = earliest end of a transfer in flight (min over all destinations)
+  const u64 m = wave_min64(my_min);
+  if (lane == 0 && m != kInf) {
+    u64 *nt = &ctl->next_t[(event + 1u) & 1u];
+    const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (m < cur) atomicMin(nt, m);
+  }
+}
+
+// The same with a compact schedule: the matches of a forward pass are appended as (link, chunk)
+// records at ctl->n_rec; in a reversed pass (whose records are its arrivals, appended by the
+// arrivals kernel of the next span) first_next receives the index that span's records start at.
+// For topologies whose links all cost differently: about one match per span, millions of spans.
+template <int NP, int MODE>
+__global__ __launch_bounds__(256) void match_compact_kernel(PassDev p, u32 event, uint2 *__restrict__ recs,
+                                                            u32 *__restrict__ first_next)
+{
+  const int lane = threadIdx.x & 63;
+  const u32 per_xcd = gridDim.x >> 3;
+  const u32 pos = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  const u32 slot = uniform(pos * 4u + (threadIdx.x >> 6));
+  if (slot >= p.n_slots) return;
+  const uint4 sr = p.slot_rec[slot];
+  const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
+  Ctl *ctl = p.ctl;
+  if (ctl->done) return;
+  const u64 t = ctl->next_t[event & 1u];
+  if (first_next && slot == 0u && lane == 0) *first_next = ctl->n_rec;
+  __shared__ uint4 need_lds[4 * NP * 64];
+  uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
+  const RecOut rec = p.reversed ? RecOut() : RecOut{recs, &ctl->n_rec};
+  u64 my_min;
+  const RowsHbm rows{p.held, p.row_words};
+  if constexpr (MODE == 0) my_min = match_destination<NP, false>(p, rows, d, jb, je, event, t, nullptr, lane, my_need, rec);
+  else my_min = match_destination_pairs<NP, 0>(p, rows, d, jb, je, event, t, nullptr, lane, my_need, MODE == 2, rec);
   const u64 m = wave_min64(my_min);
   if (lane == 0 && m != kInf) {
     u64 *nt = &ctl->next_t[(event + 1u) & 1u];
@@ -2050,18 +2094,41 @@ void launch_init_pass(const PassDev &p, hipStream_t s)
   hipLaunchKernelGGL(init_links_kernel, dim3((p.L + 255) / 256 + (p.L == 0)), dim3(256), 0, s, p);
 }
 
-void launch_arrive(const PassDev &p, u32 event, u64 *event_time_slot, u32 *sched_row, hipStream_t s)
+void launch_arrive(const PassDev &p, u32 event, u64 *event_time_slot, u32 *sched_row, uint2 *recs, u32 *first_slot,
+                   hipStream_t s)
 {
   // few destinations left in the processing order: only their in-lists are looked at
   const u64 slot_threads = (u64)p.n_slots * p.max_deg;
   if (p.n_slots < p.N && p.max_deg >= 1u && p.max_deg <= 64u && slot_threads * 2ull <= (u64)p.L) {
     const u32 blocks = (u32)((slot_threads + 255ull) / 256ull);
     hipLaunchKernelGGL(arrive_slots_kernel, dim3(blocks ? blocks : 1u), dim3(256), 0, s, p, event, event_time_slot,
-                       sched_row, p.max_deg);
+                       sched_row, recs, first_slot, p.max_deg);
     return;
   }
   hipLaunchKernelGGL(arrive_kernel, dim3((p.L + 255) / 256), dim3(256), 0, s, p, event,
-                     event_time_slot, sched_row);
+                     event_time_slot, sched_row, recs, first_slot);
+}
+
+void launch_match_compact(const PassDev &p, u32 event, uint2 *recs, u32 *first_next, u32 mode, hipStream_t s)
+{
+  const u32 n_wg = (p.n_slots + 3u) / 4u;
+  const dim3 grid(8u * ((n_wg + 7u) / 8u + (n_wg == 0u)), 1, 1), block(256);
+#define TACOS_MATCH_COMPACT(NP_)                                                                              \
+  if (mode == 0) hipLaunchKernelGGL((match_compact_kernel<NP_, 0>), grid, block, 0, s, p, event, recs, first_next);      \
+  else if (mode == 1) hipLaunchKernelGGL((match_compact_kernel<NP_, 1>), grid, block, 0, s, p, event, recs, first_next); \
+  else hipLaunchKernelGGL((match_compact_kernel<NP_, 2>), grid, block, 0, s, p, event, recs, first_next)
+  switch (p.NP) {
+    case 1: TACOS_MATCH_COMPACT(1); break;
+    case 2: TACOS_MATCH_COMPACT(2); break;
+    case 3: TACOS_MATCH_COMPACT(3); break;
+    case 4: TACOS_MATCH_COMPACT(4); break;
+    case 5: TACOS_MATCH_COMPACT(5); break;
+    case 6: TACOS_MATCH_COMPACT(6); break;
+    case 7: TACOS_MATCH_COMPACT(7); break;
+    case 8: TACOS_MATCH_COMPACT(8); break;
+    default: break;  // the host uses this path for rows of at most 8 pieces only
+  }
+#undef TACOS_MATCH_COMPACT
 }
 
 // Shapes whose register planes fit without spilling at three or more wavefronts per SIMD
@@ -2297,10 +2364,16 @@ hipError_t launch_small_sweep_batch(const SmallJob *jobs, u32 n_jobs, const Pass
 
 size_t small_sweep_lds_bytes(u32 N, u32 L, u32 NP) { return NP <= 2 ? small_lds_bytes(N, L, NP) : (size_t)-1; }
 
+uint32_t compact_schedule_max_links() { return (uint32_t)((lds_limit() - 2048) / 4); }
+
 void launch_compact_epilogue(uint2 *recs, const u32 *span_first, u32 n_spans, u32 L, const u64 *span_time, u64 t_base,
                              u32 reversed, u64 *digest, hipStream_t s)
 {
   if (n_spans == 0) return;
+  // more than 64 KiB of dynamic LDS has to be allowed explicitly
+  if ((size_t)L * 4 > 64 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&compact_epilogue_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)((size_t)L * 4));
   hipLaunchKernelGGL(compact_epilogue_kernel, dim3(n_spans), dim3(256), (size_t)L * 4, s, recs, span_first, L, span_time,
                      t_base, reversed, digest);
 }

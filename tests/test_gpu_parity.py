@@ -447,6 +447,58 @@ def test_scalability_shapes_all_reduce_full(name, mk, stream):
             assert np.array_equal(r.read(first, cnt), ref.xfers[first:first + cnt]), (name, first)
 
 
+def _every_link_its_own_cost(n, deg, seed):
+    topo = T.random_regular_out(n, deg, seed=seed)[0]
+    rng = np.random.default_rng(seed)
+    topo.alpha_ps[:] = rng.integers(200_000, 2_000_000, size=topo.n_links)
+    topo.beta_fs_per_B[:] = rng.choice([5_000, 10_000, 20_000, 40_000], size=topo.n_links)
+    return topo
+
+
+@pytest.mark.parametrize("n,deg,cpn,coll,matching,link_order,seed", [
+    (60, 3, 2, T.ALL_GATHER, 0, 0, 1), (60, 3, 2, T.REDUCE_SCATTER, 0, 0, 2), (90, 4, 1, T.ALL_REDUCE, 1, 0, 4),
+    (40, 5, 3, T.ALL_GATHER, 0, 1, 6), (200, 4, 1, T.ALL_REDUCE, 0, 0, 7), (64, 3, 40, T.REDUCE, 1, 0, 9)])
+def test_per_span_launches_keep_compact_records_when_every_link_has_its_own_cost(n, deg, cpn, coll, matching,
+                                                                                link_order, seed, stream):
+    """Links that nearly all cost differently: about one transfer starts per span, and the
+    per-span launches keep (link, chunk) records instead of one row of n_links entries per
+    span.  Records, per-span traces of forward and reversed passes, link counts; the device
+    memory held stays proportional to the transfers."""
+    topo = _every_link_its_own_cost(n, deg, seed)
+    kw = dict(matching=matching, link_order=link_order, root=3)
+    ref = cpu(topo, cpn, MiB, coll, seed, **kw)
+    with gpu(topo, cpn, MiB, coll, seed, stream, launch_mode=1, **kw) as r:
+        assert_same(r, ref, "own costs")
+        t, m = r.event_trace(r.num_passes - 1)
+        assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches)
+        if coll == T.ALL_REDUCE:
+            rs = cpu(topo, cpn, MiB, T.REDUCE_SCATTER, seed, **kw)
+            t, m = r.event_trace(0)
+            assert np.array_equal(t, rs.event_times) and np.array_equal(m, rs.event_matches)
+        per_pass = r.num_xfers // r.num_passes
+        for ps in range(r.num_passes):
+            first = ps * per_pass
+            want = np.bincount(ref.xfers["link"][first:first + per_pass], minlength=topo.n_links)
+            assert np.array_equal(r.link_counts(ps, topo.n_links), want)
+        assert r.device_bytes <= 24 * r.num_xfers + 4096        # 8 B per transfer + 12 B per span
+        assert r.device_bytes < r.num_events * topo.n_links * 4  # what dense rows would take
+
+
+def test_workload_4_prefix_through_the_per_span_launches(stream):
+    """The 1,024-NPU heterogeneous workload through two launches per span (compact records),
+    first 20,000 spans: record by record against the oracle's prefix."""
+    w = T.workload(4)
+    t = w.topo
+    ref = oracle.synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B, w.chunks_per_npu,
+                            w.chunk_bytes, w.collective, w.seed, max_events=20_000,
+                            n_threads=min(16, oracle.max_threads()))
+    with binding.tacos_synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B, w.chunks_per_npu,
+                                  w.chunk_bytes, w.collective, w.seed, stream=stream, launch_mode=1,
+                                  max_events=20_000) as r:
+        assert_same(r, ref, "workload 4 prefix")
+        assert r.device_bytes < 64 << 20
+
+
 @pytest.mark.parametrize("coll", [T.ALL_GATHER, T.REDUCE_SCATTER, T.ALL_REDUCE])
 def test_heterogeneous_mesh_with_few_destinations_left(coll, stream):
     """A mesh with different link classes per dimension through the per-span launches:
