@@ -377,6 +377,11 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
     p.dest_done = d_done.as<uint32_t>();
     h_done.assign(N, 0);
   }
+  DevBuf d_next_slots;
+  if (!small && !uniform) {
+    d_next_slots.alloc((size_t)2 * tacos::kNextSlots * 8);
+    p.next_slots = d_next_slots.as<unsigned long long>();
+  }
   tacos::launch_init_pass(p, stream);
   HIP_TRY(hipGetLastError());
 

@@ -79,8 +79,15 @@ struct PassDev {
   unsigned long long *free_at;     // [L] busy-until time, same indexing
   uint32_t *rnd;                   // [L] by in-list position: word 0 of Philox(link, current span, phase, 0),
                                    //     written by arrive_kernel for the link-centric match_kernel; else null
+  // Per-span launches: the matching kernels min-reduce the end times of the transfers in flight
+  // into kNextSlots words per span parity ([2][kNextSlots], wavefronts spread over them: the
+  // wavefronts of a short launch all finish together, and thousands of atomics on ONE word
+  // take tens of microseconds); the arrivals kernel of the next span takes the minimum of the
+  // words, publishes it as Ctl::next_t and clears the other parity.  Null in the other modes.
+  unsigned long long *next_slots;
   Ctl *ctl;
 };
+constexpr uint32_t kNextSlots = 64;
 
 // a1: cost = alpha + round(beta*bytes/1000); *overflow set non-zero if any cost >= 2^64-1
 void launch_link_cost(const unsigned long long *alpha, const unsigned long long *beta,

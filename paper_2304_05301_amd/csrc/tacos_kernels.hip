@@ -219,6 +219,7 @@ __global__ void init_links_kernel(PassDev p)
     c->now = 0ull;
     for (int i = 0; i < 4; ++i) { c->need_flag[i] = 0u; c->match_flag[i] = 0u; }
   }
+  if (p.next_slots && l < 2u * kNextSlots) p.next_slots[l] = l == 0u ? 0ull : kInf;  // span 0 is at time 0
 }
 
 // Compact schedule records: (link, chunk) pairs appended in the order the spans are swept, at a
@@ -261,9 +262,13 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
     if (sched_row || recs || p.rnd) link = p.in_link[l];
   }
   if (ctl->done) return;
-  const u64 t = ctl->next_t[event & 1u];
+  // the span's time: the earliest end of a transfer in flight (a8), reduced over the slots the
+  // matching of the previous span min-reduced into
+  const u64 t = wave_min64(p.next_slots[(event & 1u) * kNextSlots + (threadIdx.x & 63u)]);
+  if (blockIdx.x == 0 && threadIdx.x < kNextSlots) p.next_slots[((event + 1u) & 1u) * kNextSlots + threadIdx.x] = kInf;
   if (l == 0) {
     if (first_slot) *first_slot = ctl->n_rec;
+    ctl->next_t[event & 1u] = t;
     if (t == kInf) {
       // a4 / a8: nothing is in flight after the previous span's matching.  If no destination
       // needed a chunk there, every postcondition is satisfied and the collective ended at
@@ -321,9 +326,11 @@ __global__ __launch_bounds__(256) void arrive_slots_kernel(PassDev p, u32 event,
     }
   }
   if (ctl->done) return;
-  const u64 t = ctl->next_t[event & 1u];
+  const u64 t = wave_min64(p.next_slots[(event & 1u) * kNextSlots + (threadIdx.x & 63u)]);  // as arrive_kernel
+  if (blockIdx.x == 0 && threadIdx.x < kNextSlots) p.next_slots[((event + 1u) & 1u) * kNextSlots + threadIdx.x] = kInf;
   if (q == 0) {
     if (first_slot) *first_slot = ctl->n_rec;
+    ctl->next_t[event & 1u] = t;
     if (t == kInf) {  // as arrive_kernel
       if (event != 0u && ctl->need_flag[(event - 1u) & 1u] == 0u) {
         ctl->T = ctl->now;
@@ -1091,7 +1098,7 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   // a8: next span = earliest end of a transfer in flight (min over all destinations)
   const u64 m = wave_min64(my_min);
   if (lane == 0 && m != kInf) {
-    u64 *nt = &ctl->next_t[(event + 1u) & 1u];
+    u64 *nt = &p.next_slots[((event + 1u) & 1u) * kNextSlots + (slot & (kNextSlots - 1u))];
     const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (m < cur) atomicMin(nt, m);
   }
@@ -1125,7 +1132,7 @@ __global__ __launch_bounds__(256) void match_compact_kernel(PassDev p, u32 event
   else my_min = match_destination_pairs<NP, 0>(p, rows, d, jb, je, event, t, nullptr, lane, my_need, MODE == 2, rec);
   const u64 m = wave_min64(my_min);
   if (lane == 0 && m != kInf) {
-    u64 *nt = &ctl->next_t[(event + 1u) & 1u];
+    u64 *nt = &p.next_slots[((event + 1u) & 1u) * kNextSlots + (slot & (kNextSlots - 1u))];
     const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (m < cur) atomicMin(nt, m);
   }
@@ -1434,7 +1441,7 @@ __global__ __launch_bounds__(256) void match_kernel_streamed(PassDev p, u32 even
   const u64 my_min = match_destination_streamed(p, d, jb, je, event, t, sched_row, lane, my_need);
   const u64 m = wave_min64(my_min);
   if (lane == 0 && m != kInf) {
-    u64 *nt = &ctl->next_t[(event + 1u) & 1u];
+    u64 *nt = &p.next_slots[((event + 1u) & 1u) * kNextSlots + (slot & (kNextSlots - 1u))];
     const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (m < cur) atomicMin(nt, m);
   }
