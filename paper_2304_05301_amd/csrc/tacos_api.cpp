@@ -381,6 +381,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   if (!small && !uniform) {
     d_next_slots.alloc((size_t)2 * tacos::kNextSlots * 8);
     p.next_slots = d_next_slots.as<unsigned long long>();
+    p.next_mask = N <= 8192u ? tacos::kNextSlots - 1u : 0u;  // short launches spread over the words
   }
   tacos::launch_init_pass(p, stream);
   HIP_TRY(hipGetLastError());

@@ -80,11 +80,16 @@ struct PassDev {
   uint32_t *rnd;                   // [L] by in-list position: word 0 of Philox(link, current span, phase, 0),
                                    //     written by arrive_kernel for the link-centric match_kernel; else null
   // Per-span launches: the matching kernels min-reduce the end times of the transfers in flight
-  // into kNextSlots words per span parity ([2][kNextSlots], wavefronts spread over them: the
-  // wavefronts of a short launch all finish together, and thousands of atomics on ONE word
-  // take tens of microseconds); the arrivals kernel of the next span takes the minimum of the
-  // words, publishes it as Ctl::next_t and clears the other parity.  Null in the other modes.
+  // (a workgroup's four wavefronts through LDS, then one atomic, skipped if the word is already as
+  // small) into kNextSlots words per span parity ([2][kNextSlots]); the arrivals kernel of the next
+  // span takes the minimum of the words, publishes it as Ctl::next_t and clears the other parity.
+  // The workgroups of a SHORT launch all finish together, every one of them then sees the word
+  // still at infinity, and thousands of atomics on one address take tens of microseconds: such
+  // launches spread over all the words (next_mask = kNextSlots - 1); long launches, whose first
+  // finisher's value stops all the others, use the first word only (next_mask = 0; spreading
+  // costs them a few per cent).  Null in the other modes.
   unsigned long long *next_slots;
+  uint32_t next_mask;
   Ctl *ctl;
 };
 constexpr uint32_t kNextSlots = 64;

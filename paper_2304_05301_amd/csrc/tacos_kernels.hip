@@ -1082,25 +1082,34 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   const u32 per_xcd = gridDim.x >> 3;
   const u32 pos = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
   const u32 slot = uniform(pos * 4u + (threadIdx.x >> 6));
-  if (slot >= p.n_slots) return;
-  const uint4 sr = p.slot_rec[slot];  // (destination, its in-list begin, end)
-  const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
   Ctl *ctl = p.ctl;
-  if (ctl->done) return;
-  const u64 t = ctl->next_t[event & 1u];
   __shared__ uint4 need_lds[4 * NP * 64];
-  uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
-  u64 my_min;
-  const RowsHbm rows{p.held, p.row_words};
-  if constexpr (MODE == 0) my_min = match_destination<NP, false>(p, rows, d, jb, je, event, t, sched_row, lane, my_need);
-  else my_min = match_destination_pairs<NP, DEG>(p, rows, d, jb, je, event, t, sched_row, lane, my_need, MODE == 2);
-
-  // a8: next span = earliest end of a transfer in flight (min over all destinations)
+  __shared__ u64 wg_min[4];
+  u64 my_min = kInf;
+  if (slot < p.n_slots && !ctl->done) {
+    const uint4 sr = p.slot_rec[slot];  // (destination, its in-list begin, end)
+    const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
+    const u64 t = ctl->next_t[event & 1u];
+    uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
+    const RowsHbm rows{p.held, p.row_words};
+    if constexpr (MODE == 0) my_min = match_destination<NP, false>(p, rows, d, jb, je, event, t, sched_row, lane, my_need);
+    else my_min = match_destination_pairs<NP, DEG>(p, rows, d, jb, je, event, t, sched_row, lane, my_need, MODE == 2);
+  }
+  // a8: next span = earliest end of a transfer in flight (min over all destinations): the
+  // workgroup's four wavefronts through LDS, then one filtered atomic
   const u64 m = wave_min64(my_min);
-  if (lane == 0 && m != kInf) {
-    u64 *nt = &p.next_slots[((event + 1u) & 1u) * kNextSlots + (slot & (kNextSlots - 1u))];
-    const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (m < cur) atomicMin(nt, m);
+  if (lane == 0) wg_min[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    u64 mm = wg_min[0];
+    mm = wg_min[1] < mm ? wg_min[1] : mm;
+    mm = wg_min[2] < mm ? wg_min[2] : mm;
+    mm = wg_min[3] < mm ? wg_min[3] : mm;
+    if (mm != kInf) {
+      u64 *nt = &p.next_slots[((event + 1u) & 1u) * kNextSlots + (pos & p.next_mask)];
+      const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (mm < cur) atomicMin(nt, mm);
+    }
   }
 }
 
@@ -1116,25 +1125,34 @@ __global__ __launch_bounds__(256) void match_compact_kernel(PassDev p, u32 event
   const u32 per_xcd = gridDim.x >> 3;
   const u32 pos = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
   const u32 slot = uniform(pos * 4u + (threadIdx.x >> 6));
-  if (slot >= p.n_slots) return;
-  const uint4 sr = p.slot_rec[slot];
-  const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
   Ctl *ctl = p.ctl;
-  if (ctl->done) return;
-  const u64 t = ctl->next_t[event & 1u];
-  if (first_next && slot == 0u && lane == 0) *first_next = ctl->n_rec;
   __shared__ uint4 need_lds[4 * NP * 64];
-  uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
-  const RecOut rec = p.reversed ? RecOut() : RecOut{recs, &ctl->n_rec};
-  u64 my_min;
-  const RowsHbm rows{p.held, p.row_words};
-  if constexpr (MODE == 0) my_min = match_destination<NP, false>(p, rows, d, jb, je, event, t, nullptr, lane, my_need, rec);
-  else my_min = match_destination_pairs<NP, 0>(p, rows, d, jb, je, event, t, nullptr, lane, my_need, MODE == 2, rec);
-  const u64 m = wave_min64(my_min);
-  if (lane == 0 && m != kInf) {
-    u64 *nt = &p.next_slots[((event + 1u) & 1u) * kNextSlots + (slot & (kNextSlots - 1u))];
-    const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (m < cur) atomicMin(nt, m);
+  __shared__ u64 wg_min[4];
+  u64 my_min = kInf;
+  if (slot < p.n_slots && !ctl->done) {
+    const uint4 sr = p.slot_rec[slot];
+    const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
+    const u64 t = ctl->next_t[event & 1u];
+    if (first_next && slot == 0u && lane == 0) *first_next = ctl->n_rec;
+    uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
+    const RecOut rec = p.reversed ? RecOut() : RecOut{recs, &ctl->n_rec};
+    const RowsHbm rows{p.held, p.row_words};
+    if constexpr (MODE == 0) my_min = match_destination<NP, false>(p, rows, d, jb, je, event, t, nullptr, lane, my_need, rec);
+    else my_min = match_destination_pairs<NP, 0>(p, rows, d, jb, je, event, t, nullptr, lane, my_need, MODE == 2, rec);
+  }
+  const u64 m = wave_min64(my_min);  // as match_kernel
+  if (lane == 0) wg_min[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    u64 mm = wg_min[0];
+    mm = wg_min[1] < mm ? wg_min[1] : mm;
+    mm = wg_min[2] < mm ? wg_min[2] : mm;
+    mm = wg_min[3] < mm ? wg_min[3] : mm;
+    if (mm != kInf) {
+      u64 *nt = &p.next_slots[((event + 1u) & 1u) * kNextSlots + (pos & p.next_mask)];
+      const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (mm < cur) atomicMin(nt, mm);
+    }
   }
 }
 
@@ -1441,7 +1459,7 @@ __global__ __launch_bounds__(256) void match_kernel_streamed(PassDev p, u32 even
   const u64 my_min = match_destination_streamed(p, d, jb, je, event, t, sched_row, lane, my_need);
   const u64 m = wave_min64(my_min);
   if (lane == 0 && m != kInf) {
-    u64 *nt = &p.next_slots[((event + 1u) & 1u) * kNextSlots + (slot & (kNextSlots - 1u))];
+    u64 *nt = &p.next_slots[((event + 1u) & 1u) * kNextSlots + (slot & p.next_mask)];
     const u64 cur = __hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (m < cur) atomicMin(nt, m);
   }
