@@ -578,7 +578,7 @@ __device__ __forceinline__ u32 draw_chunks(const Rows &rows, u32 s, const u32 &r
 template <int NP, bool LATENCY_BOUND, class Rows>
 __device__ __forceinline__ u64 match_destination(const PassDev &p, const Rows &rows, u32 d, u32 jb, u32 je, u32 event,
                                                      u64 t, u32 *__restrict__ sched_row, int lane, uint4 *need_lds,
-                                                     const RecOut rec = RecOut())
+                                                     const RecOut rec = RecOut(), u32 *wave_need = nullptr)
 {
   constexpr int NW = 2 * NP;
   Ctl *ctl = p.ctl;
@@ -647,7 +647,11 @@ __device__ __forceinline__ u64 match_destination(const PassDev &p, const Rows &r
     // d holds every chunk: nothing is or will be in flight to it, its links stay idle for
     // good, and the host may drop it from the processing order
     if (!need_any && p.dest_done && lane == 0) p.dest_done[d] = 1u;
-    if (need_any && lane == 0) state_st<LATENCY_BOUND>(&ctl->need_flag[event & 1u], 1u);
+    // (wave_need: the caller collects the flag per workgroup instead of one store per wavefront)
+    if (need_any && lane == 0) {
+      if (wave_need) *wave_need = 1u;
+      else state_st<LATENCY_BOUND>(&ctl->need_flag[event & 1u], 1u);
+    }
     for (u32 base = jb; base < je; base += 64) {
       const u32 j = base + lane;
       u32 cr = kNone;
@@ -1085,14 +1089,18 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   Ctl *ctl = p.ctl;
   __shared__ uint4 need_lds[4 * NP * 64];
   __shared__ u64 wg_min[4];
+  __shared__ u32 wg_need[4];
   u64 my_min = kInf;
+  if (lane == 0) wg_need[threadIdx.x >> 6] = 0u;
   if (slot < p.n_slots && !ctl->done) {
     const uint4 sr = p.slot_rec[slot];  // (destination, its in-list begin, end)
     const u32 d = uniform(sr.x), jb = uniform(sr.y), je = uniform(sr.z);
     const u64 t = ctl->next_t[event & 1u];
     uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
     const RowsHbm rows{p.held, p.row_words};
-    if constexpr (MODE == 0) my_min = match_destination<NP, false>(p, rows, d, jb, je, event, t, sched_row, lane, my_need);
+    if constexpr (MODE == 0)
+      my_min = match_destination<NP, false>(p, rows, d, jb, je, event, t, sched_row, lane, my_need, RecOut(),
+                                            &wg_need[threadIdx.x >> 6]);
     else my_min = match_destination_pairs<NP, DEG>(p, rows, d, jb, je, event, t, sched_row, lane, my_need, MODE == 2);
   }
   // a8: next span = earliest end of a transfer in flight (min over all destinations): the
@@ -1101,6 +1109,9 @@ void match_kernel(PassDev p, u32 event, u32 *__restrict__ sched_row)
   if (lane == 0) wg_min[threadIdx.x >> 6] = m;
   __syncthreads();
   if (threadIdx.x == 0) {
+    if constexpr (MODE == 0) {
+      if ((wg_need[0] | wg_need[1] | wg_need[2] | wg_need[3]) != 0u) ctl->need_flag[event & 1u] = 1u;
+    }
     u64 mm = wg_min[0];
     mm = wg_min[1] < mm ? wg_min[1] : mm;
     mm = wg_min[2] < mm ? wg_min[2] : mm;
