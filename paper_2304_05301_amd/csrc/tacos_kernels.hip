@@ -244,6 +244,15 @@ __device__ __forceinline__ void append_records(const RecOut &rec, bool has, u32 
 
 // ---------------------------------------------------------------- a3: arrivals
 
+// The time of span `event`: the minimum of the words the matching of the span before reduced into
+// (all of them, or only the first one: PassDev::next_mask).  Wave-uniform; all 64 lanes call it.
+__device__ __forceinline__ u64 next_event_time(const PassDev &p, u32 event)
+{
+  const u64 *w = p.next_slots + (event & 1u) * kNextSlots;
+  if (p.next_mask == 0u) return w[0];
+  return wave_min64(w[threadIdx.x & 63u]);
+}
+
 // Compact schedules (recs != null; see RecOut): a reversed pass appends its arrivals as (link,
 // chunk) records at ctl->n_rec; first_slot, if not null, receives the index of the span's first
 // record (forward pass: the matching kernel appends the span's matches after this launch).
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(256) void arrive_kernel(PassDev p, u32 event, u64 *
   if (ctl->done) return;
   // the span's time: the earliest end of a transfer in flight (a8), reduced over the slots the
   // matching of the previous span min-reduced into
-  const u64 t = wave_min64(p.next_slots[(event & 1u) * kNextSlots + (threadIdx.x & 63u)]);
+  const u64 t = next_event_time(p, event);
   if (blockIdx.x == 0 && threadIdx.x < kNextSlots) p.next_slots[((event + 1u) & 1u) * kNextSlots + threadIdx.x] = kInf;
   if (l == 0) {
     if (first_slot) *first_slot = ctl->n_rec;
@@ -326,7 +335,7 @@ __global__ __launch_bounds__(256) void arrive_slots_kernel(PassDev p, u32 event,
     }
   }
   if (ctl->done) return;
-  const u64 t = wave_min64(p.next_slots[(event & 1u) * kNextSlots + (threadIdx.x & 63u)]);  // as arrive_kernel
+  const u64 t = next_event_time(p, event);  // as arrive_kernel
   if (blockIdx.x == 0 && threadIdx.x < kNextSlots) p.next_slots[((event + 1u) & 1u) * kNextSlots + threadIdx.x] = kInf;
   if (q == 0) {
     if (first_slot) *first_slot = ctl->n_rec;
