@@ -115,13 +115,18 @@ def main():
     if os.path.exists(bench_json):
         with open(bench_json) as f:
             spans = json.loads(f.read().strip().splitlines()[-1])["ten_spans"]
+    # tail_sweep_kernel: one workgroup sweeping the last stretch of a pass, many spans per launch
+    tail = [e - s for s, e, n in trace if "tail_sweep_kernel" in n]
     if kernel == "match_kernel":
         if spans is None:
             spans = sum(1 for d in durs if d > 0.3 * max(durs))
-        work = sorted(durs, reverse=True)[:spans]
+        # (a pass that ends inside a tail launch queues no match_kernel launch past its end)
+        work = list(durs) if tail else sorted(durs, reverse=True)[:spans]
     else:
         work = durs
-    mean_us = sum(work) / len(work) / 1e3
+    # launches, a tail launch counted once per span it swept (as tacos_result_kernel_launches does)
+    n_units = spans if tail else len(work)
+    mean_us = (sum(work) + sum(tail)) / n_units / 1e3
     out = [f"rocprofv3 summary: {kernel} on workload {w.name}{' (matching = %d)' % args.matching if args.matching else ''} "
            f"({w.topo.n_npus} NPUs, {w.topo.n_links} links, {w.topo.n_npus * w.chunks_per_npu} chunks of {w.chunk_bytes} B, seed {w.seed})",
            "device: AMD Instinct MI355X (gfx950, 256 CUs), ROCm 7.2.0; automatic launch mode",
@@ -133,8 +138,15 @@ def main():
             out.append(f"{n} | {row['Calls']} | {row['TotalDurationNs']} | {float(row['AverageNs']):.1f} | "
                        f"{row['Percentage']} | {row['MinNs']} | {row['MaxNs']}")
     out.append("")
-    out.append(f"{kernel}: {len(durs)} launches, {len(work)} of them did work; working launches: mean {mean_us:.2f} us, "
-               f"median {sorted(work)[len(work) // 2] / 1e3:.2f} us")
+    if tail:
+        out.append(f"{kernel}: {len(durs)} launches, all of them did work ({sum(work) / 1e6:.1f} ms); tail_sweep_kernel: "
+                   f"{len(tail)} launches sweeping the other {spans - len(work)} spans ({sum(tail) / 1e6:.1f} ms, "
+                   f"{sum(tail) / max(1, spans - len(work)) / 1e3:.2f} us per span); per span over all {spans}: mean "
+                   f"{mean_us:.2f} us; {kernel} alone: mean {sum(work) / len(work) / 1e3:.2f} us, "
+                   f"median {sorted(work)[len(work) // 2] / 1e3:.2f} us")
+    else:
+        out.append(f"{kernel}: {len(durs)} launches, {len(work)} of them did work; working launches: mean {mean_us:.2f} us, "
+                   f"median {sorted(work)[len(work) // 2] / 1e3:.2f} us")
     if kernel == "match_kernel":
         # per span: arrive -> (gap) -> match -> (gap) -> next arrive, over the working spans
         thr = sorted(durs, reverse=True)[len(work) - 1]
@@ -147,9 +159,10 @@ def main():
                 arr.append(trace[i - 1][1] - trace[i - 1][0])
         if arr:
             a, g1, g2 = (sum(x) / len(x) / 1e3 for x in (arr, g_am, g_ma))
-            span = mean_us + a + g1 + g2
-            out.append(f"per span ({len(arr)} spans): arrivals kernel {a:.2f} us + gap {g1:.2f} us + {kernel} {mean_us:.2f} us + "
-                       f"gap {g2:.2f} us = {span:.2f} us; outside {kernel}: {100 * (span - mean_us) / span:.1f} %")
+            m_us = sum(work) / len(work) / 1e3
+            span = m_us + a + g1 + g2
+            out.append(f"per span with two launches ({len(arr)} spans): arrivals kernel {a:.2f} us + gap {g1:.2f} us + {kernel} "
+                       f"{m_us:.2f} us + gap {g2:.2f} us = {span:.2f} us; outside {kernel}: {100 * (span - m_us) / span:.1f} %")
     n_chunks = w.topo.n_npus * w.chunks_per_npu
     wb = 8 * ((n_chunks + 63) // 64)
     out.append("")
@@ -162,8 +175,10 @@ def main():
         cp_w = wr["WRITE_SIZE"]["__amd_rocclr_copyBuffer"][2]
         fs, ws = 1048576 / cp_f, 1048576 / cp_w
         mk = [k for k in fe["FETCH_SIZE"] if kernel in k][0]
-        fb = fe["FETCH_SIZE"][mk][1] * fs * 1024 / len(work)
-        wbytes = wr["WRITE_SIZE"][mk][1] * ws * 1024 / len(work)
+        tk = [k for k in fe["FETCH_SIZE"] if "tail_sweep_kernel" in k]  # counted with the launches it replaces
+        total = lambda table: table[mk][1] + sum(table[k][1] for k in tk)
+        fb = total(fe["FETCH_SIZE"]) * fs * 1024 / n_units
+        wbytes = total(wr["WRITE_SIZE"]) * ws * 1024 / n_units
         out += ["commands (counters, one run each; --calibrate-copy adds one plain 1 GiB device copy as reference dispatch):",
                 "  " + cmds["fetch"], "  " + cmds["write"], "  " + cmds["tcc"],
                 f"reference: plain device copy of 1 GiB: FETCH_SIZE reads {cp_f:.1f} (KiB units) -> scale {fs:.4f}; "
@@ -175,10 +190,10 @@ def main():
         tcc_dir = os.path.join(args.dir, f"prof_{t}_tcc")
         if os.path.isdir(tcc_dir):
             tc = counters(tcc_dir)
-            hit, miss, req = (tc[c][mk][1] for c in ("TCC_HIT_sum", "TCC_MISS_sum", "TCC_REQ_sum"))
-            out.append(f"  L2 (TCC) per working launch: {req / len(work) / 1e6:.2f} M requests of 128 B = "
-                       f"{req / len(work) * 128 / 1e6:.1f} MB asked of L2, hit rate {100 * hit / (hit + miss):.1f} %")
-            vals["l2_request_bytes_per_launch"] = f"{req / len(work) * 128:.0f}"
+            hit, miss, req = (total(tc[c]) for c in ("TCC_HIT_sum", "TCC_MISS_sum", "TCC_REQ_sum"))
+            out.append(f"  L2 (TCC) per working launch: {req / n_units / 1e6:.2f} M requests of 128 B = "
+                       f"{req / n_units * 128 / 1e6:.1f} MB asked of L2, hit rate {100 * hit / (hit + miss):.1f} %")
+            vals["l2_request_bytes_per_launch"] = f"{req / n_units * 128:.0f}"
             vals["l2_hit_rate"] = f"{hit / (hit + miss):.4f}"
         with open(os.path.join(out_dir, f"{kernel}_{w.name}{variant}_traffic.txt"), "w") as f:
             f.write(f"# per working launch of {kernel}: bytes beyond L2 (FETCH_SIZE + WRITE_SIZE, each scaled by a plain 1 GiB copy)\n"

@@ -133,7 +133,11 @@ typedef struct {
                              available                                                      */
   uint32_t launch_mode;   /* 0 = automatic.
                              1 = two plain launches per span (arrivals; matching + next-event
-                             reduction), queued in batches.
+                             reduction), queued in batches; once at most 16 destinations
+                             still miss chunks (link-centric matching, complete runs, dense
+                             schedule rows), one workgroup sweeps the remaining spans, many per
+                             launch, with those destinations' link state in registers.
+                             4 = as 1, with two launches for every span up to the last.
                              2 = small topologies: ONE workgroup sweeps many spans per launch
                              with the per-link state and a work list in LDS and matches only
                              the destinations something changed for; needs links, NPUs and
@@ -244,7 +248,8 @@ int tacos_result_link_counts(const tacos_result_t *r, uint32_t pass, uint64_t *l
 uint64_t tacos_result_digest(const tacos_result_t *r);
 /* Milliseconds spent inside the kernel that does the matching (sum over its launches:
  * the per-span matching kernel, or the single-workgroup sweep kernel of launch_mode 2) and
- * the number of launches; 0 unless opts->time_kernels was set. */
+ * the number of launches (a launch of the per-span form that sweeps the last stretch of a
+ * pass counts once per span it swept); 0 unless opts->time_kernels was set. */
 double   tacos_result_kernel_ms(const tacos_result_t *r);
 uint64_t tacos_result_kernel_launches(const tacos_result_t *r);
 /* Host wall-clock milliseconds of the whole tacos_synthesize call. */

@@ -472,10 +472,29 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
       if (stop_event != 0xFFFFFFFFu) { stopped = true; break; }
     }
   } else {
+    // Link-centric passes with dense rows: once at most kTailSlots destinations are left in the
+    // processing order, one single-workgroup launch sweeps many spans (tail_sweep_kernel), up
+    // to the end of the row segment.  launch_mode 4 keeps two launches for every span.
+    const bool tail_ok = launch_mode != 4 && !uniform && !compact_spans && match_mode == 0 && NP <= 8 && max_events == 0 &&
+                         p.max_deg >= 1u && p.max_deg <= 64u;
+    constexpr uint32_t kTailBatch = 1024;
     uint32_t batch = 8;
     for (;;) {
       size_t n_timed = 0;
+      uint64_t tail_spans = 0;  // spans of this batch swept by a tail launch (then the whole batch)
       if (time_kernels) pool.ensure(2 * (size_t)batch);
+      if (tail_ok && p.n_slots <= tacos::kTailSlots) {
+        if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
+        uint32_t *row = nullptr;
+        unsigned long long *tslot = nullptr;
+        row_slot(e, &row, &tslot);
+        const uint64_t seg_end = (e / pass.rows_per_seg + 1) * pass.rows_per_seg;
+        tail_spans = std::min<uint64_t>(std::min<uint64_t>(kTailBatch, seg_end - e), 0xFFFFFFFEull - e);
+        if (time_kernels) HIP_TRY(hipEventRecord(pool.ev[0], stream));
+        HIP_TRY(tacos::launch_tail_sweep(p, (uint32_t)e, (uint32_t)tail_spans, row, pass.row_stride(), tslot, stream));
+        if (time_kernels) { HIP_TRY(hipEventRecord(pool.ev[1], stream)); n_timed = 1; }
+        e += tail_spans;
+      } else
       for (uint32_t i = 0; i < batch; ++i) {
         if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
         uint32_t *row = nullptr;
@@ -517,7 +536,14 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
       HIP_TRY(hipMemcpyAsync(host_ctl.p, p.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, stream));
       HIP_TRY(hipStreamSynchronize(stream));
       const bool done = host_ctl.p->done != 0;
-      if (time_kernels) {
+      if (time_kernels && tail_spans) {
+        // a tail launch counts once per span it swept
+        const uint64_t e_first = e - tail_spans, e_end = host_ctl.p->n_events;
+        const uint64_t useful = !done ? tail_spans : (e_end > e_first ? std::min<uint64_t>(tail_spans, e_end - e_first) : 0);
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, pool.ev[0], pool.ev[1]));
+        if (useful) { res.kernel_ms += ms; res.kernel_launches += useful; }
+      } else if (time_kernels) {
         // launches after the pass ended return at once; count the ones that did work
         const uint64_t e_first = e - n_timed, e_end = host_ctl.p->n_events;
         const uint64_t useful = !done ? n_timed : (e_end > e_first ? std::min<uint64_t>(n_timed, e_end - e_first) : 0);
@@ -733,7 +759,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
   if (rc != TACOS_OK) return rc;
   const uint64_t max_events = opts ? opts->max_events : 0;
   if (max_events && has_reversed_pass((int)coll)) return TACOS_E_INVAL;
-  if (opts && (opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 3 ||
+  if (opts && (opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 4 ||
                opts->matching > TACOS_MATCH_POSTCONDITION))
     return TACOS_E_INVAL;
   // kernel variant: 0 link-centric; 1 postcondition-centric, random holder; 2 first holder
@@ -837,7 +863,7 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
   if (!seeds || n_seeds == 0 || !time_ps) return TACOS_E_INVAL;
   int rc = validate(topo, chunks_per_npu, chunk_bytes, (int)coll, opts);
   if (rc != TACOS_OK) return rc;
-  if (opts && (opts->max_events != 0 || opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 3 ||
+  if (opts && (opts->max_events != 0 || opts->link_order > TACOS_LINK_ORDER_COST || opts->launch_mode > 4 ||
                opts->matching > TACOS_MATCH_POSTCONDITION))
     return TACOS_E_INVAL;
   uint32_t match_mode = 0;

@@ -144,6 +144,15 @@ void launch_arrive(const PassDev &p, uint32_t event, unsigned long long *event_t
 // mode 0: link-centric; 1: postcondition-centric with a random holder link; 2: postcondition-
 // centric with the first holder of the incoming list (in-degree <= 64 for modes 1, 2)
 void launch_match(const PassDev &p, uint32_t event, uint32_t *sched_row, uint32_t mode, hipStream_t s);
+// Per-span launches with at most kTailSlots destinations left in the processing order (link-centric
+// matching, dense schedule rows, in-degrees up to 64, rows of at most 8 pieces): one workgroup
+// sweeps spans first_event .. first_event + n_spans - 1 (or up to the end of the pass) in ONE
+// launch, arrivals and matching; rows0 / times0 are the schedule row and time slot of span
+// first_event, the rows of the following spans row_stride words apart (same segment).  Leaves
+// the state as launch_arrive + launch_match of those spans would.
+constexpr uint32_t kTailSlots = 16;
+hipError_t launch_tail_sweep(const PassDev &p, uint32_t first_event, uint32_t n_spans, uint32_t *rows0,
+                             unsigned long long row_stride, unsigned long long *times0, hipStream_t s);
 // The same with a compact schedule: a forward pass appends its matches as (link, chunk) records
 // at Ctl::n_rec; first_next, if not null (reversed pass), receives the index at which the records
 // of the next span (its arrivals) start.  Rows of at most 8 pieces.

@@ -1862,6 +1862,161 @@ __global__ __launch_bounds__(1024) void small_sweep_batch_kernel(const SmallJob 
                                            nullptr, nullptr, dst_in_lds, held_lanes, rec_in_lds);
 }
 
+// ---------------------------------------------------------------- last stretch of a pass: few destinations left
+
+// Per-span launches, link-centric matching, dense schedule rows: once at most kTailSlots
+// destinations are left in the processing order (on a mesh the corner NPUs, whose two or three
+// incoming links need thousands of spans more than everyone else's), ONE workgroup sweeps many
+// spans per launch, one wavefront per destination and one lane per incoming link (in-degrees up
+// to 64).  The lane keeps its link's state (chunk carried, busy-until time) in registers and the
+// wavefront its destination's need row in LDS for the whole launch: an arrival moves a chunk
+// from "in flight" to "held", which leaves need = ~held & ~inflight as it is, and a match clears
+// its bit, so after the set-up a span costs no read of d's own row, of the records or of the
+// link state.  Arrivals are atomics on the held table in device memory as in arrive_kernel; a
+// workgroup barrier separates them from the matching, whose source rows may belong to another
+// wavefront's destination.  Span times, schedule rows, the control block and (on return) the
+// link state and the next event time are written exactly as arrive_kernel and match_kernel
+// write them, so the host may switch between the two forms at any span.
+// rows0 / times0: schedule row and time slot of span first_event; the launch stays inside one
+// row segment, row_stride apart.
+template <int NP>
+__global__ __launch_bounds__(64 * kTailSlots) void tail_sweep_kernel(PassDev p, u32 first_event, u32 n_spans,
+                                                                     u32 *__restrict__ rows0, u64 row_stride,
+                                                                     u64 *__restrict__ times0)
+{
+  constexpr int NW = 2 * NP;
+  extern __shared__ __align__(16) unsigned char tail_lds[];  // kTailSlots need rows of NP KiB
+  __shared__ u64 s_min[2][kTailSlots];
+  __shared__ u32 s_need[2][kTailSlots];
+  const int lane = threadIdx.x & 63;
+  const u32 w = uniform(threadIdx.x >> 6);
+  Ctl *ctl = p.ctl;
+  if (ctl->done) return;
+  uint4 *need_lds = reinterpret_cast<uint4 *>(tail_lds) + w * NP * 64;
+  const RowsHbm rows{p.held, p.row_words};
+  const bool active = w < p.n_slots;
+  u32 d = 0, jb = 0, je = 0;
+  if (active) {
+    const uint4 sr = p.slot_rec[w];
+    d = uniform(sr.x); jb = uniform(sr.y); je = uniform(sr.z);
+  }
+  const u32 j = jb + (u32)lane;
+  const bool valid = active && j < je;
+  u32 link = 0, src = 0, cr = kNone;
+  u64 cs = 0, fa = 0;
+  if (valid) {
+    const uint4 rec = p.in_rec[j];
+    link = rec.x; src = rec.y; cs = ((u64)rec.w << 32) | rec.z;
+    cr = p.carry[j];
+    fa = p.free_at[j];
+  }
+  if (active) {
+    // need = ~held[d] & ~inflight[d] (as match_destination sets it up)
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      uint4 v = rows.load(d, i, lane);
+      v.x = ~v.x; v.y = ~v.y; v.z = ~v.z; v.w = ~v.w;
+      need_lds[i * 64 + lane] = v;
+    }
+    if (cr != kNone) {
+      const u32 wd = cr >> 6;
+      const u32 ln = wd / (u32)NW;
+      const u32 iw = wd - ln * (u32)NW;
+      u32 *ptr = reinterpret_cast<u32 *>(&need_lds[(iw >> 1) * 64u + ln]) + ((iw & 1u) * 2u + ((cr >> 5) & 1u));
+      atomicAnd(ptr, ~(1u << (cr & 31u)));
+    }
+  }
+  u64 t = next_event_time(p, first_event);  // time of the span at hand, kInf: nothing in flight
+  u64 t_before = ctl->now;
+  u32 need_before = first_event != 0u ? ctl->need_flag[(first_event - 1u) & 1u] : 1u;
+  u32 i = 0;
+  bool ended = false;  // uniform
+  for (; i < n_spans; ++i) {
+    const u32 event = first_event + i;
+    if (threadIdx.x == 0) {  // as arrive_kernel
+      ctl->next_t[event & 1u] = t;
+      if (t == kInf) {
+        if (event != 0u && need_before == 0u) {
+          ctl->T = t_before;
+          ctl->n_events = event - 1u;
+        } else {
+          ctl->status = kStUnreachable;
+        }
+        ctl->done = 1u;
+      } else {
+        times0[i] = t;
+        ctl->now = t;
+        ctl->next_t[(event + 1u) & 1u] = kInf;
+      }
+    }
+    if (t == kInf) { ended = true; break; }
+    u32 *row = rows0 + (u64)i * row_stride;
+    // a3: arrivals on this wavefront's links
+    if (valid && cr != kNone && fa == t) {
+      atomicOr(&p.held[(u64)d * p.row_words + phys_word(cr >> 6, p.NP)], 1ull << (cr & 63u));
+      if (p.reversed) row[link] = cr;  // rows are pre-filled with kNone
+      cr = kNone;
+    }
+    __syncthreads();  // the arrival atomics of all wavefronts have been performed
+    // a5-a7: matching
+    const u64 idle = __ballot(valid && cr == kNone);
+    u32 acc = 0;
+    if (idle != 0ull) {
+#pragma unroll
+      for (int q = 0; q < NP; ++q) {
+        const uint4 v = need_lds[q * 64 + lane];
+        acc |= v.x | v.y | v.z | v.w;
+      }
+    }
+    const bool need_now = __ballot(acc != 0u) != 0ull;
+    // what match_destination calls need_any: chunks d does not hold, in flight or not
+    const bool need_any = need_now || __ballot(valid && cr != kNone) != 0ull;
+    u32 res = kNone;
+    if (idle != 0ull && need_now) {
+      u32 r = 0;
+      res = draw_chunks<NP>(rows, src, r, idle, need_lds, lane, [&]() {
+        r = philox4x32_10_word0(link, event, p.phase, 0u, p.seed_lo, p.seed_hi);  // behind the first row request
+        return true;
+      });
+    }
+    if (idle != 0ull && !need_any && p.dest_done && lane == 0) p.dest_done[d] = 1u;
+    if (valid && res != kNone) {
+      if (res >= p.C) {
+        ctl->status = kStInternal;
+        ctl->done = 1u;
+      } else if (cs > kInf - 1ull - t) {
+        ctl->status = kStOverflow;
+        ctl->done = 1u;
+      } else {
+        if (!p.reversed) row[link] = res;
+        cr = res;
+        fa = t + cs;
+      }
+    }
+    // a8: next span = earliest end of a transfer in flight; the buffers alternate, so one
+    // barrier per reduction is enough
+    const u64 m = wave_min64((valid && cr != kNone) ? fa : kInf);
+    if (lane == 0) {
+      s_min[i & 1u][w] = m;
+      s_need[i & 1u][w] = (idle != 0ull && need_any) ? 1u : 0u;
+    }
+    lds_barrier();
+    const u64 tn = wave_min64((u32)lane < kTailSlots ? s_min[i & 1u][lane] : kInf);
+    const u32 nd = __ballot((u32)lane < kTailSlots && s_need[i & 1u][lane] != 0u) != 0ull ? 1u : 0u;
+    if (threadIdx.x == 0) ctl->need_flag[event & 1u] = nd;
+    t_before = t;
+    need_before = nd;
+    t = tn;
+  }
+  // hand the state back: the link state, and the next event time where arrive_kernel looks for it
+  if (valid) {
+    p.carry[j] = cr;
+    p.free_at[j] = fa;
+  }
+  if (!ended && threadIdx.x < kNextSlots)
+    p.next_slots[((first_event + i) & 1u) * kNextSlots + threadIdx.x] = threadIdx.x == 0 ? t : kInf;
+}
+
 // ---------------------------------------------------------------- epilogue
 
 __device__ __forceinline__ u64 mix_record(u64 t, u32 link, u32 chunk)
@@ -2228,6 +2383,35 @@ void launch_match(const PassDev &p, u32 event, u32 *sched_row, u32 mode, hipStre
   if (mode == 0) launch_match_mode<0, 0>(p, event, sched_row, s);
   else if (mode == 1) launch_match_pairs<1>(p, event, sched_row, s);
   else launch_match_pairs<2>(p, event, sched_row, s);
+}
+
+hipError_t launch_tail_sweep(const PassDev &p, u32 first_event, u32 n_spans, u32 *rows0, u64 row_stride, u64 *times0,
+                             hipStream_t s)
+{
+  if (p.n_slots > kTailSlots || p.max_deg > 64u || p.NP > 8u || n_spans == 0u) return hipErrorInvalidValue;
+  const size_t lds = (size_t)kTailSlots * p.NP * 1024;
+#define TACOS_TAIL(NP_)                                                                                      \
+  {                                                                                                          \
+    /* more than 64 KiB of dynamic LDS has to be allowed explicitly */                                       \
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tail_sweep_kernel<NP_>),        \
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
+    if (e != hipSuccess) return e;                                                                           \
+    hipLaunchKernelGGL((tail_sweep_kernel<NP_>), dim3(1), dim3(64 * kTailSlots), lds, s, p, first_event, n_spans, rows0, \
+                       row_stride, times0);                                                                  \
+    return hipGetLastError();                                                                                \
+  }
+  switch (p.NP) {
+    case 1: TACOS_TAIL(1)
+    case 2: TACOS_TAIL(2)
+    case 3: TACOS_TAIL(3)
+    case 4: TACOS_TAIL(4)
+    case 5: TACOS_TAIL(5)
+    case 6: TACOS_TAIL(6)
+    case 7: TACOS_TAIL(7)
+    case 8: TACOS_TAIL(8)
+    default: return hipErrorInvalidValue;
+  }
+#undef TACOS_TAIL
 }
 
 void launch_uniform_init(const PassDev &p, const UniformDev &u, uint32_t mode, hipStream_t s)

@@ -223,11 +223,11 @@ def test_kernel_timing_is_reported(stream):
 
 
 @pytest.mark.parametrize("name,mk,cpn,coll", SMALL, ids=[c[0] for c in SMALL])
-@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("mode", [1, 2, 4])
 def test_explicit_launch_modes_bit_exact(name, mk, cpn, coll, mode, stream):
-    """launch_mode 1 (two launches per span) and 2 (one workgroup sweeping many spans with
-    the link state in LDS) give the schedule of the oracle, like the automatic mode the
-    other tests use."""
+    """launch_mode 1 (two launches per span, one workgroup sweeping the last stretch of a pass),
+    4 (two launches per span to the end) and 2 (one workgroup sweeping many spans with the link
+    state in LDS) give the schedule of the oracle, like the automatic mode the other tests use."""
     topo = mk()
     cb = 192 << 10
     ref = cpu(topo, cpn, cb, coll, 5)
@@ -499,18 +499,51 @@ def test_workload_4_prefix_through_the_per_span_launches(stream):
         assert r.device_bytes < 64 << 20
 
 
+@pytest.mark.parametrize("mode", [1, 4])
 @pytest.mark.parametrize("coll", [T.ALL_GATHER, T.REDUCE_SCATTER, T.ALL_REDUCE])
-def test_heterogeneous_mesh_with_few_destinations_left(coll, stream):
+def test_heterogeneous_mesh_with_few_destinations_left(coll, mode, stream):
     """A mesh with different link classes per dimension through the per-span launches:
     the interior completes long before the corners, the host drops complete destinations
     from the launches, and the arrivals are then looked for in the remaining in-lists
-    only; spans sit on many distinct times, forward and reversed passes.  Record by record."""
+    only; spans sit on many distinct times, forward and reversed passes.  With launch_mode 1
+    the last stretch (at most 16 destinations left) is swept by one workgroup, many spans per
+    launch; with 4 every span keeps its two launches.  Record by record."""
     topo = T.grid([14, 11], False, [300_000, 700_000], [5_000, 20_000])
     ref = cpu(topo, 2, 96 << 10, coll, 23, n_threads=min(16, oracle.max_threads()))
-    with gpu(topo, 2, 96 << 10, coll, 23, stream, launch_mode=1) as r:
+    with gpu(topo, 2, 96 << 10, coll, 23, stream, launch_mode=mode) as r:
         assert_same(r, ref, "hetero mesh 14x11")
         n_pass = 2 if coll == T.ALL_REDUCE else 1
         assert [r.pass_events(i) for i in range(n_pass)] == list(ref.pass_events)[:n_pass]
+
+
+TAIL = [
+    # at most 16 NPUs: the whole pass is swept by the single-workgroup tail launches, 1,024 spans each
+    ("biring12_cpn150", lambda: T.grid([12], True, [300_000], [5_000]), 150, T.ALL_GATHER, 96 << 10),
+    ("mesh4x4_hetero_cpn200_ar", lambda: T.grid([4, 4], False, [300_000, 700_000], [5_000, 20_000]), 200, T.ALL_REDUCE, 64 << 10),
+    ("uniring16_rs_two_piece_rows", lambda: T.ring(16), 700, T.REDUCE_SCATTER, MiB),
+    # larger: two launches per span first, the tail launches take over when 16 destinations are left
+    ("mesh9x7_corners_last_ar", lambda: T.mesh2d(9, 7), 40, T.ALL_REDUCE, MiB),
+    ("mesh3d_5x4x3_hetero_ag", lambda: T.grid([5, 4, 3], False, [300_000, 500_000, 900_000], [5_000, 10_000, 20_000]), 30,
+     T.ALL_GATHER, 256 << 10),
+]
+
+
+@pytest.mark.parametrize("name,mk,cpn,coll,cb", TAIL, ids=[c[0] for c in TAIL])
+def test_last_stretch_of_a_pass_in_one_workgroup(name, mk, cpn, coll, cb, stream):
+    """launch_mode 1 once at most 16 destinations still miss chunks: one workgroup sweeps the
+    remaining spans, many per launch, with the link state in registers and the need rows in LDS;
+    it takes over from the two launches per span (or runs the whole pass), hands over from one
+    launch to the next, and ends the pass.  Record by record against the oracle, and the same
+    digest, times and span counts as launch_mode 4 (two launches for every span); with kernel
+    timing one launch is counted per span."""
+    topo = mk()
+    ref = cpu(topo, cpn, cb, coll, 41, n_threads=min(16, oracle.max_threads()))
+    with gpu(topo, cpn, cb, coll, 41, stream, launch_mode=1, time_kernels=True) as r:
+        assert_same(r, ref, name)
+        assert r.kernel_launches == r.num_events
+        with gpu(topo, cpn, cb, coll, 41, stream, launch_mode=4) as q:
+            assert q.digest == r.digest and q.collective_time_ps == r.collective_time_ps
+            assert q.num_events == r.num_events and q.num_xfers == r.num_xfers
 
 
 @pytest.mark.parametrize("idx,n_ev", [(6, 40), (7, 40)])
