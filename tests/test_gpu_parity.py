@@ -521,6 +521,12 @@ TAIL = [
     ("biring12_cpn150", lambda: T.grid([12], True, [300_000], [5_000]), 150, T.ALL_GATHER, 96 << 10),
     ("mesh4x4_hetero_cpn200_ar", lambda: T.grid([4, 4], False, [300_000, 700_000], [5_000, 20_000]), 200, T.ALL_REDUCE, 64 << 10),
     ("uniring16_rs_two_piece_rows", lambda: T.ring(16), 700, T.REDUCE_SCATTER, MiB),
+    # rows of 3, 5, 6 and 8 pieces (every row width is its own instantiation of the kernel)
+    ("biring8_three_piece_rows", lambda: T.grid([8], True), 2500, T.ALL_GATHER, MiB),
+    ("mesh3x3_hetero_five_piece_rows", lambda: T.grid([3, 3], False, [300_000, 700_000], [5_000, 20_000]), 4400,
+     T.ALL_GATHER, 64 << 10),
+    ("torus2x2x3_parallel_links_six_piece_rows_rs", lambda: T.grid([2, 2, 3], True), 3800, T.REDUCE_SCATTER, MiB),
+    ("uniring5_eight_piece_rows", lambda: T.ring(5), 13000, T.ALL_GATHER, MiB),
     # larger: two launches per span first, the tail launches take over when 16 destinations are left
     ("mesh9x7_corners_last_ar", lambda: T.mesh2d(9, 7), 40, T.ALL_REDUCE, MiB),
     ("mesh3d_5x4x3_hetero_ag", lambda: T.grid([5, 4, 3], False, [300_000, 500_000, 900_000], [5_000, 10_000, 20_000]), 30,
