@@ -334,6 +334,15 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
 
   PassGraph g;
   build_pass_graph(N, L, psrc, pdst, order_cost, stream, g);
+  // An NPU without incoming links (in this pass's orientation) never receives anything.  If it
+  // misses a chunk, the sweep ends with postconditions left and nothing in flight: the topology
+  // is not strongly connected (Algorithm 2 would expand the TEN for ever).  The per-span kernels
+  // look for missing chunks through a destination's idle incoming links, which such an NPU does
+  // not have, so the case is settled here, for every launch mode alike.
+  for (uint32_t d = 0; d < N; ++d) {
+    const bool misses_chunks = root == tacos::kNoRoot ? N > 1 : d != root;
+    if (misses_chunks && g.h_in_ptr[d + 1] == g.h_in_ptr[d]) return TACOS_E_UNREACHABLE;
+  }
   // Small topologies: one workgroup sweeps many spans with the link state in LDS.  Chosen
   // automatically when the shape fits (launch_mode 0), forced by launch_mode 2.
   bool small = false;

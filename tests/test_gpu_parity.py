@@ -135,6 +135,63 @@ def test_unreachable_is_an_error(stream):
     assert e.value.code == binding.TACOS_E_UNREACHABLE
 
 
+NOT_STRONGLY_CONNECTED = [
+    ("never_receives", lambda: T.from_edge_list(3, [(0, 1, 500_000, 20_000), (1, 0, 500_000, 20_000), (2, 0, 500_000, 20_000)])),
+    ("never_sends", lambda: T.from_edge_list(3, [(0, 1, 1000, 10), (1, 0, 1000, 10), (0, 2, 1000, 10)])),
+    ("two_islands", lambda: T.from_edge_list(4, [(0, 1, 1000, 10), (1, 0, 1000, 10), (2, 3, 1000, 10), (3, 2, 1000, 10)])),
+    ("path", lambda: T.from_edge_list(3, [(0, 1, 1, 0), (1, 2, 1, 0)])),
+]
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("name,mk", NOT_STRONGLY_CONNECTED, ids=[c[0] for c in NOT_STRONGLY_CONNECTED])
+def test_not_strongly_connected_is_an_error_in_every_launch_mode(name, mk, mode, stream):
+    """Postconditions left and nothing in flight (Algorithm 2 would expand the TEN for ever): an
+    error from the oracle and from every launch mode, for every collective and both matching
+    orders, also when the NPU that cannot be served has no incoming link at all."""
+    topo = mk()
+    for coll in (T.ALL_GATHER, T.REDUCE_SCATTER, T.ALL_REDUCE):
+        for matching in (0, 1):
+            if mode == 3 and matching == 1:
+                continue  # one launch per span is link-centric only
+            with pytest.raises(oracle.OracleError) as e2:
+                cpu(topo, 2, MiB, coll, 5, matching=matching)
+            assert e2.value.code == oracle.E_UNREACHABLE, (name, coll, matching)
+            with pytest.raises(binding.TacosError) as e:
+                gpu(topo, 2, MiB, coll, 5, stream, launch_mode=mode, matching=matching)
+            assert e.value.code == binding.TACOS_E_UNREACHABLE, (name, coll, matching)
+
+
+def test_large_topology_with_an_npu_nothing_reaches_is_an_error(stream):
+    """The same on a topology of the size the per-span launches take automatically: a 70 x 70
+    mesh plus one NPU that sends into it and never receives."""
+    m = T.mesh2d(70, 70)
+    src = np.repeat(np.arange(m.n_npus), np.diff(m.row_ptr))
+    edges = [(int(a), int(b), 500_000, 10_000) for a, b in zip(src, m.col_idx)] + [(m.n_npus, 0, 500_000, 10_000)]
+    topo = T.from_edge_list(m.n_npus + 1, edges)
+    for coll in (T.ALL_GATHER, T.REDUCE_SCATTER):
+        with pytest.raises(binding.TacosError) as e:
+            gpu(topo, 1, MiB, coll, 0, stream)
+        assert e.value.code == binding.TACOS_E_UNREACHABLE
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 4])
+def test_broadcast_root_needs_no_incoming_link(mode, stream):
+    """A root that nothing reaches is fine for a Broadcast (it holds every chunk) and for the
+    Reduce towards it in the reversed orientation only if it can be reached there: record by
+    record against the oracle, and the error where the oracle gives one."""
+    topo = T.from_edge_list(3, [(0, 1, 500_000, 20_000), (1, 0, 500_000, 20_000), (2, 0, 300_000, 10_000)])
+    ref = cpu(topo, 9, MiB, T.BROADCAST, 3, root=2)
+    with gpu(topo, 9, MiB, T.BROADCAST, 3, stream, root=2, launch_mode=mode) as r:
+        assert_same(r, ref, "broadcast from an NPU without incoming links")
+    with pytest.raises(oracle.OracleError) as e2:
+        cpu(topo, 9, MiB, T.BROADCAST, 3, root=0)
+    assert e2.value.code == oracle.E_UNREACHABLE
+    with pytest.raises(binding.TacosError) as e:
+        gpu(topo, 9, MiB, T.BROADCAST, 3, stream, root=0, launch_mode=mode)
+    assert e.value.code == binding.TACOS_E_UNREACHABLE
+
+
 def test_time_overflow_is_an_error(stream):
     # two hops of cost 2^63 each: the second transfer would end beyond 2^64
     big = (1 << 63)
