@@ -2,7 +2,8 @@
 out-regular heterogeneous graphs, rings, meshes, tori, unwound switches, complete graphs;
 1..70 chunks per NPU; all five collectives; both matching orders; both link orders; every
 launch mode that applies), each compared with the CPU oracle record by record.  Stops at the
-first difference."""
+first difference.  A second sweep draws 300 arbitrary small digraphs, most of them not strongly
+connected: the oracle's error code or its schedule, in every launch mode."""
 import numpy as np
 import pytest
 
@@ -82,3 +83,62 @@ def test_random_workloads_bit_exact():
             assert np.array_equal(t, ref.event_times) and np.array_equal(m, ref.event_matches), what
         modes_seen.add(mode)
     assert modes_seen == {0, 1, 2, 3, 4}
+
+
+N_ODD_CASES = 300
+
+
+def test_random_odd_inputs_agree_with_the_oracle():
+    """Arbitrary small random digraphs from a fixed seed: often not strongly connected, with
+    parallel links and NPUs that nothing reaches or that reach nothing; all five collectives,
+    both matching orders, both link orders, every launch mode that applies.  The library gives
+    the oracle's error code (postconditions left and nothing in flight) or, where the collective
+    can be completed (a Broadcast needs its root to reach everyone, no more), the oracle's
+    schedule record by record."""
+    import torch
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    rng = np.random.default_rng(405301)
+    n_feasible = n_errors = 0
+    for case in range(N_ODD_CASES):
+        n = int(rng.integers(2, 12))
+        hetero = bool(rng.integers(0, 2))
+        edges = []
+        for _ in range(int(rng.integers(1, 3 * n))):
+            a, b = int(rng.integers(0, n)), int(rng.integers(0, n))
+            if a == b:
+                continue
+            cost = (int(rng.integers(1, 2_000_000)), int(rng.choice([5_000, 10_000, 20_000]))) if hetero else (500_000, 10_000)
+            edges.append((a, b) + cost)
+        if rng.integers(0, 2):  # a ring with a few links missing: many of these can be completed
+            edges += [(i, (i + 1) % n, 500_000, 10_000) for i in range(n) if rng.integers(0, 12) != 0]
+        if not edges:
+            continue
+        topo = T.from_edge_list(n, edges)
+        cpn, coll, root = int(rng.integers(1, 40)), int(rng.integers(0, 5)), int(rng.integers(0, n))
+        seed, cb = int(rng.integers(0, 1 << 62)), int(rng.integers(1, 1 << 22))
+        kw = dict(matching=int(rng.integers(0, 2)), link_order=int(rng.integers(0, 2)), root=root)
+        equal_costs = len(set(zip(topo.alpha_ps.tolist(), topo.beta_fs_per_B.tolist()))) == 1
+        try:
+            ref, ref_code = oracle.synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B,
+                                              cpn, cb, coll, seed, **kw), 0
+        except oracle.OracleError as e:
+            ref, ref_code = None, e.code
+        for mode in (0, 1, 2, 3, 4):
+            if mode == 3 and (not equal_costs or kw["matching"] == 1):
+                continue
+            what = f"case {case}: n={n} edges={edges} cpn={cpn} coll={coll} seed={seed} chunk_bytes={cb} {kw} launch_mode={mode}"
+            try:
+                r = binding.tacos_synthesize(topo.n_npus, topo.row_ptr, topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B,
+                                             cpn, cb, coll, seed, stream=stream, launch_mode=mode, **kw)
+            except binding.TacosError as e:
+                assert e.code == ref_code, what
+                continue
+            with r:
+                assert ref_code == 0, what
+                assert r.collective_time_ps == ref.collective_time_ps and r.num_events == ref.n_events, what
+                assert r.num_xfers == ref.n_xfers and r.digest == ref.digest, what
+                assert np.array_equal(r.read(), ref.xfers), what
+        n_feasible += ref_code == 0
+        n_errors += ref_code != 0
+    assert n_feasible >= 50 and n_errors >= 50  # the sweep exercises both outcomes
