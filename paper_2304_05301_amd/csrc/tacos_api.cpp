@@ -387,7 +387,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
     h_done.assign(N, 0);
   }
   DevBuf d_next_slots;
-  if (!small && !uniform) {
+  if (!small) {  // (the homogeneous-TEN form needs them once it hands over to the link-state form)
     d_next_slots.alloc((size_t)2 * tacos::kNextSlots * 8);
     p.next_slots = d_next_slots.as<unsigned long long>();
     p.next_mask = N <= 8192u ? tacos::kNextSlots - 1u : 0u;  // short launches spread over the words
@@ -484,15 +484,25 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
     // Link-centric passes with dense rows: once at most kTailSlots destinations are left in the
     // processing order, one single-workgroup launch sweeps many spans (tail_sweep_kernel), up
     // to the end of the row segment.  launch_mode 4 keeps two launches for every span.
-    const bool tail_ok = launch_mode != 4 && !uniform && !compact_spans && match_mode == 0 && NP <= 8 && max_events == 0 &&
+    const bool tail_ok = launch_mode != 4 && !compact_spans && match_mode == 0 && NP <= 8 && max_events == 0 &&
                          p.max_deg >= 1u && p.max_deg <= 64u;
+    // The homogeneous-TEN form (one launch per span) hands over to the link-state form for that
+    // last stretch (automatic mode only; launch_mode 3 keeps one launch per span to the end).
+    bool uniform_now = uniform;
     constexpr uint32_t kTailBatch = 1024;
     uint32_t batch = 8;
     for (;;) {
       size_t n_timed = 0;
       uint64_t tail_spans = 0;  // spans of this batch swept by a tail launch (then the whole batch)
       if (time_kernels) pool.ensure(2 * (size_t)batch);
-      if (tail_ok && p.n_slots <= tacos::kTailSlots) {
+      if (uniform_now && launch_mode == 0 && tail_ok && p.n_slots <= tacos::kTailSlots && e >= 1) {
+        // state before the arrivals of span e: the table span e - 1 read, the chunks it matched in flight
+        p.held = u.held[(e - 1) & 1u];
+        HIP_TRY(hipMemsetAsync(p.next_slots, 0xFF, (size_t)2 * tacos::kNextSlots * 8, stream));  // kInf
+        tacos::launch_uniform_handover(p, u, (uint32_t)e, stream);
+        uniform_now = false;
+      }
+      if (!uniform_now && tail_ok && p.n_slots <= tacos::kTailSlots) {
         if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
         uint32_t *row = nullptr;
         unsigned long long *tslot = nullptr;
@@ -509,7 +519,7 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
         uint32_t *row = nullptr;
         unsigned long long *tslot = nullptr;
         row_slot(e, &row, &tslot);
-        if (uniform) {
+        if (uniform_now) {
           uint32_t *row_next = nullptr;
           unsigned long long *tslot_next = nullptr;
           if (reversed) row_slot(e + 1, &row_next, &tslot_next);  // rows are keyed by arrival

@@ -118,6 +118,12 @@ void launch_uniform_init(const PassDev &p, const UniformDev &u, uint32_t mode, h
 // a3-a8 of span `event` in one launch.  row: schedule row of the span (forward pass), row_next:
 // schedule row of span event + 1 (reversed pass: rows are keyed by arrival); the other is null.
 // The pass has ended when the launch of span e finds that span e - 1 needed nothing.
+// The state launch_arrive / launch_tail_sweep start span `event` (>= 1) from, out of the state the
+// homogeneous-TEN form has after span event - 1: the chunks matched there are in flight until
+// event * cost (carry, free_at, the next-event words, which the caller has set to kInf), the time
+// and need flag of span event - 1 go to the places arrive_kernel reads them from.  The held table
+// to go on with is u.held[(event - 1) & 1].
+void launch_uniform_handover(const PassDev &p, const UniformDev &u, uint32_t event, hipStream_t s);
 void launch_match_uniform(const PassDev &p, const UniformDev &u, uint32_t event, uint32_t *row, uint32_t *row_next,
                           unsigned long long *event_time_slot, uint32_t mode, hipStream_t s);
 

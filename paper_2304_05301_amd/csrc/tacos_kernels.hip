@@ -1298,11 +1298,43 @@ void match_uniform_kernel(PassDev p, UniformDev u, u32 event, u32 *__restrict__ 
   uint4 *my_need = need_lds + (threadIdx.x >> 6) * NP * 64;
   const bool any = match_destination_uniform<NP>(p, u, d, jb, je, event, sched_row, sched_row_next, lane, my_need);
   if (any && lane == 0) ctl->match_flag[event % 3u] = 1u;
-  // a6, first half, for the NEXT span: this launch's wavefronts share out the links, 64 each
+  // a6, first half, for the NEXT span.  All destinations in the launch: its wavefronts share out
+  // the links, 64 each, so that every lane of the few wavefronts that do it is busy.  Once the
+  // host has dropped complete destinations, only the links into the remaining ones can be
+  // matched again: every wavefront draws for its own destination's in-list (sharing out ALL
+  // links among a handful of wavefronts took tens of microseconds per span at the end of a pass
+  // on a mesh).
   if (u.rnd[0]) {
     u32 *rnd_next = u.rnd[(event + 1u) & 1u];
-    for (u32 q = slot * 64u + (u32)lane; q < p.L; q += p.n_slots * 64u)
-      rnd_next[q] = philox4x32_10_word0(p.in_rec[q].x, event + 1u, p.phase, 0u, p.seed_lo, p.seed_hi);
+    if (p.n_slots == p.N) {
+      for (u32 q = slot * 64u + (u32)lane; q < p.L; q += p.n_slots * 64u)
+        rnd_next[q] = philox4x32_10_word0(p.in_rec[q].x, event + 1u, p.phase, 0u, p.seed_lo, p.seed_hi);
+    } else {
+      for (u32 q = jb + (u32)lane; q < je; q += 64u)
+        rnd_next[q] = philox4x32_10_word0(p.in_rec[q].x, event + 1u, p.phase, 0u, p.seed_lo, p.seed_hi);
+    }
+  }
+}
+
+// From one launch per span to the launches with link state (see launch_uniform_handover).
+__global__ __launch_bounds__(256) void uniform_handover_kernel(PassDev p, UniformDev u, u32 event)
+{
+  const u32 j = blockIdx.x * 256u + threadIdx.x;
+  Ctl *ctl = p.ctl;
+  const u64 t = (u64)event * u.cost;
+  if (j < p.L) {
+    const u32 c = u.prev[(event - 1u) & 1u][j];
+    p.carry[j] = c;
+    p.free_at[j] = c != kNone ? t : 0ull;
+    if (c != kNone) {  // few links: the form changes when a handful of destinations are left
+      u64 *nt = &p.next_slots[(event & 1u) * kNextSlots];
+      if (__hip_atomic_load(nt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != t) atomicMin(nt, t);
+    }
+  }
+  if (j == 0) {
+    const u32 nf = ctl->need_flag[(event - 1u) % 3u];
+    ctl->now = t - u.cost;
+    ctl->need_flag[(event - 1u) & 1u] = nf;
   }
 }
 
@@ -2418,6 +2450,11 @@ void launch_uniform_init(const PassDev &p, const UniformDev &u, uint32_t mode, h
 {
   (void)mode;
   hipLaunchKernelGGL(uniform_init_kernel, dim3((p.L + 255) / 256 + (p.L == 0)), dim3(256), 0, s, p, u);
+}
+
+void launch_uniform_handover(const PassDev &p, const UniformDev &u, u32 event, hipStream_t s)
+{
+  hipLaunchKernelGGL(uniform_handover_kernel, dim3((p.L + 255) / 256 + (p.L == 0)), dim3(256), 0, s, p, u, event);
 }
 
 void launch_match_uniform(const PassDev &p, const UniformDev &u, u32 event, u32 *row, u32 *row_next,

@@ -484,6 +484,23 @@ def test_lower_cost_link_priority_bit_exact(coll, stream):
     assert cpu(topo, 3, 64 << 10, coll, 17, link_order=1).digest != cpu(topo, 3, 64 << 10, coll, 17).digest
 
 
+@pytest.mark.parametrize("coll", [T.ALL_GATHER, T.REDUCE_SCATTER])
+def test_one_launch_per_span_hands_over_to_the_last_stretch_sweep(coll, stream):
+    """Automatic mode on a homogeneous mesh too large for the single-workgroup kernel: one launch
+    per span while many destinations are left, then (16 left: the corners and their neighbours)
+    the link state is rebuilt from the chunks matched in the last span and one workgroup sweeps
+    the rest.  Record by record against the oracle; launch_mode 3 (one launch per span to the
+    end) and 4 (two launches per span to the end) give the same digest."""
+    topo = T.mesh2d(58, 58)
+    ref = cpu(topo, 1, MiB, coll, 12, n_threads=min(16, oracle.max_threads()))
+    with gpu(topo, 1, MiB, coll, 12, stream) as r:
+        assert_same(r, ref, "mesh58x58")
+        for mode in (3, 4):
+            with gpu(topo, 1, MiB, coll, 12, stream, launch_mode=mode) as q:
+                assert q.digest == r.digest and q.collective_time_ps == r.collective_time_ps
+                assert q.num_events == r.num_events
+
+
 @pytest.mark.parametrize("name,mk", [("mesh64x64", lambda: T.mesh2d(64, 64, 500_000, 20_000)),
                                      ("mesh3d_12", lambda: T.grid([12, 12, 12], False, 500_000, 20_000))])
 def test_scalability_shapes_all_reduce_full(name, mk, stream):
