@@ -148,11 +148,15 @@ typedef struct {
                              matched in span e arrives exactly at span e + 1, so arrivals,
                              matching and the next event need no separate steps.  Needs equal
                              link costs (<= 2^31 ps), <= 65,536 chunks, link-centric matching,
-                             max_events == 0, else TACOS_E_INVAL.  Automatic: 2 if it fits, else
-                             3 if it applies and its two held tables take at most 256 MiB
-                             (about 32,768 NPUs with one chunk each; the last stretch of a
-                             pass, at most 16 destinations left, as in 1), else 1.  Same
-                             results in all modes.                                           */
+                             max_events == 0, else TACOS_E_INVAL.  Automatic: 2 if it fits and a
+                             span has little to decide or its destinations can be matched
+                             one per lane (links that nearly all cost differently; at most
+                             64 links; at most 1,024 chunks with links x row words <= 8,192;
+                             the other matching orders always), else 3 if it applies and
+                             its two held tables take at most 256 MiB (about 32,768 NPUs
+                             with one chunk each; the last stretch of a pass, at most 16
+                             destinations left, as in 1), else 1.  Same results in all
+                             modes.                                                          */
   uint32_t link_order;    /* order in which a destination's idle incoming links are tried:
                              0 = ascending link id; 1 = cheapest link first, ties by link id
                              (paper, "Prioritizing Lower-cost Links").  The random draw of a

@@ -352,6 +352,18 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
       g_last_error = "launch_mode 2: links, NPUs and need rows do not fit the LDS of one workgroup";
       return TACOS_E_INVAL;
     }
+    // Automatic: one workgroup is the fastest form while a span has little to decide (links that
+    // nearly all cost differently: about one transfer per span; at most 64 links) or while its
+    // destinations are matched one per lane (links x row words up to 8,192).  Where most links are
+    // matched in most spans and a wavefront has to take the destinations one after the other, a
+    // span costs it 0.75 us per 16 links: with equal link costs one launch per span is faster
+    // (8 x 8 x 8 torus with 3 chunks per NPU: 12 against 176 us per span), with a few cost classes
+    // two launches per span (4 x 4 x 8 heterogeneous torus with 16 chunks per NPU: 10 against 27).
+    if (small && launch_mode == 0 && match_mode == 0) {
+      const bool by_lane = tacos::small_sweep_by_lane(N, L, NP, C, match_mode) && (uint64_t)L * ((C + 63u) / 64u) <= 8192u;
+      const bool one_launch_per_span_applies = uniform_cost != 0 && uniform_cost <= (1ull << 31) && max_events == 0;
+      if (!many_costs && !by_lane && L > 64 && (uniform_cost == 0 || one_launch_per_span_applies)) small = false;
+    }
   }
   // Homogeneous TEN (all links cost the same): one launch per span on a double-buffered held
   // table; link-centric matching, rows that fit the registers, complete runs only.  Span e is
@@ -466,7 +478,8 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
         HIP_TRY(hipEventRecord(ev0, stream));
       }
       HIP_TRY(tacos::launch_small_sweep(p, g.out_ptr.as<uint32_t>(), g.out_dst.as<uint32_t>(), (uint32_t)e,
-                                        (uint32_t)n, stop_event, pass.recs.as<uint2>(), row, tslot, match_mode, stream));
+                                        (uint32_t)n, stop_event, pass.recs.as<uint2>(), row, tslot, match_mode,
+                                        many_costs, stream));
       if (time_kernels) HIP_TRY(hipEventRecord(ev1, stream));
       HIP_TRY(hipMemcpyAsync(host_ctl.p, p.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, stream));
       HIP_TRY(hipStreamSynchronize(stream));

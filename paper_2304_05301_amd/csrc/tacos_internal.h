@@ -174,11 +174,17 @@ uint32_t compact_schedule_max_links();
 // (the whole pass's (link, chunk) pairs, appended in span order; within a span in no
 // particular order) and, per span from first_event on, span_first (index of the span's first
 // record) and event_times.  A forward pass records matches, a reversed pass arrivals.
-// out_ptr/out_dst: out-neighbour lists of the pass orientation.
+// out_ptr/out_dst: out-neighbour lists of the pass orientation.  sparse: about one transfer per
+// span is expected (links that nearly all cost differently): the destinations of a span are then
+// matched one per wavefront also where the shape would allow one per lane.
 hipError_t launch_small_sweep(const PassDev &p, const uint32_t *out_ptr, const uint32_t *out_dst,
                               uint32_t first_event, uint32_t n_events, uint32_t stop_event,
                               uint2 *recs, uint32_t *span_first, unsigned long long *event_times, uint32_t mode,
-                              hipStream_t s);
+                              bool sparse, hipStream_t s);
+// Whether that kernel would match this shape's destinations one per LANE (link-centric matching,
+// at most 1,024 chunks, held table and in-list records in LDS): then a span in which every
+// link is matched costs it little more than a span with one transfer.
+bool small_sweep_by_lane(uint32_t N, uint32_t L, uint32_t NP, uint32_t C, uint32_t mode);
 // The same sweep for n_jobs independent passes of one shape at once, one workgroup each
 // (jobs: device array); collective times only, no schedule rows.  p0: any of the jobs'
 // PassDev (shape).  Every unfinished job advances by n_events spans from first_event.

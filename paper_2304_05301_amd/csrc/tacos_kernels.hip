@@ -2537,15 +2537,17 @@ static hipError_t launch_small_variant(const PassDev &p, const u32 *out_ptr, con
 template <int NP, int MODE>
 static hipError_t launch_small_np(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
                                   u32 n_events, u32 stop_event, uint2 *recs, u32 *span_first, u64 *event_times,
-                                  hipStream_t s)
+                                  bool sparse, hipStream_t s)
 {
   u32 dst_in_lds = 0, held_lanes = 0, rec_in_lds = 0;
   const size_t lds = small_launch_lds(p, &dst_in_lds, &held_lanes, &rec_in_lds);
 #define TACOS_VARIANT(H_, T_)                                                                                         \
   return launch_small_variant<NP, MODE, H_, T_>(p, out_ptr, out_dst, first_event, n_events, stop_event, recs, span_first, \
                                                 event_times, lds, dst_in_lds, held_lanes, rec_in_lds, s)
+  // sparse (about one transfer per span): a wavefront per destination decides the one or two
+  // destinations of a span in a fraction of the time a single lane takes for each
   if constexpr (NP == 1 && MODE == 0) {
-    switch (tiny_words<NP, MODE>(held_lanes, rec_in_lds)) {
+    switch (sparse ? 0 : tiny_words<NP, MODE>(held_lanes, rec_in_lds)) {
       case 2: TACOS_VARIANT(true, 2);
       case 4: TACOS_VARIANT(true, 4);
       case 8: TACOS_VARIANT(true, 8);
@@ -2594,10 +2596,10 @@ static hipError_t launch_batch_np(const SmallJob *jobs, u32 n_jobs, const PassDe
 
 hipError_t launch_small_sweep(const PassDev &p, const u32 *out_ptr, const u32 *out_dst, u32 first_event,
                               u32 n_events, u32 stop_event, uint2 *recs, u32 *span_first, u64 *event_times, u32 mode,
-                              hipStream_t s)
+                              bool sparse, hipStream_t s)
 {
 #define TACOS_SMALL(NP_, M_) \
-  return launch_small_np<NP_, M_>(p, out_ptr, out_dst, first_event, n_events, stop_event, recs, span_first, event_times, s)
+  return launch_small_np<NP_, M_>(p, out_ptr, out_dst, first_event, n_events, stop_event, recs, span_first, event_times, sparse, s)
   if (mode > 2) return hipErrorInvalidValue;
   switch (p.NP * 4 + mode) {
     case 4: TACOS_SMALL(1, 0);
@@ -2626,6 +2628,16 @@ hipError_t launch_small_sweep_batch(const SmallJob *jobs, u32 n_jobs, const Pass
     default: return hipErrorInvalidValue;
   }
 #undef TACOS_BATCH
+}
+
+bool small_sweep_by_lane(u32 N, u32 L, u32 NP, u32 C, u32 mode)
+{
+  if (NP != 1 || mode != 0) return false;
+  PassDev p{};
+  p.N = N; p.L = L; p.NP = NP; p.C = C;
+  u32 dst_in_lds = 0, held_lanes = 0, rec_in_lds = 0;
+  (void)small_launch_lds(p, &dst_in_lds, &held_lanes, &rec_in_lds);
+  return tiny_words<1, 0>(held_lanes, rec_in_lds) != 0;
 }
 
 size_t small_sweep_lds_bytes(u32 N, u32 L, u32 NP) { return NP <= 2 ? small_lds_bytes(N, L, NP) : (size_t)-1; }
