@@ -151,8 +151,8 @@ typedef struct {
                              max_events == 0, else TACOS_E_INVAL.  Automatic: 2 if it fits and a
                              span has little to decide or its destinations can be matched
                              one per lane (links that nearly all cost differently; at most
-                             64 links; at most 1,024 chunks with links x row words <= 8,192;
-                             the other matching orders always), else 3 if it applies and
+                             64 links; link-centric matching of at most 1,024 chunks with
+                             links x row words <= 8,192), else 3 if it applies and
                              its two held tables take at most 256 MiB (about 32,768 NPUs
                              with one chunk each; the last stretch of a pass, at most 16
                              destinations left, as in 1), else 1.  Same results in all

@@ -359,10 +359,11 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
     // span costs it 0.75 us per 16 links: with equal link costs one launch per span is faster
     // (8 x 8 x 8 torus with 3 chunks per NPU: 12 against 176 us per span), with a few cost classes
     // two launches per span (4 x 4 x 8 heterogeneous torus with 16 chunks per NPU: 10 against 27).
-    if (small && launch_mode == 0 && match_mode == 0) {
+    // (The postcondition-centric orders have no lane-per-destination form: 16 x 16 mesh with 8
+    // chunks per NPU 57 against 12 us per span with two launches.)
+    if (small && launch_mode == 0) {
       const bool by_lane = tacos::small_sweep_by_lane(N, L, NP, C, match_mode) && (uint64_t)L * ((C + 63u) / 64u) <= 8192u;
-      const bool one_launch_per_span_applies = uniform_cost != 0 && uniform_cost <= (1ull << 31) && max_events == 0;
-      if (!many_costs && !by_lane && L > 64 && (uniform_cost == 0 || one_launch_per_span_applies)) small = false;
+      if (!many_costs && !by_lane && L > 64) small = false;
     }
   }
   // Homogeneous TEN (all links cost the same): one launch per span on a double-buffered held
