@@ -371,37 +371,40 @@ __global__ __launch_bounds__(256) void arrive_slots_kernel(PassDev p, u32 event,
 // A lane's share of a bitset row (NDW dwords) held in native vector registers, so that
 // the compiler can index it with a wave-uniform register index (s_set_gpr_idx) instead
 // of a chain of selects or branches.  Indexable vectors come in 4/8/16/32 dwords; a row
-// of more than 16 dwords that is not 32 is split into a 16-dword part and a remainder
-// so that no registers are wasted on padding.
+// of 17..31 dwords is split into a 16-dword part and a remainder, one of 33..64 dwords into a
+// 32-dword part and a remainder, so that few registers are wasted on padding.
 template <int N> struct VecOf {
   typedef u32 type __attribute__((ext_vector_type(N <= 4 ? 4 : N <= 8 ? 8 : N <= 16 ? 16 : 32)));
 };
 // (Two separate vector variables rather than one struct: a struct of two vectors that
 // is indexed dynamically ends up in scratch memory.)
 template <int NDW> struct RowRegs {
-  static constexpr bool kSplit = NDW > 16 && NDW < 32;
-  static constexpr int kA = kSplit ? 16 : NDW;
-  static constexpr int kB = kSplit ? NDW - 16 : 4;  // B is unused unless split
+  static_assert(NDW <= 64, "a lane's share of a row is at most 64 dwords");
+  static constexpr bool kSplit = NDW > 16 && NDW != 32;
+  static constexpr int kCut = NDW > 32 ? 32 : 16;  // dwords in part A of a split row
+  static constexpr int kA = kSplit ? kCut : NDW;
+  static constexpr int kB = kSplit ? NDW - kCut : 4;  // B is unused unless split
   typedef typename VecOf<kA>::type A;
   typedef typename VecOf<kB>::type B;
+  static constexpr u32 kMaskA = sizeof(A) / 4 - 1;
   static constexpr u32 kMaskB = sizeof(B) / 4 - 1;
   template <int I> static __device__ __forceinline__ u32 get(const A &a, const B &b)
   {
-    if constexpr (!kSplit || I < 16) return a[I];
-    else return b[I - 16];
+    if constexpr (!kSplit || I < kCut) return a[I];
+    else return b[I - kCut];
   }
   template <int I> static __device__ __forceinline__ void set(A &a, B &b, u32 x)
   {
-    if constexpr (!kSplit || I < 16) a[I] = x;
-    else b[I - 16] = x;
+    if constexpr (!kSplit || I < kCut) a[I] = x;
+    else b[I - kCut] = x;
   }
   // i is wave-uniform: both parts are indexed and the scalar condition picks one
   static __device__ __forceinline__ u32 at(const A &a, const B &b, u32 i)
   {
     if constexpr (!kSplit) return a[i];
     else {
-      const u32 x = a[i & 15u], y = b[(i - 16u) & kMaskB];
-      return i < 16u ? x : y;
+      const u32 x = a[i & kMaskA], y = b[(i - (u32)kCut) & kMaskB];
+      return i < (u32)kCut ? x : y;
     }
   }
 };
@@ -1378,6 +1381,8 @@ __global__ __launch_bounds__(256) void uniform_handover_kernel(PassDev p, Unifor
 // one 16-byte share and selects the bit.  The need row (NP KiB) is in LDS as before.
 // np <= kMaxStreamedPieces pieces; same results as match_destination.
 constexpr u32 kMaxStreamedPieces = 32;
+// (Rows of up to kMaxRegisterPieces pieces are matched with whole rows in registers: match_destination.)
+constexpr u32 kMaxRegisterPieces = 12;
 
 __device__ __forceinline__ u64 match_destination_streamed(const PassDev &p, u32 d, u32 jb, u32 je, u32 event,
                                                           u64 t, u32 *__restrict__ sched_row, int lane,
@@ -2416,7 +2421,19 @@ template <int MODE, int DEG> static void launch_match_mode(const PassDev &p, u32
     case 6: TACOS_MATCH(6); break;
     case 7: TACOS_MATCH(7); break;
     case 8: TACOS_MATCH(8); break;
-    default: break;  // rejected by the host before any launch
+    default:
+      // rows of 9..kMaxRegisterPieces pieces (up to 98,304 chunks), link-centric only: still whole
+      // rows in registers, at three wavefronts per SIMD
+      if constexpr (MODE == 0 && DEG == 0) {
+        switch (p.NP) {
+          case 9: TACOS_MATCH(9); break;
+          case 10: TACOS_MATCH(10); break;
+          case 11: TACOS_MATCH(11); break;
+          case 12: TACOS_MATCH(12); break;
+          default: break;  // rejected by the host before any launch
+        }
+      }
+      break;
   }
 #undef TACOS_MATCH
 }
@@ -2432,7 +2449,7 @@ template <int MODE> static void launch_match_pairs(const PassDev &p, u32 event, 
 
 void launch_match(const PassDev &p, u32 event, u32 *sched_row, u32 mode, hipStream_t s)
 {
-  if (p.NP > 8) {  // streamed rows (link-centric only; the host rejects the rest)
+  if (p.NP > kMaxRegisterPieces) {  // streamed rows (link-centric only; the host rejects the rest)
     const u32 n_wg = (p.n_slots + 3u) / 4u;
     const dim3 grid(8u * ((n_wg + 7u) / 8u + (n_wg == 0u)), 1, 1), block(256);
     const size_t lds = (size_t)4 * p.NP * 1024;
