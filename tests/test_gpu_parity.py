@@ -493,8 +493,9 @@ def test_one_launch_per_span_hands_over_to_the_last_stretch_sweep(coll, stream):
     end) and 4 (two launches per span to the end) give the same digest."""
     topo = T.mesh2d(58, 58)
     ref = cpu(topo, 1, MiB, coll, 12, n_threads=min(16, oracle.max_threads()))
-    with gpu(topo, 1, MiB, coll, 12, stream) as r:
+    with gpu(topo, 1, MiB, coll, 12, stream, time_kernels=True) as r:
         assert_same(r, ref, "mesh58x58")
+        assert r.kernel_launches == r.num_events  # a launch that sweeps several spans counts once per span
         for mode in (3, 4):
             with gpu(topo, 1, MiB, coll, 12, stream, launch_mode=mode) as q:
                 assert q.digest == r.digest and q.collective_time_ps == r.collective_time_ps
