@@ -155,8 +155,9 @@ typedef struct {
                              links x row words <= 8,192), else 3 if it applies and
                              its two held tables take at most 256 MiB (about 32,768 NPUs
                              with one chunk each; the last stretch of a pass, at most 16
-                             destinations left, as in 1), else 1.  Same results in all
-                             modes.                                                          */
+                             destinations left, as in 1), else 1 (with equal link costs one
+                             launch per span once at most 2,048 destinations are left).
+                             Same results in all modes.                                      */
   uint32_t link_order;    /* order in which a destination's idle incoming links are tried:
                              0 = ascending link id; 1 = cheapest link first, ties by link id
                              (paper, "Prioritizing Lower-cost Links").  The random draw of a

@@ -503,12 +503,41 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
     // The homogeneous-TEN form (one launch per span) hands over to the link-state form for that
     // last stretch (automatic mode only; launch_mode 3 keeps one launch per span to the end).
     bool uniform_now = uniform;
+    // ... and a pass that started with two launches per span because of its size goes over to
+    // one launch per span once at most kLateUniformSlots destinations are left (automatic mode).
+    constexpr uint32_t kLateUniformSlots = 2048;
+    bool late_uniform_ok = launch_mode == 0 && !uniform && !compact_spans && uniform_cost != 0 &&
+                           uniform_cost <= (1ull << 31) && NP <= 8 && match_mode == 0 && max_events == 0;
+    DevBuf d_held_b, d_rnd_b;
     constexpr uint32_t kTailBatch = 1024;
     uint32_t batch = 8;
     for (;;) {
       size_t n_timed = 0;
       uint64_t tail_spans = 0;  // spans of this batch swept by a tail launch (then the whole batch)
       if (time_kernels) pool.ensure(2 * (size_t)batch);
+      if (!uniform_now && late_uniform_ok && p.n_slots <= kLateUniformSlots && p.n_slots > tacos::kTailSlots && e >= 1) {
+        // Equal link costs on a topology too large for two held tables beside each other in the
+        // Infinity Cache: with few destinations left that no longer matters, and one launch per
+        // span is half the launches.  The table so far becomes the one span e reads (it receives
+        // the arrivals of span e), a copy of it the lagging one.
+        d_held_b.alloc(held_bytes);
+        d_prev.alloc((size_t)L * 4 * 2);
+        d_rnd_b.alloc((size_t)L * 4 * 2);
+        u.held[e & 1u] = d_held.as<unsigned long long>();
+        u.held[(e + 1) & 1u] = d_held_b.as<unsigned long long>();
+        u.prev[0] = d_prev.as<uint32_t>();
+        u.prev[1] = u.prev[0] + L;
+        u.rnd[0] = d_rnd_b.as<uint32_t>();
+        u.rnd[1] = u.rnd[0] + L;
+        u.cost = uniform_cost;
+        uint32_t *row = nullptr;
+        unsigned long long *tslot = nullptr;
+        row_slot(e, &row, &tslot);
+        tacos::launch_links_to_uniform(p, u, (uint32_t)e, reversed ? row : nullptr, stream);
+        HIP_TRY(hipGetLastError());
+        uniform_now = true;
+        late_uniform_ok = false;  // once
+      }
       if (uniform_now && launch_mode == 0 && tail_ok && p.n_slots <= tacos::kTailSlots && e >= 1) {
         // state before the arrivals of span e: the table span e - 1 read, the chunks it matched in flight
         p.held = u.held[(e - 1) & 1u];

@@ -124,6 +124,13 @@ void launch_uniform_init(const PassDev &p, const UniformDev &u, uint32_t mode, h
 // and need flag of span event - 1 go to the places arrive_kernel reads them from.  The held table
 // to go on with is u.held[(event - 1) & 1].
 void launch_uniform_handover(const PassDev &p, const UniformDev &u, uint32_t event, hipStream_t s);
+// The opposite direction, before the arrivals of span `event` (>= 1) on a topology of equal link
+// costs: u.held[event & 1] is the table the launches with link state worked on (it receives the
+// arrivals of the span), u.held[(event + 1) & 1] becomes a copy of it as it is before; the flags of
+// span event - 1 are set here and all others cleared.  sched_row: the span's
+// schedule row in a reversed pass, else null.
+void launch_links_to_uniform(const PassDev &p, const UniformDev &u, uint32_t event, uint32_t *sched_row,
+                             hipStream_t s);
 void launch_match_uniform(const PassDev &p, const UniformDev &u, uint32_t event, uint32_t *row, uint32_t *row_next,
                           unsigned long long *event_time_slot, uint32_t mode, hipStream_t s);
 

@@ -1349,6 +1349,41 @@ void match_uniform_kernel(PassDev p, UniformDev u, u32 event, u32 *__restrict__ 
   }
 }
 
+// From the launches with link state to one launch per span (see launch_links_to_uniform): the
+// chunks in flight (all matched in span event - 1: equal link costs) become the arrivals of span
+// `event`: into the table that span reads, into the list the lagging table is brought up to date
+// from, and (reversed pass) into the span's schedule row.
+__global__ __launch_bounds__(256) void links_to_uniform_kernel(PassDev p, UniformDev u, u32 event,
+                                                               u32 *__restrict__ sched_row)
+{
+  const u32 j = blockIdx.x * 256u + threadIdx.x;
+  Ctl *ctl = p.ctl;
+  if (j < p.L) {
+    const u32 c = __hip_atomic_load(&p.carry[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const u32 link = p.in_link[j];
+    u.prev[(event + 1u) & 1u][j] = c;
+    u.prev[event & 1u][j] = kNone;
+    u.rnd[event & 1u][j] = philox4x32_10_word0(link, event, p.phase, 0u, p.seed_lo, p.seed_hi);
+    if (c != kNone) {
+      atomicOr(&u.held[event & 1u][(u64)p.pos_dst[j] * p.row_words + phys_word(c >> 6, p.NP)], 1ull << (c & 63u));
+      if (sched_row) sched_row[link] = c;  // rows are pre-filled with kNone
+      ctl->match_flag[(event - 1u) % 3u] = 1u;
+    }
+  }
+}
+
+// the need flag of span event - 1 from where the launches with link state keep it to where one
+// launch per span looks for it; every other flag cleared
+__global__ void links_to_uniform_flags_kernel(Ctl *ctl, u32 event)
+{
+  // (An atomic load, i.e. a vector memory instruction: as a plain load of a uniform address this
+  // becomes a scalar load, which the hardware does not order with the vector stores below; they
+  // overtook it and it returned the cleared flag.)
+  const u32 nf = __hip_atomic_load(&ctl->need_flag[(event - 1u) & 1u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int i = 0; i < 4; ++i) { ctl->need_flag[i] = 0u; ctl->match_flag[i] = 0u; }
+  ctl->need_flag[(event - 1u) % 3u] = nf;
+}
+
 // From one launch per span to the launches with link state (see launch_uniform_handover).
 __global__ __launch_bounds__(256) void uniform_handover_kernel(PassDev p, UniformDev u, u32 event)
 {
@@ -1356,7 +1391,7 @@ __global__ __launch_bounds__(256) void uniform_handover_kernel(PassDev p, Unifor
   Ctl *ctl = p.ctl;
   const u64 t = (u64)event * u.cost;
   if (j < p.L) {
-    const u32 c = u.prev[(event - 1u) & 1u][j];
+    const u32 c = __hip_atomic_load(&u.prev[(event - 1u) & 1u][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     p.carry[j] = c;
     p.free_at[j] = c != kNone ? t : 0ull;
     if (c != kNone) {  // few links: the form changes when a handful of destinations are left
@@ -1365,7 +1400,7 @@ __global__ __launch_bounds__(256) void uniform_handover_kernel(PassDev p, Unifor
     }
   }
   if (j == 0) {
-    const u32 nf = ctl->need_flag[(event - 1u) % 3u];
+    const u32 nf = __hip_atomic_load(&ctl->need_flag[(event - 1u) % 3u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     ctl->now = t - u.cost;
     ctl->need_flag[(event - 1u) & 1u] = nf;
   }
@@ -2497,6 +2532,22 @@ void launch_uniform_init(const PassDev &p, const UniformDev &u, uint32_t mode, h
 {
   (void)mode;
   hipLaunchKernelGGL(uniform_init_kernel, dim3((p.L + 255) / 256 + (p.L == 0)), dim3(256), 0, s, p, u);
+}
+
+// (a kernel rather than a device-to-device hipMemcpyAsync: the launches around it then depend on
+// each other as kernels of one stream always do)
+__global__ __launch_bounds__(256) void copy_table_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, u64 n)
+{
+  for (u64 i = (u64)blockIdx.x * 256u + threadIdx.x; i < n; i += (u64)gridDim.x * 256u) dst[i] = src[i];
+}
+
+void launch_links_to_uniform(const PassDev &p, const UniformDev &u, u32 event, u32 *sched_row, hipStream_t s)
+{
+  const u64 n16 = (u64)p.N * p.row_words / 2u;  // rows are multiples of 1 KiB
+  hipLaunchKernelGGL(copy_table_kernel, dim3(256 * 8), dim3(256), 0, s, reinterpret_cast<uint4 *>(u.held[(event + 1u) & 1u]),
+                     reinterpret_cast<const uint4 *>(u.held[event & 1u]), n16);
+  hipLaunchKernelGGL(links_to_uniform_flags_kernel, dim3(1), dim3(1), 0, s, p.ctl, event);
+  hipLaunchKernelGGL(links_to_uniform_kernel, dim3((p.L + 255) / 256 + (p.L == 0)), dim3(256), 0, s, p, u, event, sched_row);
 }
 
 void launch_uniform_handover(const PassDev &p, const UniformDev &u, u32 event, hipStream_t s)

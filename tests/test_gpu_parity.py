@@ -502,6 +502,25 @@ def test_one_launch_per_span_hands_over_to_the_last_stretch_sweep(coll, stream):
                 assert q.num_events == r.num_events
 
 
+@pytest.mark.parametrize("coll", [T.ALL_GATHER, T.REDUCE_SCATTER])
+def test_large_mesh_changes_launch_form_twice(coll, stream):
+    """Automatic mode on a homogeneous mesh whose two held tables would not fit the Infinity Cache
+    (182 x 182: 2 x 170 MB): two launches per span while most destinations are left, one launch
+    per span from 2,048 destinations on (the link state becomes the arrivals of the next span),
+    one workgroup for the last 16.  Same digest, times and span count as two launches per span
+    to the end (launch_mode 4) and as one launch per span from the start (launch_mode 3); the
+    full-size workloads 6 and 7 take the same route against the oracle's stored results."""
+    topo = T.mesh2d(182, 182)
+    with gpu(topo, 1, MiB, coll, 21, stream) as r:
+        for mode in (4, 3):
+            with gpu(topo, 1, MiB, coll, 21, stream, launch_mode=mode) as q:
+                assert q.digest == r.digest and q.collective_time_ps == r.collective_time_ps
+                assert q.num_events == r.num_events and q.num_xfers == r.num_xfers
+                t0, m0 = r.event_trace(0)
+                t1, m1 = q.event_trace(0)
+                assert np.array_equal(t0, t1) and np.array_equal(m0, m1)
+
+
 @pytest.mark.parametrize("name,mk", [("mesh64x64", lambda: T.mesh2d(64, 64, 500_000, 20_000)),
                                      ("mesh3d_12", lambda: T.grid([12, 12, 12], False, 500_000, 20_000))])
 def test_scalability_shapes_all_reduce_full(name, mk, stream):
