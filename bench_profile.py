@@ -117,16 +117,19 @@ def main():
             spans = json.loads(f.read().strip().splitlines()[-1])["ten_spans"]
     # tail_sweep_kernel: one workgroup sweeping the last stretch of a pass, many spans per launch
     tail = [e - s for s, e, n in trace if "tail_sweep_kernel" in n]
+    # match_uniform_kernel: one launch per span, which a large pass on equal link costs goes over to
+    # once few destinations are left (before the tail launches)
+    late = [e - s for s, e, n in trace if "match_uniform_kernel" in n] if kernel == "match_kernel" else []
     if kernel == "match_kernel":
         if spans is None:
             spans = sum(1 for d in durs if d > 0.3 * max(durs))
-        # (a pass that ends inside a tail launch queues no match_kernel launch past its end)
+        # (a pass that ends inside a tail launch queues no launch of the other kernels past its end)
         work = list(durs) if tail else sorted(durs, reverse=True)[:spans]
     else:
         work = durs
     # launches, a tail launch counted once per span it swept (as tacos_result_kernel_launches does)
     n_units = spans if tail else len(work)
-    mean_us = (sum(work) + sum(tail)) / n_units / 1e3
+    mean_us = (sum(work) + sum(late) + sum(tail)) / n_units / 1e3
     out = [f"rocprofv3 summary: {kernel} on workload {w.name}{' (matching = %d)' % args.matching if args.matching else ''} "
            f"({w.topo.n_npus} NPUs, {w.topo.n_links} links, {w.topo.n_npus * w.chunks_per_npu} chunks of {w.chunk_bytes} B, seed {w.seed})",
            "device: AMD Instinct MI355X (gfx950, 256 CUs), ROCm 7.2.0; automatic launch mode",
@@ -139,9 +142,12 @@ def main():
                        f"{row['Percentage']} | {row['MinNs']} | {row['MaxNs']}")
     out.append("")
     if tail:
-        out.append(f"{kernel}: {len(durs)} launches, all of them did work ({sum(work) / 1e6:.1f} ms); tail_sweep_kernel: "
-                   f"{len(tail)} launches sweeping the other {spans - len(work)} spans ({sum(tail) / 1e6:.1f} ms, "
-                   f"{sum(tail) / max(1, spans - len(work)) / 1e3:.2f} us per span); per span over all {spans}: mean "
+        n_tail = spans - len(work) - len(late)
+        out.append(f"{kernel}: {len(durs)} launches, all of them did work ({sum(work) / 1e6:.1f} ms); match_uniform_kernel "
+                   f"(one launch per span once at most 2,048 destinations are left): {len(late)} launches "
+                   f"({sum(late) / 1e6:.1f} ms, {sum(late) / max(1, len(late)) / 1e3:.2f} us each); tail_sweep_kernel: "
+                   f"{len(tail)} launches sweeping the other {n_tail} spans ({sum(tail) / 1e6:.1f} ms, "
+                   f"{sum(tail) / max(1, n_tail) / 1e3:.2f} us per span); per span over all {spans}: mean "
                    f"{mean_us:.2f} us; {kernel} alone: mean {sum(work) / len(work) / 1e3:.2f} us, "
                    f"median {sorted(work)[len(work) // 2] / 1e3:.2f} us")
     else:
@@ -175,7 +181,8 @@ def main():
         cp_w = wr["WRITE_SIZE"]["__amd_rocclr_copyBuffer"][2]
         fs, ws = 1048576 / cp_f, 1048576 / cp_w
         mk = [k for k in fe["FETCH_SIZE"] if kernel in k][0]
-        tk = [k for k in fe["FETCH_SIZE"] if "tail_sweep_kernel" in k]  # counted with the launches it replaces
+        # counted with the launches they replace
+        tk = [k for k in fe["FETCH_SIZE"] if "tail_sweep_kernel" in k or "match_uniform_kernel" in k]
         total = lambda table: table[mk][1] + sum(table[k][1] for k in tk)
         fb = total(fe["FETCH_SIZE"]) * fs * 1024 / n_units
         wbytes = total(wr["WRITE_SIZE"]) * ws * 1024 / n_units
