@@ -59,6 +59,18 @@ struct DevBuf {
     HIP_TRY(hipMalloc(&p, n ? n : 1));
     bytes = n;
   }
+  // for memory the caller can do without: false (and no pending HIP error) if there is none
+  bool try_alloc(size_t n)
+  {
+    reset();
+    if (hipMalloc(&p, n ? n : 1) != hipSuccess) {
+      (void)hipGetLastError();
+      p = nullptr;
+      return false;
+    }
+    bytes = n;
+    return true;
+  }
   void reset()
   {
     if (p) (void)hipFree(p);
@@ -516,27 +528,27 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
       uint64_t tail_spans = 0;  // spans of this batch swept by a tail launch (then the whole batch)
       if (time_kernels) pool.ensure(2 * (size_t)batch);
       if (!uniform_now && late_uniform_ok && p.n_slots <= kLateUniformSlots && p.n_slots > tacos::kTailSlots && e >= 1) {
+        late_uniform_ok = false;  // once
         // Equal link costs on a topology too large for two held tables beside each other in the
         // Infinity Cache: with few destinations left that no longer matters, and one launch per
         // span is half the launches.  The table so far becomes the one span e reads (it receives
-        // the arrivals of span e), a copy of it the lagging one.
-        d_held_b.alloc(held_bytes);
-        d_prev.alloc((size_t)L * 4 * 2);
-        d_rnd_b.alloc((size_t)L * 4 * 2);
-        u.held[e & 1u] = d_held.as<unsigned long long>();
-        u.held[(e + 1) & 1u] = d_held_b.as<unsigned long long>();
-        u.prev[0] = d_prev.as<uint32_t>();
-        u.prev[1] = u.prev[0] + L;
-        u.rnd[0] = d_rnd_b.as<uint32_t>();
-        u.rnd[1] = u.rnd[0] + L;
-        u.cost = uniform_cost;
-        uint32_t *row = nullptr;
-        unsigned long long *tslot = nullptr;
-        row_slot(e, &row, &tslot);
-        tacos::launch_links_to_uniform(p, u, (uint32_t)e, reversed ? row : nullptr, stream);
-        HIP_TRY(hipGetLastError());
-        uniform_now = true;
-        late_uniform_ok = false;  // once
+        // the arrivals of span e), a copy of it the lagging one.  Without memory for the copy the
+        // pass goes on as it is.
+        if (d_held_b.try_alloc(held_bytes) && d_prev.try_alloc((size_t)L * 4 * 2) && d_rnd_b.try_alloc((size_t)L * 4 * 2)) {
+          u.held[e & 1u] = d_held.as<unsigned long long>();
+          u.held[(e + 1) & 1u] = d_held_b.as<unsigned long long>();
+          u.prev[0] = d_prev.as<uint32_t>();
+          u.prev[1] = u.prev[0] + L;
+          u.rnd[0] = d_rnd_b.as<uint32_t>();
+          u.rnd[1] = u.rnd[0] + L;
+          u.cost = uniform_cost;
+          uint32_t *row = nullptr;
+          unsigned long long *tslot = nullptr;
+          row_slot(e, &row, &tslot);
+          tacos::launch_links_to_uniform(p, u, (uint32_t)e, reversed ? row : nullptr, stream);
+          HIP_TRY(hipGetLastError());
+          uniform_now = true;
+        }
       }
       if (uniform_now && launch_mode == 0 && tail_ok && p.n_slots <= tacos::kTailSlots && e >= 1) {
         // state before the arrivals of span e: the table span e - 1 read, the chunks it matched in flight
@@ -556,8 +568,8 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
         HIP_TRY(tacos::launch_tail_sweep(p, (uint32_t)e, (uint32_t)tail_spans, row, pass.row_stride(), tslot, stream));
         if (time_kernels) { HIP_TRY(hipEventRecord(pool.ev[1], stream)); n_timed = 1; }
         e += tail_spans;
-      } else
-      for (uint32_t i = 0; i < batch; ++i) {
+      }
+      for (uint32_t i = 0; i < batch && tail_spans == 0; ++i) {
         if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
         uint32_t *row = nullptr;
         unsigned long long *tslot = nullptr;
