@@ -95,7 +95,7 @@ typedef enum {
 
 /* Largest supported number of chunks N*chunks_per_npu (rooted collectives: chunks_per_npu).
  * A wavefront keeps a destination's whole "still needed" bitset in its share of the LDS and,
- * up to 98,304 chunks, a source's whole row in registers; beyond that the source rows are
+ * up to 122,880 chunks, a source's whole row in registers; beyond that the source rows are
  * streamed.  More than 65,536 chunks: link-centric matching, per-span launches only. */
 #define TACOS_MAX_CHUNKS 262144u
 /* Largest number of chunks for tacos_options_t::matching = 1 and for launch_mode 2. */

@@ -1417,7 +1417,7 @@ __global__ __launch_bounds__(256) void uniform_handover_kernel(PassDev p, Unifor
 // np <= kMaxStreamedPieces pieces; same results as match_destination.
 constexpr u32 kMaxStreamedPieces = 32;
 // (Rows of up to kMaxRegisterPieces pieces are matched with whole rows in registers: match_destination.)
-constexpr u32 kMaxRegisterPieces = 12;
+constexpr u32 kMaxRegisterPieces = 15;
 
 __device__ __forceinline__ u64 match_destination_streamed(const PassDev &p, u32 d, u32 jb, u32 je, u32 event,
                                                           u64 t, u32 *__restrict__ sched_row, int lane,
@@ -2457,14 +2457,18 @@ template <int MODE, int DEG> static void launch_match_mode(const PassDev &p, u32
     case 7: TACOS_MATCH(7); break;
     case 8: TACOS_MATCH(8); break;
     default:
-      // rows of 9..kMaxRegisterPieces pieces (up to 98,304 chunks), link-centric only: still whole
-      // rows in registers, at three wavefronts per SIMD
+      // rows of 9..kMaxRegisterPieces pieces (up to 122,880 chunks), link-centric only: still whole
+      // rows in registers, at two to four wavefronts per SIMD (16 pieces would need more than the
+      // 64 KiB of LDS a kernel may declare for its four need rows)
       if constexpr (MODE == 0 && DEG == 0) {
         switch (p.NP) {
           case 9: TACOS_MATCH(9); break;
           case 10: TACOS_MATCH(10); break;
           case 11: TACOS_MATCH(11); break;
           case 12: TACOS_MATCH(12); break;
+          case 13: TACOS_MATCH(13); break;
+          case 14: TACOS_MATCH(14); break;
+          case 15: TACOS_MATCH(15); break;
           default: break;  // rejected by the host before any launch
         }
       }

@@ -912,17 +912,20 @@ BIG_ROWS = [
     ("broadcast_c200001_25_pieces", lambda: T.random_regular_out(20, 3, seed=3)[0], 200_001, T.BROADCAST, dict(root=7, max_events=3000)),
     ("reduce_c65537_9_pieces", lambda: T.mesh2d(4, 3), 65_537, T.REDUCE, dict(root=5)),
     ("fc70_indeg69_c70000_9_pieces", lambda: T.fully_connected(70), 1000, T.ALL_GATHER, dict(link_order=1)),
-    # 10, 11, 12 pieces: the last row widths matched with whole rows in registers; 13: the first streamed one
+    # 10 to 15 pieces: the last row widths matched with whole rows in registers; 16: the first streamed one
     ("mesh3x3_c81000_10_pieces", lambda: T.mesh2d(3, 3), 9000, T.ALL_GATHER, {}),
     ("biring8_c88000_11_pieces_rs", lambda: T.ring(8, bidirectional=True), 11000, T.REDUCE_SCATTER, {}),
     ("fc12_c96000_12_pieces", lambda: T.fully_connected(12), 8000, T.ALL_GATHER, dict(link_order=1)),
     ("torus2x5_c100000_13_pieces", lambda: T.grid([2, 5], True), 10000, T.ALL_GATHER, {}),
+    ("mesh5x2_c110000_14_pieces", lambda: T.mesh2d(5, 2), 11000, T.ALL_GATHER, {}),
+    ("fc8_c120000_15_pieces_ar", lambda: T.fully_connected(8), 15000, T.ALL_REDUCE, {}),
+    ("biring6_c126000_16_pieces", lambda: T.ring(6, bidirectional=True), 21000, T.ALL_GATHER, {}),
 ]
 
 
 @pytest.mark.parametrize("name,mk,cpn,coll,kw", BIG_ROWS, ids=[c[0] for c in BIG_ROWS])
 def test_more_than_65536_chunks_streamed_rows(name, mk, cpn, coll, kw, stream):
-    """Rows of 9 to 32 one-KiB pieces: up to 12 pieces a source's whole row is still kept in
+    """Rows of 9 to 32 one-KiB pieces: up to 15 pieces a source's whole row is still kept in
     registers, beyond that the source rows are streamed.  Digest over all transfers, times,
     spans, the per-span trace (All-Gather), the first and the last 50,000 records."""
     topo = mk()
