@@ -233,6 +233,61 @@ def report_seed_search(binding, T, stream):
         print(f"[report] seed search on workload {idx} done", file=sys.stderr, flush=True)
 
 
+def report_modes(binding, T, stream):
+    """The launch forms against each other on shapes between the benchmark workloads: what the
+    automatic choice (launch_mode 0) picks and what the other forms would have cost.  Wall-clock
+    of one tacos_synthesize call (best of two), All-Gather unless named, 1 MiB chunks, seed 3."""
+    MiB = 1 << 20
+    h3 = ([300_000, 500_000, 1_000_000], [5_000, 10_000, 20_000])
+    h2 = ([300_000, 700_000], [5_000, 20_000])
+    ag = T.ALL_GATHER
+    cases = [
+        ("mesh8x8, 4 chunks per NPU", T.mesh2d(8, 8), 4, ag, {}),
+        ("mesh8x8, 32 chunks per NPU", T.mesh2d(8, 8), 32, ag, {}),
+        ("mesh16x16", T.mesh2d(16, 16), 1, ag, {}),
+        ("mesh16x16, 8 chunks per NPU", T.mesh2d(16, 16), 8, ag, {}),
+        ("mesh16x16, 8 chunks per NPU, matching 1", T.mesh2d(16, 16), 8, ag, dict(matching=1)),
+        ("heterogeneous mesh16x16, 8 chunks per NPU", T.grid([16, 16], False, *h2), 8, ag, {}),
+        ("heterogeneous torus4x4x8, 4 chunks per NPU, All-Reduce", T.workload(3).topo, 4, T.ALL_REDUCE, {}),
+        ("heterogeneous torus4x4x8, 16 chunks per NPU", T.workload(3).topo, 16, ag, {}),
+        ("torus8x8x8", T.torus3d(8, 8, 8), 1, ag, {}),
+        ("torus8x8x8, 3 chunks per NPU", T.torus3d(8, 8, 8), 3, ag, {}),
+        ("heterogeneous torus8x8x8", T.grid([8, 8, 8], True, *h3), 1, ag, {}),
+        ("unwound switch, 256 ports, degree 4, 4 chunks per NPU", T.switch_unwound(256, 4), 4, ag, {}),
+        ("random 256 NPUs, out-degree 4, every link its own cost, 4 chunks per NPU",
+         T.random_regular_out(256, 4, seed=3)[0], 4, ag, {}),
+        ("torus16x16x16", T.torus3d(16, 16, 16), 1, ag, {}),
+        ("torus64x64", T.grid([64, 64], True), 1, ag, {}),
+        ("mesh64x64", T.mesh2d(64, 64), 1, ag, {}),
+        ("torus32x32x16", T.torus3d(32, 32, 16), 1, ag, {}),
+        ("mesh128x128", T.mesh2d(128, 128), 1, ag, {}),
+        ("torus32x32x32", T.torus3d(32, 32, 32), 1, ag, {}),
+    ]
+    print("| topology | NPUs | links | chunks | TEN spans | matches per span | automatic (ms) | one workgroup, mode 2 (ms) | "
+          "one launch per span, mode 3 (ms) | two launches per span, mode 4 (ms) |")
+    print("|---|---|---|---|---|---|---|---|---|---|")
+    for name, t, cpn, coll, kw in cases:
+        cells, ev, nx = [], 0, 0
+        binding.tacos_synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B, cpn, MiB, coll, 3,
+                                 stream=stream, **kw).free()  # warm-up
+        for mode in (0, 2, 3, 4):
+            best = None
+            try:
+                for _ in range(2):
+                    t0 = time.perf_counter()
+                    r = binding.tacos_synthesize(t.n_npus, t.row_ptr, t.col_idx, t.alpha_ps, t.beta_fs_per_B, cpn, MiB,
+                                                 coll, 3, stream=stream, launch_mode=mode, **kw)
+                    dt = time.perf_counter() - t0
+                    ev, nx = r.num_events, r.num_xfers
+                    r.free()
+                    best = dt if best is None else min(best, dt)
+                cells.append(f"{best * 1e3:.2f}")
+            except binding.TacosError:
+                cells.append("does not apply")
+        print(f"| {name} | {t.n_npus} | {t.n_links} | {t.n_npus * cpn} | {ev} | {nx // max(1, ev)} | " + " | ".join(cells) + " |")
+        print(f"[report] {name} done", file=sys.stderr, flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -248,6 +303,9 @@ def main():
     ap.add_argument("--report-all", action="store_true",
                     help="instead of the one JSON line: a table over workloads 1..7 (GPU time, spans, "
                          "matches/s, fraction of the HBM roofline, oracle time on the host cores)")
+    ap.add_argument("--report-modes", action="store_true",
+                    help="instead of the one JSON line: the launch forms against each other on shapes between "
+                         "the benchmark workloads")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for HBM counters)")
     args = ap.parse_args()
@@ -264,6 +322,9 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream().cuda_stream
+    if args.report_modes:
+        report_modes(binding, T, stream)
+        return
     if args.report_all:
         report_all(binding, T, stream, not args.no_cpu_baseline)
         report_seed_search(binding, T, stream)
