@@ -124,7 +124,11 @@ typedef struct {
 /* Optional knobs; zero-initialise for the defaults. */
 typedef struct {
   void    *stream;        /* hipStream_t to launch on (NULL = the null stream).  The call
-                             returns after the work on it has completed.                    */
+                             returns after the work on it has completed.  An All-Reduce on
+                             up to about 16,000 NPUs sweeps its two passes at the same time:
+                             the All-Gather pass on a stream the library creates for the
+                             call, from a second host thread that has ended when the call
+                             returns (not with time_kernels).                               */
   uint64_t max_events;    /* 0 = run to completion; > 0 = stop each pass after that many
                              matching sweeps (the result then covers that prefix only and
                              collective_time is the time reached)                           */
