@@ -204,7 +204,10 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu,
  * seeds[*best] again for it.  When the topology fits the single-workgroup kernel
  * (launch_mode 2 of tacos_synthesize) every pass of every seed is one workgroup and all
  * of them sweep their spans concurrently, one CU each; otherwise (or with launch_mode 1)
- * the seeds run one after the other.  opts: stream, launch_mode, link_order, matching, root as
+ * the seeds are synthesized whole: up to about 16,000 NPUs several at a time, on streams the
+ * library creates for the call from host threads that have ended when it returns (such a
+ * synthesis leaves most of the GPU idle), beyond that one after the other on `stream`.
+ * opts: stream, launch_mode, link_order, matching, root as
  * for tacos_synthesize; max_events must be 0.  Errors as tacos_synthesize; on error the
  * outputs are unspecified.
  */

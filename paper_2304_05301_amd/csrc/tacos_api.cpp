@@ -8,12 +8,15 @@
 #include "tacos_internal.h"
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cstdio>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
+#include <system_error>
 #include <thread>
 #include <utility>
 #include <vector>
@@ -129,6 +132,9 @@ template <class T> void upload(DevBuf &b, const T *src, size_t n, hipStream_t s)
 // Largest size of the two held tables of the homogeneous-TEN path for which the automatic
 // launch mode chooses it.
 constexpr size_t kUniformAutoBytes = 256ull << 20;
+// Largest held table of a pass for which independent passes (the halves of an All-Reduce, the
+// seeds of a search) sweep at the same time on streams of their own.
+constexpr size_t kConcurrentPassBytes = 48ull << 20;
 
 // Schedule rows are stored in segments so that the number of spans need not be known
 // up front: segment k holds rows [k*rows_per_seg, (k+1)*rows_per_seg) and their times.
@@ -929,7 +935,6 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       // timing, which is to measure a kernel by itself.
       const uint32_t C_total = total_chunks(N, chunks_per_npu, root);
       const size_t held_bytes_pass = (size_t)N * ((C_total + 8191u) / 8192u) * 1024;
-      constexpr size_t kConcurrentPassBytes = 48ull << 20;
       if (coll == TACOS_ALL_REDUCE && !time_kernels && held_bytes_pass <= kConcurrentPassBytes &&
           (uint64_t)C_total * (N - 1) >= 4096) {
         res->passes.reserve(2);
@@ -985,6 +990,9 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
   } catch (const std::bad_alloc &) {
     g_last_error = "host allocation failed";
     return TACOS_E_NOMEM;
+  } catch (const std::system_error &e) {  // a host thread could not be started
+    g_last_error = std::string("host thread: ") + e.what();
+    return TACOS_E_DEVICE;
   }
   res->wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - wall0).count();
   *out = res.release();
@@ -1037,14 +1045,65 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
       return TACOS_E_INVAL;
     }
     if (!concurrent) {
-      // a topology this large fills the GPU by itself: one seed after the other
-      for (uint32_t i = 0; i < n_seeds; ++i) {
+      // Whole syntheses, each with its per-span launches.  Up to some ten thousand NPUs such a
+      // synthesis is bound by the latency of its launches and leaves most of the GPU idle:
+      // several host threads then take the seeds in turn, each on a stream of its own (8 seeds
+      // on a 64 x 64 mesh 121 -> 47 ms with four threads; an All-Reduce already sweeps its two
+      // passes at once and gets two).  A larger topology fills the GPU by itself: one seed after
+      // the other on the caller's stream.
+      auto one_seed = [&](uint32_t i, const tacos_options_t *o) {
         tacos_result_t *r = nullptr;
-        rc = tacos_synthesize(topo, chunks_per_npu, chunk_bytes, coll, seeds[i], opts, &r);
-        if (rc != TACOS_OK) return rc;
+        const int c = tacos_synthesize(topo, chunks_per_npu, chunk_bytes, coll, seeds[i], o, &r);
+        if (c != TACOS_OK) return c;
         time_ps[i] = r->collective_time;
         if (num_events) num_events[i] = r->n_events;
         tacos_result_free(r);
+        return (int)TACOS_OK;
+      };
+      const size_t held_bytes_pass = (size_t)N * NP * 1024;
+      const uint32_t n_threads = (held_bytes_pass <= kConcurrentPassBytes && (uint64_t)C * (N - 1) >= 4096)
+                                     ? std::min<uint32_t>(coll == TACOS_ALL_REDUCE ? 2u : 4u, n_seeds) : 1u;
+      if (n_threads <= 1) {
+        for (uint32_t i = 0; i < n_seeds; ++i) {
+          rc = one_seed(i, opts);
+          if (rc != TACOS_OK) return rc;
+        }
+      } else {
+        std::atomic<uint32_t> next{0};
+        std::atomic<int> first_rc{TACOS_OK};
+        std::mutex err_lock;
+        std::string err;
+        {
+          std::vector<std::unique_ptr<JoiningThread>> workers;
+          for (uint32_t w = 0; w < n_threads; ++w) {
+            workers.emplace_back(new JoiningThread([&] {
+              int c = TACOS_OK;
+              try {
+                HIP_TRY(hipSetDevice(device));
+                OwnedStream own;
+                tacos_options_t o{};
+                if (opts) o = *opts;
+                o.stream = own.s;
+                for (uint32_t i = next.fetch_add(1); i < n_seeds && first_rc.load() == TACOS_OK; i = next.fetch_add(1))
+                  if ((c = one_seed(i, &o)) != TACOS_OK) break;
+              } catch (const HipFail &f) {
+                c = f.code;
+              } catch (const std::bad_alloc &) {
+                g_last_error = "host allocation failed";
+                c = TACOS_E_NOMEM;
+              }
+              if (c != TACOS_OK) {
+                std::lock_guard<std::mutex> hold(err_lock);
+                int expected = TACOS_OK;
+                if (first_rc.compare_exchange_strong(expected, c)) err = g_last_error;
+              }
+            }));
+          }
+        }  // joined
+        if (first_rc.load() != TACOS_OK) {
+          g_last_error = err;
+          return first_rc.load();
+        }
       }
       pick_best();
       return TACOS_OK;
@@ -1128,6 +1187,9 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
   } catch (const std::bad_alloc &) {
     g_last_error = "host allocation failed";
     return TACOS_E_NOMEM;
+  } catch (const std::system_error &e) {  // a host thread could not be started
+    g_last_error = std::string("host thread: ") + e.what();
+    return TACOS_E_DEVICE;
   }
   pick_best();
   return TACOS_OK;

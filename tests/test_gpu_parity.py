@@ -812,6 +812,39 @@ def test_seed_search_errors_and_degenerate_inputs(stream):
     assert e.value.code == binding.TACOS_E_UNREACHABLE
 
 
+@pytest.mark.parametrize("coll", [T.ALL_GATHER, T.ALL_REDUCE, T.BROADCAST])
+def test_seed_search_beyond_one_workgroup_runs_seeds_on_several_streams(coll, stream):
+    """Per-span launches (here forced with launch_mode 1; a topology too large for the single-
+    workgroup kernel takes them by itself) on a topology small enough to leave the GPU mostly
+    idle: the seeds are synthesized whole, several at a time on streams of the library's own
+    from several host threads (an All-Reduce additionally sweeps its two passes at once).  Times
+    and span counts of the oracle for every seed, and of a single synthesis with each seed; an
+    unreachable NPU is reported from whichever thread finds it."""
+    topo = T.grid([24, 24], False, [300_000, 700_000], [5_000, 20_000])
+    seeds = np.array([11, 12, 13, 14, 15, 16, 17], dtype=np.uint64)
+    kw = dict(root=77) if coll == T.BROADCAST else {}
+    cpn = 600 if coll == T.BROADCAST else 1
+    want_t, want_e = oracle_times(topo, cpn, MiB, coll, seeds, n_threads=min(16, oracle.max_threads()), **kw)
+    times, events, best = search(topo, cpn, MiB, coll, seeds, stream, launch_mode=1, **kw)
+    assert np.array_equal(times, want_t) and np.array_equal(events, want_e)
+    assert best == int(np.argmin(want_t))
+    for i in (0, 6):
+        with gpu(topo, cpn, MiB, coll, int(seeds[i]), stream, **kw) as r:
+            assert r.collective_time_ps == int(times[i]) and r.num_events == int(events[i])
+    big = T.mesh2d(58, 58)  # beyond the single-workgroup kernel: the same path in automatic mode
+    times, events, best = search(big, 1, MiB, coll if coll != T.BROADCAST else T.ALL_GATHER, seeds[:5], stream)
+    for i in (1, 4):
+        with gpu(big, 1, MiB, coll if coll != T.BROADCAST else T.ALL_GATHER, int(seeds[i]), stream) as r:
+            assert r.collective_time_ps == int(times[i]) and r.num_events == int(events[i])
+    src = np.repeat(np.arange(topo.n_npus), np.diff(topo.row_ptr))
+    edges = [(int(a), int(b), int(al), int(be)) for a, b, al, be in zip(src, topo.col_idx, topo.alpha_ps, topo.beta_fs_per_B)]
+    broken = T.from_edge_list(topo.n_npus + 1, edges + [(topo.n_npus, 0, 500_000, 10_000)])  # the new NPU never receives
+    if coll != T.BROADCAST:
+        with pytest.raises(binding.TacosError) as e:
+            search(broken, 1, MiB, coll, seeds, stream, launch_mode=1)
+        assert e.value.code == binding.TACOS_E_UNREACHABLE
+
+
 def test_best_of_seeds_returns_the_winning_schedule(stream):
     w = T.workload(3)
     seeds = np.arange(50, 90, dtype=np.uint64)
