@@ -347,6 +347,16 @@ PassDev make_pass_dev(const PassGraph &g, const DevBuf &d_cost, uint32_t cpn, ui
   return p;
 }
 
+// Nearly every link with a cost of its own: spans then sit on about as many times as there are
+// transfers, about one transfer per span.
+bool nearly_all_costs_differ(const std::vector<uint64_t> &cost)
+{
+  std::vector<uint64_t> sorted(cost);
+  std::sort(sorted.begin(), sorted.end());
+  const size_t distinct = (size_t)(std::unique(sorted.begin(), sorted.end()) - sorted.begin());
+  return distinct >= 64 && distinct * 4 >= cost.size();
+}
+
 // Whether the single-workgroup kernel can take this shape on the current device.
 bool fits_small_kernel(uint32_t N, uint32_t L, uint32_t NP)
 {
@@ -411,8 +421,8 @@ int run_pass(uint32_t N, uint32_t L, const std::vector<uint32_t> &psrc, const st
   const size_t held_bytes = (size_t)N * row_words * 8;
   const bool can_uniform = !small && uniform_cost != 0 && uniform_cost <= (1ull << 31) && NP <= 8 && match_mode == 0 &&
                            max_events == 0;
-  // Chosen automatically while both tables fit the 256 MiB Infinity Cache: then it is 1.15x
-  // (32,768 NPUs) to 2.2x (4,096 NPUs) faster than two launches per span; beyond that the
+  // Chosen automatically while both tables fit the 256 MiB Infinity Cache: then it is 1.1x
+  // (32,768 NPUs) to 1.6x (4,096 NPUs) faster than two launches per span; beyond that the
   // second table's traffic costs more than the saved launch (40,960 NPUs: 13 % slower).
   const bool uniform = can_uniform && (launch_mode == 3 || (launch_mode == 0 && 2 * held_bytes <= kUniformAutoBytes));
   if (launch_mode == 3 && !uniform) {
@@ -909,14 +919,7 @@ int tacos_synthesize(const tacos_topology_t *topo, uint32_t chunks_per_npu, uint
       uint64_t uniform_cost = host_cost[0];
       for (uint32_t l = 1; l < L && uniform_cost; ++l)
         if (host_cost[l] != host_cost[0]) uniform_cost = 0;
-      // nearly every link with a cost of its own: spans then sit on about as many times as there are transfers
-      bool many_costs = false;
-      if (!uniform_cost) {
-        std::vector<uint64_t> sorted(host_cost);
-        std::sort(sorted.begin(), sorted.end());
-        const size_t distinct = (size_t)(std::unique(sorted.begin(), sorted.end()) - sorted.begin());
-        many_costs = distinct >= 64 && distinct * 4 >= (size_t)L;
-      }
+      const bool many_costs = !uniform_cost && nearly_all_costs_differ(host_cost);
       // reversed pass: every link (s -> d) is used as (d -> s), ids and costs unchanged
       auto run_one = [&](bool rev, hipStream_t st, Pass &ps) {
         return run_pass(N, L, rev ? res->link_dst : res->link_src, rev ? res->link_src : res->link_dst, d_cost,
@@ -1115,9 +1118,10 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
     DevBuf d_cost;
     std::vector<uint64_t> host_cost;
     const bool by_cost = opts && opts->link_order == TACOS_LINK_ORDER_COST;
-    rc = device_costs(topo, chunk_bytes, stream, d_cost, by_cost ? &host_cost : nullptr);
+    rc = device_costs(topo, chunk_bytes, stream, d_cost, &host_cost);
     if (rc != TACOS_OK) return rc;
     const std::vector<uint64_t> *order_cost = by_cost ? &host_cost : nullptr;
+    const bool sparse = nearly_all_costs_differ(host_cost);  // as tacos_synthesize: one destination per wavefront
     const bool want_rev = has_reversed_pass((int)coll), want_fwd = has_forward_pass((int)coll);
     PassGraph g_rev, g_fwd;
     if (want_rev) build_pass_graph(N, L, link_dst, link_src, order_cost, stream, g_rev);
@@ -1159,7 +1163,7 @@ int tacos_seed_search(const tacos_topology_t *topo, uint32_t chunks_per_npu, uin
         if (e >= 0xFFFFFFFEull) { g_last_error = "more than 2^32-2 spans"; return TACOS_E_OVERFLOW; }
         const uint32_t n = (uint32_t)std::min<uint64_t>(kSearchSpansPerLaunch, 0xFFFFFFFEull - e);
         HIP_TRY(tacos::launch_small_sweep_batch(d_jobs.as<tacos::SmallJob>(), n_jobs, jobs[0].p, (uint32_t)e, n,
-                                                match_mode, stream));
+                                                match_mode, sparse, stream));
         HIP_TRY(hipMemcpyAsync(host_ctl.p, d_ctl.p, (size_t)n_jobs * sizeof(Ctl), hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
         e += n;

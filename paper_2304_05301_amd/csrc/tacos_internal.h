@@ -194,14 +194,16 @@ hipError_t launch_small_sweep(const PassDev &p, const uint32_t *out_ptr, const u
 bool small_sweep_by_lane(uint32_t N, uint32_t L, uint32_t NP, uint32_t C, uint32_t mode);
 // The same sweep for n_jobs independent passes of one shape at once, one workgroup each
 // (jobs: device array); collective times only, no schedule rows.  p0: any of the jobs'
-// PassDev (shape).  Every unfinished job advances by n_events spans from first_event.
+// PassDev (shape).  Every unfinished job advances by n_events spans from first_event.  sparse: as
+// launch_small_sweep.
 struct SmallJob {
   PassDev p;
   const uint32_t *out_ptr;
   const uint32_t *out_dst;
 };
 hipError_t launch_small_sweep_batch(const SmallJob *jobs, uint32_t n_jobs, const PassDev &p0,
-                                    uint32_t first_event, uint32_t n_events, uint32_t mode, hipStream_t s);
+                                    uint32_t first_event, uint32_t n_events, uint32_t mode, bool sparse,
+                                    hipStream_t s);
 // LDS the small-topology kernel needs, (size_t)-1 if the shape is not supported
 size_t small_sweep_lds_bytes(uint32_t N, uint32_t L, uint32_t NP);
 // epilogue: per-row match counts and the schedule digest of a block of rows; `digest` points at

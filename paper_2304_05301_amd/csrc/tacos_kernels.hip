@@ -2675,14 +2675,14 @@ static hipError_t launch_batch_variant(const SmallJob *jobs, u32 n_jobs, u32 fir
 
 template <int NP, int MODE>
 static hipError_t launch_batch_np(const SmallJob *jobs, u32 n_jobs, const PassDev &p0, u32 first_event,
-                                  u32 n_events, hipStream_t s)
+                                  u32 n_events, bool sparse, hipStream_t s)
 {
   u32 dst_in_lds = 0, held_lanes = 0, rec_in_lds = 0;
   const size_t lds = small_launch_lds(p0, &dst_in_lds, &held_lanes, &rec_in_lds);
 #define TACOS_VARIANT(H_, T_) \
   return launch_batch_variant<NP, MODE, H_, T_>(jobs, n_jobs, first_event, n_events, lds, dst_in_lds, held_lanes, rec_in_lds, s)
   if constexpr (NP == 1 && MODE == 0) {
-    switch (tiny_words<NP, MODE>(held_lanes, rec_in_lds)) {
+    switch (sparse ? 0 : tiny_words<NP, MODE>(held_lanes, rec_in_lds)) {
       case 2: TACOS_VARIANT(true, 2);
       case 4: TACOS_VARIANT(true, 4);
       case 8: TACOS_VARIANT(true, 8);
@@ -2715,9 +2715,9 @@ hipError_t launch_small_sweep(const PassDev &p, const u32 *out_ptr, const u32 *o
 }
 
 hipError_t launch_small_sweep_batch(const SmallJob *jobs, u32 n_jobs, const PassDev &p0, u32 first_event,
-                                    u32 n_events, u32 mode, hipStream_t s)
+                                    u32 n_events, u32 mode, bool sparse, hipStream_t s)
 {
-#define TACOS_BATCH(NP_, M_) return launch_batch_np<NP_, M_>(jobs, n_jobs, p0, first_event, n_events, s)
+#define TACOS_BATCH(NP_, M_) return launch_batch_np<NP_, M_>(jobs, n_jobs, p0, first_event, n_events, sparse, s)
   if (mode > 2 || n_jobs == 0) return hipErrorInvalidValue;
   switch (p0.NP * 4 + mode) {
     case 4: TACOS_BATCH(1, 0);
